@@ -1,0 +1,169 @@
+/*
+ * kvc.h -- C ABI of the MI355X (gfx950) KV-cache compress / decompress library.
+ *
+ * The library implements the quantizer Q and codec C stages of the KVServe compression
+ * pipeline BS = C(Q(T(X))) (paper section 5.1) and their inverses, as they run at the
+ * two ends of a KV movement (section 4: Prefill -> Compression -> Communication ->
+ * Decompression -> Decode).  A *strategy* (section 5.1: the choice of modules and their
+ * parameters) is fixed for a whole request (section 3.1) and applied to that request's
+ * K and V tensors; the result is one self-contained payload whose byte size V_p defines
+ * the compression ratio cr = V / V_p (section 3.1).
+ *
+ * Conventions, for every entry point:
+ *  - plain C types only; pointers are HOST pointers unless the comment says DEVICE;
+ *  - the caller owns every buffer; the library allocates no device memory and, apart from
+ *    launching kernels on the caller's stream, performs no device synchronisation;
+ *  - all device pointers must be 16-byte aligned; strides are in elements (2 bytes);
+ *  - errors the host can see are returned (negative kvc_status) before anything is
+ *    launched; errors only the device can see (bad block-table entry, corrupt payload)
+ *    are written to the caller's status words and never cause out-of-bounds accesses;
+ *  - head_dim must be 128 (the kernels map 16 lanes x 8 channels onto one token row);
+ *  - inputs must be finite; +0 and -0 are both reconstructed as +0.
+ */
+#ifndef KVC_H
+#define KVC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KVC_OK = 0,
+    KVC_ERR_ARG = -1,          /* null pointer, misalignment, non-positive size, bad enum    */
+    KVC_ERR_UNSUPPORTED = -2,  /* valid in the format but not built (head_dim != 128, ...)   */
+    KVC_ERR_CAPACITY = -3,     /* payload / workspace / plan limit too small                 */
+    KVC_ERR_FORMAT = -4,       /* payload header is not a KVC1 header or is inconsistent      */
+    KVC_ERR_MISMATCH = -5,     /* payload does not belong to this plan                        */
+    KVC_ERR_DEVICE = -6        /* a HIP call failed                                           */
+} kvc_status;
+
+/* device-side status bits (OR-ed into the caller's int32 status word of a request) */
+enum {
+    KVC_DEV_BAD_BLOCK = 1,     /* block-table entry outside [0, num_phys_blocks)              */
+    KVC_DEV_BAD_HEADER = 2,    /* payload header does not match the plan / request            */
+    KVC_DEV_BAD_CHUNK = 4,     /* coder directory or chunk body inconsistent                  */
+    KVC_DEV_BAD_TABLE = 8,     /* code-length table is not a complete prefix code             */
+    KVC_DEV_SCAN_TIMEOUT = 16  /* internal: chunk-offset scan gave up waiting                 */
+};
+
+enum { KVC_F16 = 1, KVC_BF16 = 2 };
+enum { KVC_CODEC_NONE = 0, KVC_CODEC_HUFF8 = 1 };
+
+/*
+ * The knobs a controller selects (section 5.1, "Quantizer": bit width, granularity and
+ * mixed precision; "Codec"; section 7.1: KIVI = asymmetric 2-bit).
+ *   bits_k / bits_v : 2, 3, 4, 8, or 16 (16 = the tensor travels unchanged: the bypass case)
+ *   group_k         : tokens per K group (K is quantized per channel): 32, 64 or 128
+ *   group_v         : channels per V group (V is quantized per token): 32, 64 or 128
+ *   codec           : lossless stage over the packed code bytes (needs bits < 16)
+ *   transform       : stage T; only 0 (none) is built
+ *   head_bits_k/v   : reserved for per-head bit widths (MixHQ); must be NULL
+ * Every group carries two fp16 values (scale, zero): the 32 bits per group that cap
+ * 2-bit / group-32 at 16/(2+1) = 5.33x (section 7.3).
+ */
+typedef struct {
+    uint8_t bits_k, bits_v;
+    uint16_t group_k, group_v;
+    uint8_t codec, transform;
+    const uint8_t *head_bits_k, *head_bits_v;
+} kvc_strategy;
+
+typedef struct {
+    uint8_t dtype;                       /* KVC_F16 or KVC_BF16 (input and output type)      */
+    int32_t layers, kv_heads, head_dim;
+} kvc_model;
+
+/*
+ * One request's KV in device memory.  Element (l, h, t, d) of K lives at
+ *   k + l*stride_layer + h*stride_head + tok(t) + d
+ *   tok(t) = t*stride_token                                         when block_table == NULL
+ *          = block_table[t / block_tokens]*stride_block
+ *            + (t % block_tokens)*stride_token                      otherwise (paged)
+ * and likewise for V from v.  A contiguous [layer][kv][head][token][dim] cache is
+ *   v = k + heads*tokens*dim, stride_layer = 2*heads*tokens*dim, stride_head = tokens*dim,
+ *   stride_token = dim;
+ * a vLLM-style pool [layer][kv][phys_block][block_tokens][head][dim] is
+ *   stride_head = dim, stride_token = heads*dim, stride_block = block_tokens*heads*dim.
+ * block_table (DEVICE, ceil(tokens/block_tokens) int32 entries) is shared by all layers;
+ * block_tokens must be a power of two.  For kvc_decompress the same struct names the
+ * destination (k, v are written), which may use a different block table than the sender.
+ */
+typedef struct {
+    void *k, *v;                         /* DEVICE */
+    int64_t tokens;
+    int64_t stride_layer, stride_head, stride_token, stride_block;
+    const int32_t *block_table;          /* DEVICE or NULL */
+    int32_t block_tokens, num_phys_blocks;
+} kvc_request;
+
+typedef struct kvc_plan_s kvc_plan_t;      /* opaque, host memory */
+
+/*
+ * Validate a (model, strategy) pair and fix the limits the workspace is sized for.
+ * Returns KVC_OK and a plan in *out (release with kvc_plan_free), or an error and
+ * *out = NULL.  Touches no device.
+ */
+int kvc_plan(const kvc_model *model, const kvc_strategy *strategy, int64_t max_tokens,
+             int32_t max_batch, kvc_plan_t **out);
+void kvc_plan_free(kvc_plan_t *plan);
+
+/*
+ * Payload bytes of a request of `tokens` tokens: V_p of section 3.1.  Without the codec
+ * the value is exact (*is_exact = 1):
+ *   128 + a16(4*L*H*ceil(T/group_k)*D) + a16(4*L*H*T*D/group_v)
+ *       + a16(L*H*T*D*bits_k/8) + a16(L*H*T*D*bits_v/8),      a16 = round up to 16;
+ * with it, the value is the capacity the caller must provide (every chunk stored raw,
+ * plus tables and directory) and the true size is reported by kvc_compress.
+ */
+int kvc_payload_size(const kvc_plan_t *plan, int64_t tokens, uint64_t *bytes, int *is_exact);
+
+/* Bytes of DEVICE scratch kvc_compress / kvc_decompress need (may be 0). */
+size_t kvc_workspace_size(const kvc_plan_t *plan);
+
+/*
+ * Compress n requests (n <= max_batch, each tokens <= max_tokens) with the plan's strategy.
+ *   payload      DEVICE buffer; request i's payload starts at payload + payload_off[i]
+ *   payload_off  HOST, n+1 ascending multiples of 16; payload_off[i+1]-payload_off[i] must
+ *                be >= kvc_payload_size(tokens_i)
+ *   out_bytes    DEVICE, n x uint64: the true payload size of each request
+ *   dev_status   DEVICE, n x int32: KVC_DEV_* bits (zeroed by the call, then OR-ed)
+ *   workspace    DEVICE, kvc_workspace_size bytes (may be NULL when that is 0)
+ *   hip_stream   hipStream_t the kernels are enqueued on (NULL = default stream)
+ * Each payload is independent of the others in the batch (the profile is fixed per
+ * request, section 3.1) and identical to compressing that request alone.
+ */
+int kvc_compress(const kvc_plan_t *plan, const kvc_request *reqs, int32_t n, void *payload,
+                 const uint64_t *payload_off, uint64_t *out_bytes, int32_t *dev_status,
+                 void *workspace, void *hip_stream);
+
+/*
+ * Inverse: rebuild K and V of n requests into dst[i] (layout may differ from the sender's).
+ * dst[i].tokens must equal the payload's token count; the device checks each header against
+ * the plan and sets KVC_DEV_BAD_HEADER (writing nothing for that request) on a mismatch.
+ * Reconstruction: x^ = round(code*scale + zero) in the model dtype.
+ */
+int kvc_decompress(const kvc_plan_t *plan, const void *payload, const uint64_t *payload_off,
+                   const kvc_request *dst, int32_t n, int32_t *dev_status, void *workspace,
+                   void *hip_stream);
+
+/*
+ * Decode a 128-byte payload header held in HOST memory.  sections[10] receives five
+ * (offset, bytes) pairs: K meta, V meta, coder tables+directory, K codes, V codes.
+ * Any output pointer may be NULL.  Returns KVC_ERR_FORMAT for a bad magic, version or
+ * field combination.
+ */
+int kvc_payload_inspect(const void *header128, kvc_model *model, kvc_strategy *strategy,
+                        int64_t *tokens, uint64_t *total_bytes, uint64_t *sections);
+
+/* Host-side check of a block table held in HOST memory (every entry in range). */
+int kvc_check_block_table(const int32_t *table, int64_t entries, int32_t num_phys_blocks);
+
+const char *kvc_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,414 @@
+// Host side of the C ABI (include/kvc.h): plan validation, payload geometry and header,
+// and the launch sequences of kvc_compress / kvc_decompress.  No device allocation, no
+// synchronisation; everything is enqueued on the caller's stream.
+
+#include <stdlib.h>
+#include <string.h>
+
+#include "../../include/kvc.h"
+#include "kvc_internal.h"
+
+using namespace kvc;
+
+struct kvc_plan_s {
+    kvc_model model;
+    kvc_strategy strat;
+    int64_t max_tokens;
+    int32_t max_batch;
+    size_t ws_request;          // workspace bytes per request
+    size_t ws_state_off;        // offset of the scan state inside a request's workspace
+};
+
+static inline long long a16(long long n) { return (n + 15) & ~15ll; }
+static inline size_t a256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+static bool bits_ok(int b) { return b == 2 || b == 3 || b == 4 || b == 8 || b == 16; }
+static bool group_ok(int g) { return g == 32 || g == 64 || g == 128; }
+
+static long long chunks_per_head(long long tokens) { return (tokens + kChunkRows - 1) / kChunkRows; }
+
+// Payload = header | K meta | V meta | coder tables + directory | K codes | V codes, each
+// part on a 16-byte boundary; two fp16 values of metadata per group (section 7.3).
+static void geometry(const kvc_plan_t *p, long long T, Geometry *g)
+{
+    const long long LH = (long long)p->model.layers * p->model.kv_heads, D = p->model.head_dim;
+    const int bk = p->strat.bits_k, bv = p->strat.bits_v;
+    g->meta_k = bk == 16 ? 0 : 4 * LH * ((T + p->strat.group_k - 1) / p->strat.group_k) * D;
+    g->meta_v = bv == 16 ? 0 : 4 * LH * T * (D / p->strat.group_v);
+    g->codes_k = LH * T * D * bk / 8;
+    g->codes_v = LH * T * D * bv / 8;
+    g->chunks_k = g->chunks_v = LH * chunks_per_head(T);
+    g->aux = p->strat.codec ? 512 + 4 * (g->chunks_k + g->chunks_v + 1) : 0;
+    g->off_meta_k = kHeader;
+    g->off_meta_v = g->off_meta_k + a16(g->meta_k);
+    g->off_aux = g->off_meta_v + a16(g->meta_v);
+    g->off_codes_k = g->off_aux + a16(g->aux);
+    g->off_codes_v = g->off_codes_k + a16(g->codes_k);
+    g->total = g->off_codes_v + a16(g->codes_v);
+}
+
+static void put16(uint8_t *p, unsigned v) { p[0] = (uint8_t)v; p[1] = (uint8_t)(v >> 8); }
+static void put32(uint8_t *p, uint32_t v) { for (int i = 0; i < 4; ++i) p[i] = (uint8_t)(v >> (8 * i)); }
+static void put64(uint8_t *p, uint64_t v) { for (int i = 0; i < 8; ++i) p[i] = (uint8_t)(v >> (8 * i)); }
+static unsigned get16(const uint8_t *p) { return p[0] | (p[1] << 8); }
+static uint32_t get32(const uint8_t *p) { uint32_t v = 0; for (int i = 0; i < 4; ++i) v |= (uint32_t)p[i] << (8 * i); return v; }
+static uint64_t get64(const uint8_t *p) { uint64_t v = 0; for (int i = 0; i < 8; ++i) v |= (uint64_t)p[i] << (8 * i); return v; }
+
+// 128-byte little-endian header.  With the coder, the four size-dependent fields (total,
+// K code bytes, V code offset, V code bytes) are left zero here and patched on the device.
+static void make_header(const kvc_plan_t *p, long long T, const Geometry &g, HeaderBytes *out)
+{
+    uint8_t h[kHeader];
+    memset(h, 0, sizeof h);
+    memcpy(h, "KVC1", 4);
+    put16(h + 4, 1);
+    h[6] = p->model.dtype;
+    h[7] = p->strat.codec;
+    put32(h + 8, (uint32_t)p->model.layers);
+    put32(h + 12, (uint32_t)p->model.kv_heads);
+    put32(h + 16, (uint32_t)p->model.head_dim);
+    h[20] = p->strat.bits_k;
+    h[21] = p->strat.bits_v;
+    put16(h + 22, p->strat.group_k);
+    put16(h + 24, p->strat.group_v);
+    put64(h + 32, (uint64_t)T);
+    put64(h + 48, (uint64_t)g.off_meta_k); put64(h + 56, (uint64_t)g.meta_k);
+    put64(h + 64, (uint64_t)g.off_meta_v); put64(h + 72, (uint64_t)g.meta_v);
+    put64(h + 80, (uint64_t)g.off_aux);    put64(h + 88, (uint64_t)g.aux);
+    put64(h + 96, (uint64_t)g.off_codes_k);
+    if (!p->strat.codec) {
+        put64(h + 40, (uint64_t)g.total);
+        put64(h + 104, (uint64_t)g.codes_k);
+        put64(h + 112, (uint64_t)g.off_codes_v);
+        put64(h + 120, (uint64_t)g.codes_v);
+    }
+    memcpy(out->w, h, kHeader);
+}
+
+extern "C" const char *kvc_status_string(int s)
+{
+    switch (s) {
+    case KVC_OK: return "ok";
+    case KVC_ERR_ARG: return "invalid argument";
+    case KVC_ERR_UNSUPPORTED: return "unsupported configuration";
+    case KVC_ERR_CAPACITY: return "capacity too small";
+    case KVC_ERR_FORMAT: return "malformed payload";
+    case KVC_ERR_MISMATCH: return "payload does not match plan";
+    case KVC_ERR_DEVICE: return "HIP error";
+    }
+    return "unknown status";
+}
+
+static int check_pair(const kvc_model *m, const kvc_strategy *s)
+{
+    if (!m || !s) return KVC_ERR_ARG;
+    if (m->dtype != KVC_F16 && m->dtype != KVC_BF16) return KVC_ERR_ARG;
+    if (m->layers < 1 || m->kv_heads < 1 || m->head_dim < 1) return KVC_ERR_ARG;
+    if (!bits_ok(s->bits_k) || !bits_ok(s->bits_v)) return KVC_ERR_ARG;
+    if (s->codec != KVC_CODEC_NONE && s->codec != KVC_CODEC_HUFF8) return KVC_ERR_ARG;
+    if (s->bits_k != 16 && !group_ok(s->group_k)) return KVC_ERR_ARG;
+    if (s->bits_v != 16 && !group_ok(s->group_v)) return KVC_ERR_ARG;
+    if (m->head_dim != kDim) return KVC_ERR_UNSUPPORTED;
+    if (s->transform != 0 || s->head_bits_k || s->head_bits_v) return KVC_ERR_UNSUPPORTED;
+    if (s->codec && (s->bits_k == 16 || s->bits_v == 16)) return KVC_ERR_UNSUPPORTED;
+    return KVC_OK;
+}
+
+extern "C" int kvc_plan(const kvc_model *model, const kvc_strategy *strategy, int64_t max_tokens,
+                        int32_t max_batch, kvc_plan_t **out)
+{
+    if (!out) return KVC_ERR_ARG;
+    *out = nullptr;
+    int rc = check_pair(model, strategy);
+    if (rc) return rc;
+    if (max_tokens < 0 || max_batch < 1) return KVC_ERR_ARG;
+    kvc_plan_t *p = (kvc_plan_t *)calloc(1, sizeof(kvc_plan_t));
+    if (!p) return KVC_ERR_ARG;
+    p->model = *model;
+    p->strat = *strategy;
+    if (p->strat.bits_k == 16) p->strat.group_k = 32;       // unused; keep the header canonical
+    if (p->strat.bits_v == 16) p->strat.group_v = 32;
+    p->max_tokens = max_tokens;
+    p->max_batch = max_batch;
+    if (strategy->codec) {
+        // histograms, encode tables, decode tables, ticket, then the scan state
+        const long long chunks = (long long)model->layers * model->kv_heads * chunks_per_head(max_tokens);
+        const long long wgs = 2 * ((chunks + 3) / 4);
+        p->ws_state_off = a256(2 * 256 * 4) + a256(2 * 256 * 4) + a256(2 * 4096 * 2) + 256;
+        p->ws_request = p->ws_state_off + a256((size_t)wgs * 8 + 8);
+    }
+    *out = p;
+    return KVC_OK;
+}
+
+extern "C" void kvc_plan_free(kvc_plan_t *plan) { free(plan); }
+
+extern "C" int kvc_payload_size(const kvc_plan_t *plan, int64_t tokens, uint64_t *bytes, int *is_exact)
+{
+    if (!plan || !bytes || tokens < 0) return KVC_ERR_ARG;
+    Geometry g;
+    geometry(plan, tokens, &g);
+    *bytes = (uint64_t)g.total;
+    if (is_exact) *is_exact = plan->strat.codec == 0;
+    return KVC_OK;
+}
+
+extern "C" size_t kvc_workspace_size(const kvc_plan_t *plan)
+{
+    return plan ? plan->ws_request * (size_t)plan->max_batch : 0;
+}
+
+extern "C" int kvc_payload_inspect(const void *header128, kvc_model *model, kvc_strategy *strategy,
+                                   int64_t *tokens, uint64_t *total_bytes, uint64_t *sections)
+{
+    const uint8_t *h = (const uint8_t *)header128;
+    if (!h) return KVC_ERR_ARG;
+    if (memcmp(h, "KVC1", 4) != 0 || get16(h + 4) != 1) return KVC_ERR_FORMAT;
+    kvc_model m;
+    kvc_strategy s;
+    memset(&m, 0, sizeof m);
+    memset(&s, 0, sizeof s);
+    m.dtype = h[6];
+    s.codec = h[7];
+    m.layers = (int32_t)get32(h + 8);
+    m.kv_heads = (int32_t)get32(h + 12);
+    m.head_dim = (int32_t)get32(h + 16);
+    s.bits_k = h[20];
+    s.bits_v = h[21];
+    s.group_k = (uint16_t)get16(h + 22);
+    s.group_v = (uint16_t)get16(h + 24);
+    const int64_t T = (int64_t)get64(h + 32);
+    int rc = check_pair(&m, &s);
+    if (rc == KVC_ERR_ARG || T < 0) return KVC_ERR_FORMAT;
+    for (int i = 26; i < 32; ++i)
+        if (h[i]) return KVC_ERR_FORMAT;
+    // the fixed part of the section table must be the closed form of the fields above
+    kvc_plan_t tmp;
+    memset(&tmp, 0, sizeof tmp);
+    tmp.model = m;
+    tmp.strat = s;
+    Geometry g;
+    geometry(&tmp, T, &g);
+    const uint64_t want[7] = {(uint64_t)g.off_meta_k, (uint64_t)g.meta_k, (uint64_t)g.off_meta_v,
+                              (uint64_t)g.meta_v, (uint64_t)g.off_aux, (uint64_t)g.aux,
+                              (uint64_t)g.off_codes_k};
+    for (int i = 0; i < 7; ++i)
+        if (get64(h + 48 + 8 * i) != want[i]) return KVC_ERR_FORMAT;
+    const uint64_t total = get64(h + 40), ck = get64(h + 104), ov = get64(h + 112), cv = get64(h + 120);
+    if (!s.codec) {
+        if (total != (uint64_t)g.total || ck != (uint64_t)g.codes_k || ov != (uint64_t)g.off_codes_v ||
+            cv != (uint64_t)g.codes_v)
+            return KVC_ERR_FORMAT;
+    } else {
+        if (ov != (uint64_t)g.off_codes_k + ck || total != ov + cv || total > (uint64_t)g.total ||
+            (ck & 15) || (cv & 15))
+            return KVC_ERR_FORMAT;
+    }
+    if (model) *model = m;
+    if (strategy) *strategy = s;
+    if (tokens) *tokens = T;
+    if (total_bytes) *total_bytes = total;
+    if (sections) {
+        for (int i = 0; i < 7; ++i) sections[i] = want[i];
+        sections[7] = ck; sections[8] = ov; sections[9] = cv;
+    }
+    return rc;     // KVC_OK, or KVC_ERR_UNSUPPORTED for a well-formed header this build cannot run
+}
+
+extern "C" int kvc_check_block_table(const int32_t *table, int64_t entries, int32_t num_phys_blocks)
+{
+    if (!table || entries < 0 || num_phys_blocks < 1) return KVC_ERR_ARG;
+    for (int64_t i = 0; i < entries; ++i)
+        if (table[i] < 0 || table[i] >= num_phys_blocks) return KVC_ERR_ARG;
+    return KVC_OK;
+}
+
+static bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+static int check_request(const kvc_plan_t *p, const kvc_request *r)
+{
+    if (r->tokens < 0) return KVC_ERR_ARG;
+    if (r->tokens > p->max_tokens) return KVC_ERR_CAPACITY;
+    if (r->tokens == 0) return KVC_OK;
+    if (!r->k || !r->v || !aligned16(r->k) || !aligned16(r->v)) return KVC_ERR_ARG;
+    if ((r->stride_layer | r->stride_head | r->stride_token) & 7) return KVC_ERR_ARG;
+    if (r->stride_token < kDim) return KVC_ERR_ARG;
+    if (r->block_table) {
+        if (r->block_tokens < 1 || (r->block_tokens & (r->block_tokens - 1))) return KVC_ERR_UNSUPPORTED;
+        if (r->num_phys_blocks < 1 || (r->stride_block & 7) || r->stride_block < 1) return KVC_ERR_ARG;
+        if (((uintptr_t)r->block_table & 3)) return KVC_ERR_ARG;
+    }
+    return KVC_OK;
+}
+
+static TensorView view_of(const kvc_request *r, int is_v)
+{
+    TensorView v;
+    v.base = (uint16_t *)(is_v ? r->v : r->k);
+    v.stride_layer = r->stride_layer;
+    v.stride_head = r->stride_head;
+    v.stride_token = r->stride_token;
+    v.stride_block = r->stride_block;
+    v.block_table = r->block_table;
+    v.bt_shift = 0;
+    if (r->block_table)
+        while ((1 << v.bt_shift) < r->block_tokens) ++v.bt_shift;
+    v.num_phys_blocks = r->num_phys_blocks;
+    return v;
+}
+
+static QuantArgs quant_args(const kvc_plan_t *p, const kvc_request *r, int is_v, uint8_t *payload,
+                            const Geometry &g, int *status, bool compress)
+{
+    QuantArgs a;
+    memset(&a, 0, sizeof a);
+    const int bits = is_v ? p->strat.bits_v : p->strat.bits_k;
+    const int group = is_v ? p->strat.group_v : p->strat.group_k;
+    a.x = view_of(r, is_v);
+    a.codes = payload + (is_v ? g.off_codes_v : g.off_codes_k);
+    a.meta = payload + (is_v ? g.off_meta_v : g.off_meta_k);
+    a.tokens = r->tokens;
+    a.heads = p->model.kv_heads;
+    a.group = group;
+    const long long rows_per_unit = (compress && !is_v && bits != 16) ? group : kPassRows;
+    a.units_per_head = (r->tokens + rows_per_unit - 1) / rows_per_unit;
+    a.total_units = a.units_per_head * p->model.layers * p->model.kv_heads;
+    a.status = status;
+    return a;
+}
+
+static CoderArgs coder_args(const kvc_plan_t *p, const QuantArgs &q, int is_v, uint8_t *payload,
+                            const Geometry &g, uint8_t *ws, long long capacity, uint64_t *out_bytes)
+{
+    CoderArgs c;
+    memset(&c, 0, sizeof c);
+    c.q = q;
+    c.payload = payload;
+    c.off_aux = g.off_aux;
+    c.off_bodies = g.off_codes_k;
+    c.capacity = capacity;
+    c.chunks = is_v ? g.chunks_v : g.chunks_k;
+    c.chunk_base = is_v ? g.chunks_k : 0;
+    const long long wg_k = (g.chunks_k + 3) / 4, wg_v = (g.chunks_v + 3) / 4;
+    c.wg_base = is_v ? wg_k : 0;
+    c.total_wgs = wg_k + wg_v;
+    c.total_chunks = g.chunks_k + g.chunks_v;
+    c.is_v = is_v;
+    c.ws.hist = (uint32_t *)ws;
+    c.ws.enc = (uint32_t *)(ws + a256(2 * 256 * 4));
+    c.ws.lut = (uint16_t *)(ws + 2 * a256(2 * 256 * 4));
+    c.ws.ticket = (uint32_t *)(ws + 2 * a256(2 * 256 * 4) + a256(2 * 4096 * 2));
+    c.ws.state = (unsigned long long *)(ws + p->ws_state_off);
+    c.out_bytes = (unsigned long long *)out_bytes;
+    return c;
+}
+
+static int check_batch(const kvc_plan_t *p, const kvc_request *reqs, int32_t n, const void *payload,
+                       const uint64_t *off, const void *workspace)
+{
+    if (!p || !reqs || n < 1 || !payload || !off || !aligned16(payload)) return KVC_ERR_ARG;
+    if (n > p->max_batch) return KVC_ERR_CAPACITY;
+    if (p->ws_request && (!workspace || !aligned16(workspace))) return KVC_ERR_ARG;
+    for (int i = 0; i < n; ++i) {
+        int rc = check_request(p, &reqs[i]);
+        if (rc) return rc;
+        if ((off[i] & 15) || off[i + 1] < off[i]) return KVC_ERR_ARG;
+    }
+    return KVC_OK;
+}
+
+#define KVC_TRY(expr) do { int rc__ = (expr); if (rc__ != KVC_OK) return rc__; } while (0)
+
+extern "C" int kvc_compress(const kvc_plan_t *plan, const kvc_request *reqs, int32_t n, void *payload,
+                            const uint64_t *payload_off, uint64_t *out_bytes, int32_t *dev_status,
+                            void *workspace, void *hip_stream)
+{
+    KVC_TRY(check_batch(plan, reqs, n, payload, payload_off, workspace));
+    if (!out_bytes || !dev_status || ((uintptr_t)out_bytes & 7) || ((uintptr_t)dev_status & 3)) return KVC_ERR_ARG;
+    for (int i = 0; i < n; ++i) {
+        Geometry g;
+        geometry(plan, reqs[i].tokens, &g);
+        if (payload_off[i + 1] - payload_off[i] < (uint64_t)g.total) return KVC_ERR_CAPACITY;
+    }
+    hipStream_t s = (hipStream_t)hip_stream;
+    const kvc_strategy &st = plan->strat;
+    const int dt = plan->model.dtype;
+    KVC_TRY(launch_fill_u32((uint32_t *)dev_status, 0, n, s));
+    for (int i = 0; i < n; ++i) {
+        const kvc_request *r = &reqs[i];
+        Geometry g;
+        geometry(plan, r->tokens, &g);
+        uint8_t *pl = (uint8_t *)payload + payload_off[i];
+        HeaderBytes hb;
+        make_header(plan, r->tokens, g, &hb);
+        KVC_TRY(launch_write_header(pl, hb, s));
+        // alignment padding after the V metadata and after the coder tables is zero
+        if (a16(g.meta_v) != g.meta_v)
+            KVC_TRY(launch_fill_u32((uint32_t *)(pl + g.off_meta_v + g.meta_v), 0, (a16(g.meta_v) - g.meta_v) / 4, s));
+        if (a16(g.aux) != g.aux)
+            KVC_TRY(launch_fill_u32((uint32_t *)(pl + g.off_aux + g.aux), 0, (a16(g.aux) - g.aux) / 4, s));
+        QuantArgs qk = quant_args(plan, r, 0, pl, g, dev_status + i, true);
+        QuantArgs qv = quant_args(plan, r, 1, pl, g, dev_status + i, true);
+        if (!st.codec) {
+            KVC_TRY(launch_compress_tensor(0, st.bits_k, st.group_k, dt, qk, s));
+            KVC_TRY(launch_compress_tensor(1, st.bits_v, st.group_v, dt, qv, s));
+            KVC_TRY(launch_fill_u32((uint32_t *)(out_bytes + i), (uint32_t)g.total, 1, s));
+            KVC_TRY(launch_fill_u32((uint32_t *)(out_bytes + i) + 1, (uint32_t)((uint64_t)g.total >> 32), 1, s));
+        } else {
+            uint8_t *ws = (uint8_t *)workspace + (size_t)i * plan->ws_request;
+            const long long cap = (long long)(payload_off[i + 1] - payload_off[i]);
+            CoderArgs ck = coder_args(plan, qk, 0, pl, g, ws, cap, out_bytes + i);
+            CoderArgs cv = coder_args(plan, qv, 1, pl, g, ws, cap, out_bytes + i);
+            // histograms, ticket and scan state start from zero
+            KVC_TRY(launch_fill_u32((uint32_t *)ws, 0, 2 * 256, s));
+            KVC_TRY(launch_fill_u32(ck.ws.ticket, 0, 64, s));
+            KVC_TRY(launch_fill_u32((uint32_t *)ck.ws.state, 0, 2 * ck.total_wgs + 2, s));
+            KVC_TRY(launch_coder_tables(st.bits_k, st.bits_v, st.group_k, st.group_v, dt, ck, cv, s));
+            KVC_TRY(launch_encode_section(st.bits_k, st.group_k, dt, ck, s));
+            KVC_TRY(launch_encode_section(st.bits_v, st.group_v, dt, cv, s));
+        }
+    }
+    return KVC_OK;
+}
+
+extern "C" int kvc_decompress(const kvc_plan_t *plan, const void *payload, const uint64_t *payload_off,
+                              const kvc_request *dst, int32_t n, int32_t *dev_status, void *workspace,
+                              void *hip_stream)
+{
+    KVC_TRY(check_batch(plan, dst, n, payload, payload_off, workspace));
+    if (!dev_status || ((uintptr_t)dev_status & 3)) return KVC_ERR_ARG;
+    for (int i = 0; i < n; ++i)
+        if (payload_off[i + 1] - payload_off[i] < kHeader) return KVC_ERR_CAPACITY;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const kvc_strategy &st = plan->strat;
+    const int dt = plan->model.dtype;
+    KVC_TRY(launch_fill_u32((uint32_t *)dev_status, 0, n, s));
+    for (int i = 0; i < n; ++i) {
+        const kvc_request *r = &dst[i];
+        Geometry g;
+        geometry(plan, r->tokens, &g);
+        uint8_t *pl = (uint8_t *)payload + payload_off[i];
+        const long long cap = (long long)(payload_off[i + 1] - payload_off[i]);
+        if (!st.codec && cap < g.total) return KVC_ERR_CAPACITY;
+        if (st.codec && cap < g.off_codes_k) return KVC_ERR_CAPACITY;
+        HeaderBytes hb;
+        make_header(plan, r->tokens, g, &hb);
+        // words 10/11 (total), 26..31 (code sizes) depend on the data when the coder is on
+        const uint32_t mask = st.codec ? 0x03fff3ffu : 0xffffffffu;
+        KVC_TRY(launch_check_header(pl, hb, mask, dev_status + i, s));
+        QuantArgs qk = quant_args(plan, r, 0, pl, g, dev_status + i, false);
+        QuantArgs qv = quant_args(plan, r, 1, pl, g, dev_status + i, false);
+        if (!st.codec) {
+            KVC_TRY(launch_decompress_tensor(0, st.bits_k, st.group_k, dt, qk, s));
+            KVC_TRY(launch_decompress_tensor(1, st.bits_v, st.group_v, dt, qv, s));
+        } else {
+            uint8_t *ws = (uint8_t *)workspace + (size_t)i * plan->ws_request;
+            CoderArgs ck = coder_args(plan, qk, 0, pl, g, ws, cap, nullptr);
+            CoderArgs cv = coder_args(plan, qv, 1, pl, g, ws, cap, nullptr);
+            KVC_TRY(launch_decode_prepare(ck, s));
+            KVC_TRY(launch_decode_section(st.bits_k, st.group_k, dt, ck, s));
+            KVC_TRY(launch_decode_section(st.bits_v, st.group_v, dt, cv, s));
+        }
+    }
+    return KVC_OK;
+}

@@ -1,0 +1,260 @@
+// Device-side building blocks shared by the gfx950 kernels: lane geometry, row addressing,
+// 16-bit float conversion, group statistics, the quantizer and the bit packers.
+//
+// Lane geometry of every kernel: a wave of 64 lanes covers 4 token rows of one head at a
+// time; lane = 16*rsub + col, col owns channels [8*col, 8*col+8) (one 128-bit load),
+// rsub picks the row.  A "pass" is 32 rows: row = row0 + 4*i + rsub, i = 0..7.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace kvc {
+
+constexpr int kDim = 128;          // head_dim the kernels are written for
+constexpr int kPassRows = 32;      // token rows per wave pass
+constexpr int kChunkRows = 128;    // token rows per coder chunk
+constexpr int kSubs = 64;          // sub-blocks per chunk (2 rows each)
+constexpr int kMaxLen = 12;        // longest code word
+constexpr int kHeader = 128;
+
+enum { DT_F16 = 1, DT_BF16 = 2 };
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// One tensor (K or V) of one request.
+struct TensorView {
+    uint16_t *base;
+    long long stride_layer, stride_head, stride_token, stride_block;   // elements
+    const int *block_table;     // null = contiguous
+    int bt_shift;               // log2(block_tokens)
+    int num_phys_blocks;
+};
+
+// Bit casts go through by-value scalars: applying __builtin_bit_cast directly to an element
+// of an ext_vector (v[i]) reads element 0 with this compiler.
+__device__ __forceinline__ half2_t as_half2(uint32_t u) { return __builtin_bit_cast(half2_t, u); }
+__device__ __forceinline__ uint32_t as_u32(half2_t h) { return __builtin_bit_cast(uint32_t, h); }
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+// Element offset of row t of head (l, h).  A block-table entry out of range is reported
+// through `bad` and replaced by block 0, so the address is always inside the pool.
+__device__ __forceinline__ long long row_offset(const TensorView &v, long long head_off, long long t,
+                                                bool &bad)
+{
+    if (v.block_table == nullptr) return head_off + t * v.stride_token;
+    int blk = v.block_table[t >> v.bt_shift];
+    if ((unsigned)blk >= (unsigned)v.num_phys_blocks) { bad = true; blk = 0; }
+    return head_off + (long long)blk * v.stride_block +
+           (t & ((1ll << v.bt_shift) - 1)) * v.stride_token;
+}
+
+// ---- 16-bit floats ----------------------------------------------------------------------
+
+template <int DT> __device__ __forceinline__ float lo_f32(uint32_t w)
+{
+    if (DT == DT_F16) return (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xffffu));
+    return __uint_as_float(w << 16);
+}
+template <int DT> __device__ __forceinline__ float hi_f32(uint32_t w)
+{
+    if (DT == DT_F16) return (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16));
+    return __uint_as_float(w & 0xffff0000u);
+}
+template <int DT> __device__ __forceinline__ float elem_f32(const u32x4 &r, int e)
+{
+    return (e & 1) ? hi_f32<DT>(r[e >> 1]) : lo_f32<DT>(r[e >> 1]);
+}
+
+__device__ __forceinline__ float f16_bits_to_f32(uint32_t h)
+{
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)h);
+}
+__device__ __forceinline__ uint32_t f32_to_f16_bits(float f)
+{
+    return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);     // round to nearest even
+}
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;                  // nearest even, finite input
+}
+
+// Two reconstructed values -> one packed word of the output type, kept finite.
+template <int DT> __device__ __forceinline__ uint32_t pack_out(float a, float b)
+{
+    if (DT == DT_F16) {
+        a = __builtin_amdgcn_fmed3f(a, -65504.0f, 65504.0f);
+        b = __builtin_amdgcn_fmed3f(b, -65504.0f, 65504.0f);
+        return f32_to_f16_bits(a) | (f32_to_f16_bits(b) << 16);
+    }
+    const float m = 3.3895313892515355e38f;
+    a = __builtin_amdgcn_fmed3f(a, -m, m);
+    b = __builtin_amdgcn_fmed3f(b, -m, m);
+    return f32_to_bf16_bits(a) | (f32_to_bf16_bits(b) << 16);
+}
+
+// ---- cross-lane helpers -----------------------------------------------------------------
+
+template <int CTRL> __device__ __forceinline__ float dpp_f32(float v)
+{
+    return __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), CTRL, 0xf, 0xf, true));
+}
+template <int CTRL> __device__ __forceinline__ uint32_t dpp_u32(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+constexpr int DPP_QUAD_XOR1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int DPP_QUAD_XOR2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int DPP_HALF_MIRROR = 0x141;     // reverse within 8 lanes
+constexpr int DPP_MIRROR = 0x140;          // reverse within 16 lanes
+constexpr int DPP_QUAD_NEXT = 0xF9;        // quad_perm [1,2,3,3]: lane k reads lane k+1
+constexpr int DPP_QUAD_PREV = 0x90;        // quad_perm [0,0,1,2]: lane k reads lane k-1
+
+__device__ __forceinline__ float xlane_f32(float v, int xor_mask)
+{
+    return __uint_as_float((uint32_t)__builtin_amdgcn_ds_bpermute(((lane_id() ^ xor_mask) << 2),
+                                                                  (int)__float_as_uint(v)));
+}
+
+// min and max over the `LANES` (4, 8 or 16) adjacent lanes that share a V group
+template <int LANES> __device__ __forceinline__ void group_minmax(float &mn, float &mx)
+{
+    mn = fminf(mn, dpp_f32<DPP_QUAD_XOR1>(mn));
+    mx = fmaxf(mx, dpp_f32<DPP_QUAD_XOR1>(mx));
+    mn = fminf(mn, dpp_f32<DPP_QUAD_XOR2>(mn));
+    mx = fmaxf(mx, dpp_f32<DPP_QUAD_XOR2>(mx));
+    if (LANES >= 8) {
+        mn = fminf(mn, dpp_f32<DPP_HALF_MIRROR>(mn));
+        mx = fmaxf(mx, dpp_f32<DPP_HALF_MIRROR>(mx));
+    }
+    if (LANES >= 16) {
+        mn = fminf(mn, dpp_f32<DPP_MIRROR>(mn));
+        mx = fmaxf(mx, dpp_f32<DPP_MIRROR>(mx));
+    }
+}
+
+// ---- quantizer (KVServe section 5.1, stage Q: asymmetric, grouped; section 7.3: two
+//      16-bit metadata values per group) ------------------------------------------------
+
+struct GroupParams {
+    float zero;       // fp16-rounded minimum, as float
+    float inv;        // 1 / fp16-rounded scale (0 when the scale is 0)
+    uint32_t meta;    // scale bits | zero bits << 16
+};
+
+// zero = fp16(min), scale = fp16((max - min) / (2^bits - 1)); a zero of either sign is +0.
+template <int BITS> __device__ __forceinline__ GroupParams make_group(float mn, float mx)
+{
+    constexpr float qmax = (float)((1 << BITS) - 1);
+    mn += 0.0f;
+    mx += 0.0f;
+    float lo = __builtin_amdgcn_fmed3f(mn, -65504.0f, 65504.0f);
+    uint32_t zb = f32_to_f16_bits(lo);
+    float s = fminf((mx - mn) / qmax, 65504.0f);
+    uint32_t sb = f32_to_f16_bits(s);
+    float sh = f16_bits_to_f32(sb);
+    GroupParams g;
+    g.zero = f16_bits_to_f32(zb);
+    g.inv = (sh == 0.0f) ? 0.0f : 1.0f / sh;
+    g.meta = sb | (zb << 16);
+    return g;
+}
+
+// code = clamp(round_half_even((x - zero) * inv), 0, 2^bits - 1); two rounded fp32 operations.
+template <int BITS> __device__ __forceinline__ uint32_t quantize(float x, float zero, float inv)
+{
+    constexpr float qmax = (float)((1 << BITS) - 1);
+    float t = (x - zero) * inv;
+    t = __builtin_amdgcn_fmed3f(t, 0.0f, qmax);
+    return (uint32_t)(int)__builtin_rintf(t);
+}
+
+// ---- bit packing: element i of a row at bits [i*BITS, i*BITS+BITS) ------------------------
+
+// The 8 codes of one lane -> BITS bytes (returned in up to two words, low bits first).
+template <int BITS> __device__ __forceinline__ u32x2 pack8(const uint32_t q[8])
+{
+    u32x2 r;
+    if (BITS == 8) {
+        r[0] = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
+        r[1] = q[4] | (q[5] << 8) | (q[6] << 16) | (q[7] << 24);
+    } else {
+        uint32_t w = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) w |= q[e] << (e * BITS);
+        r[0] = w;
+        r[1] = 0;
+    }
+    return r;
+}
+
+template <int BITS> __device__ __forceinline__ void unpack8(u32x2 w, uint32_t q[8])
+{
+    if (BITS == 8) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) q[e] = (w[e >> 2] >> ((e & 3) * 8)) & 0xffu;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) q[e] = (w[0] >> (e * BITS)) & ((1u << BITS) - 1u);
+    }
+}
+
+// 3-bit rows: the 4 lanes of a quad hold 4 x 24 bits = three aligned words.  Lane k < 3 of
+// the quad ends up owning word k.
+__device__ __forceinline__ uint32_t quad_words_from_24(uint32_t c24)
+{
+    int k = lane_id() & 3;
+    uint32_t next = dpp_u32<DPP_QUAD_NEXT>(c24);
+    return (k == 0) ? (c24 | (next << 24)) : ((c24 >> (8 * k)) | (next << (24 - 8 * k)));
+}
+// Inverse: lane k < 3 holds word k (lane 3 holds word 2 again); every lane gets its 24 bits.
+__device__ __forceinline__ uint32_t quad_24_from_words(uint32_t word)
+{
+    int k = lane_id() & 3;
+    uint32_t prev = dpp_u32<DPP_QUAD_PREV>(word);       // lane 0 reads itself
+    uint32_t lo = (k == 0) ? word : (prev >> ((32 - 8 * k) & 31));
+    uint32_t hi = (k == 0) ? 0u : (word << (8 * k));
+    return (lo | hi) & 0xffffffu;
+}
+
+// Byte offset of a lane's packed codes inside a row of 16*BITS bytes, and the store itself.
+// 2 bits: u16 per lane; 3 bits: word per lane for 3 lanes of 4; 4 bits: word; 8 bits: 2 words.
+template <int BITS> __device__ __forceinline__ void store_row_codes(uint8_t *row, u32x2 w)
+{
+    int col = lane_id() & 15;
+    if (BITS == 2) {
+        *(uint16_t *)(row + col * 2) = (uint16_t)w[0];
+    } else if (BITS == 3) {
+        uint32_t word = quad_words_from_24(w[0]);
+        if ((col & 3) != 3) *(uint32_t *)(row + (col >> 2) * 12 + (col & 3) * 4) = word;
+    } else if (BITS == 4) {
+        *(uint32_t *)(row + col * 4) = w[0];
+    } else {
+        *(u32x2 *)(row + col * 8) = w;
+    }
+}
+
+template <int BITS> __device__ __forceinline__ u32x2 load_row_codes(const uint8_t *row)
+{
+    int col = lane_id() & 15;
+    u32x2 w;
+    w[1] = 0;
+    if (BITS == 2) {
+        w[0] = *(const uint16_t *)(row + col * 2);
+    } else if (BITS == 3) {
+        int k = col & 3;
+        uint32_t word = *(const uint32_t *)(row + (col >> 2) * 12 + (k == 3 ? 2 : k) * 4);
+        w[0] = quad_24_from_words(word);
+    } else if (BITS == 4) {
+        w[0] = *(const uint32_t *)(row + col * 4);
+    } else {
+        w = *(const u32x2 *)(row + col * 8);
+    }
+    return w;
+}
+
+}  // namespace kvc

@@ -1,0 +1,314 @@
+// Codec-free kernels: quantize + pack (compress) and unpack + dequantize (decompress) one
+// tensor of one request straight between the KV layout and the payload sections.
+// One wave per work unit, four units per workgroup, no LDS, no barriers.
+//   K compress unit   = one token block of G rows x 128 channels (all 128 per-channel groups)
+//   other units       = 32 token rows
+// Stage Q of the pipeline (KVServe section 5.1); memory-bound, so no matrix cores.
+
+#include "kvc_internal.h"
+#include "kvc_tile.h"
+#include "../../include/kvc.h"
+
+namespace kvc {
+
+struct UnitPos {
+    long long lh;        // layer * heads + head
+    long long blk;       // unit index inside the head
+    long long head_off;  // element offset of x[l][h][0][0]
+};
+
+__device__ __forceinline__ bool unit_pos(const QuantArgs &a, UnitPos &u)
+{
+    long long unit = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (unit >= a.total_units) return false;
+    u.lh = unit / a.units_per_head;
+    u.blk = unit - u.lh * a.units_per_head;
+    long long l = u.lh / a.heads, h = u.lh - l * a.heads;
+    u.head_off = l * a.x.stride_layer + h * a.x.stride_head;
+    return true;
+}
+
+__device__ __forceinline__ void report(int *status, bool bad)
+{
+    if (bad) atomicOr(status, KVC_DEV_BAD_BLOCK);
+}
+
+// ---- K: groups along tokens, one per channel ------------------------------------------------
+
+template <int BITS, int G, int DT>
+__global__ __launch_bounds__(256) void compress_k_kernel(QuantArgs a)
+{
+    UnitPos u;
+    if (!unit_pos(a, u)) return;
+    constexpr int P = G / kPassRows;
+    const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
+    const long long row0 = u.blk * G;
+    bool bad = false;
+    u32x4 raw[P * 8];
+#pragma unroll
+    for (int p = 0; p < P; ++p) load_pass(a.x, u.head_off, row0 + p * kPassRows, a.tokens, raw + p * 8, bad);
+
+    float mn[8], mx[8];
+    k_stats<DT, P * 8>(raw, mn, mx);
+    GroupParams gp[8];
+    u32x4 m0, m1;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        gp[e] = make_group<BITS>(mn[e], mx[e]);
+        if (e < 4) m0[e] = gp[e].meta; else m1[e - 4] = gp[e].meta;
+    }
+    if (rsub == 0) {
+        u32x4 *m = (u32x4 *)(a.meta + ((u.lh * a.units_per_head + u.blk) * kDim + col * 8) * 4);
+        m[0] = m0;
+        m[1] = m1;
+    }
+    uint8_t *codes = a.codes + (u.lh * a.tokens + row0) * (16 * BITS);
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int r = p * kPassRows + 4 * i + rsub;
+            u32x2 w = k_quant_row<BITS, DT>(raw[p * 8 + i], gp);
+            if (BITS == 3) w[0] = quad_words_from_24(w[0]);
+            if (row0 + r < a.tokens) {
+                uint8_t *row = codes + (long long)r * (16 * BITS);
+                if (BITS == 3) {
+                    if ((col & 3) != 3) *(uint32_t *)(row + (col >> 2) * 12 + (col & 3) * 4) = w[0];
+                } else {
+                    store_row_codes<BITS>(row, w);
+                }
+            }
+        }
+    report(a.status, bad);
+}
+
+template <int BITS, int DT>
+__global__ __launch_bounds__(256) void decompress_k_kernel(QuantArgs a)
+{
+    UnitPos u;
+    if (!unit_pos(a, u)) return;
+    if (*a.status & KVC_DEV_BAD_HEADER) return;
+    const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
+    const long long row0 = u.blk * kPassRows;
+    const long long tb = row0 / a.group, nb = (a.tokens + a.group - 1) / a.group;
+    const u32x4 *m = (const u32x4 *)(a.meta + ((u.lh * nb + tb) * kDim + col * 8) * 4);
+    u32x4 m0 = m[0], m1 = m[1];
+    uint32_t meta[8] = {m0[0], m0[1], m0[2], m0[3], m1[0], m1[1], m1[2], m1[3]};
+    const uint8_t *codes = a.codes + (u.lh * a.tokens + row0) * (16 * BITS);
+    bool bad = false;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const long long row = row0 + 4 * i + rsub;
+        const bool live = row < a.tokens;              // uniform over each quad of lanes
+        u32x2 w = load_row_codes<BITS>(codes + (live ? (4 * i + rsub) : 0) * (16 * BITS));
+        u32x4 out = dequant_row<BITS, DT>(w, meta);
+        if (live) {
+            bool b = false;
+            long long off = row_offset(a.x, u.head_off, row, b);
+            if (!b) *(u32x4 *)(a.x.base + off + col * 8) = out;
+            bad |= b;
+        }
+    }
+    report(a.status, bad);
+}
+
+// ---- V: groups along channels, one set per token -----------------------------------------------
+
+template <int BITS, int GV, int DT>
+__global__ __launch_bounds__(256) void compress_v_kernel(QuantArgs a)
+{
+    UnitPos u;
+    if (!unit_pos(a, u)) return;
+    constexpr int LANES = GV / 8, NG = kDim / GV;
+    const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
+    const long long row0 = u.blk * kPassRows;
+    bool bad = false;
+    u32x4 raw[8];
+    load_pass(a.x, u.head_off, row0, a.tokens, raw, bad);
+    uint8_t *codes = a.codes + (u.lh * a.tokens + row0) * (16 * BITS);
+    uint32_t *meta = (uint32_t *)a.meta + (u.lh * a.tokens + row0) * NG;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = 4 * i + rsub;
+        uint32_t mw;
+        u32x2 w = v_quant_row<BITS, GV, DT>(raw[i], mw);
+        if (BITS == 3) w[0] = quad_words_from_24(w[0]);
+        if (row0 + r < a.tokens) {
+            uint8_t *row = codes + (long long)r * (16 * BITS);
+            if (BITS == 3) {
+                if ((col & 3) != 3) *(uint32_t *)(row + (col >> 2) * 12 + (col & 3) * 4) = w[0];
+            } else {
+                store_row_codes<BITS>(row, w);
+            }
+            if ((col & (LANES - 1)) == 0) meta[(long long)r * NG + col / LANES] = mw;
+        }
+    }
+    report(a.status, bad);
+}
+
+template <int BITS, int DT>
+__global__ __launch_bounds__(256) void decompress_v_kernel(QuantArgs a)
+{
+    UnitPos u;
+    if (!unit_pos(a, u)) return;
+    if (*a.status & KVC_DEV_BAD_HEADER) return;
+    const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
+    const long long row0 = u.blk * kPassRows;
+    const int lanes = a.group >> 3, ng = kDim / a.group;
+    const uint8_t *codes = a.codes + (u.lh * a.tokens + row0) * (16 * BITS);
+    const uint32_t *meta = (const uint32_t *)a.meta + (u.lh * a.tokens + row0) * ng;
+    bool bad = false;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const long long row = row0 + 4 * i + rsub;
+        const bool live = row < a.tokens;
+        const int r = live ? 4 * i + rsub : 0;
+        u32x2 w = load_row_codes<BITS>(codes + r * (16 * BITS));
+        uint32_t mw = meta[r * ng + col / lanes];
+        u32x4 out = dequant_row_uniform<BITS, DT>(w, mw);
+        if (live) {
+            bool b = false;
+            long long off = row_offset(a.x, u.head_off, row, b);
+            if (!b) *(u32x4 *)(a.x.base + off + col * 8) = out;
+            bad |= b;
+        }
+    }
+    report(a.status, bad);
+}
+
+// ---- 16 bits: the tensor travels unchanged ----------------------------------------------------
+
+template <bool TO_PAYLOAD>
+__global__ __launch_bounds__(256) void copy_rows_kernel(QuantArgs a)
+{
+    UnitPos u;
+    if (!unit_pos(a, u)) return;
+    if (!TO_PAYLOAD && (*a.status & KVC_DEV_BAD_HEADER)) return;
+    const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
+    const long long row0 = u.blk * kPassRows;
+    bool bad = false;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const long long row = row0 + 4 * i + rsub;
+        if (row < a.tokens) {
+            bool b = false;
+            uint16_t *x = a.x.base + row_offset(a.x, u.head_off, row, b) + col * 8;
+            u32x4 *p = (u32x4 *)(a.codes + ((u.lh * a.tokens + row) * kDim + col * 8) * 2);
+            if (TO_PAYLOAD) *p = *(const u32x4 *)x;
+            else if (!b) *(u32x4 *)x = *p;
+            bad |= b;
+        }
+    }
+    report(a.status, bad);
+}
+
+// ---- small service kernels --------------------------------------------------------------------
+
+__global__ void write_header_kernel(uint32_t *dst, HeaderBytes h)
+{
+    if (threadIdx.x < 32) dst[threadIdx.x] = h.w[threadIdx.x];
+}
+
+__global__ void check_header_kernel(const uint32_t *hdr, HeaderBytes expect, uint32_t mask, int *status)
+{
+    const int i = threadIdx.x;
+    bool diff = i < 32 && ((mask >> i) & 1u) && hdr[i] != expect.w[i];
+    if (diff) atomicOr(status, KVC_DEV_BAD_HEADER);
+}
+
+__global__ void fill_u32_kernel(uint32_t *dst, uint32_t value, long long n)
+{
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = value;
+}
+
+// ---- launchers ----------------------------------------------------------------------------------
+
+static inline dim3 grid_for(long long units) { return dim3((unsigned)((units + 3) / 4)); }
+
+#define KVC_LAUNCH(kernel, a, s)                                                        \
+    do {                                                                                \
+        if ((a).total_units > 0)                                                        \
+            hipLaunchKernelGGL(kernel, grid_for((a).total_units), dim3(256), 0, s, a);  \
+        return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_DEVICE;               \
+    } while (0)
+
+template <int BITS, int DT> static int compress_bits_dt(int is_v, int group, const QuantArgs &a, hipStream_t s)
+{
+    if (!is_v) {
+        switch (group) {
+        case 32: KVC_LAUNCH((compress_k_kernel<BITS, 32, DT>), a, s);
+        case 64: KVC_LAUNCH((compress_k_kernel<BITS, 64, DT>), a, s);
+        case 128: KVC_LAUNCH((compress_k_kernel<BITS, 128, DT>), a, s);
+        }
+    } else {
+        switch (group) {
+        case 32: KVC_LAUNCH((compress_v_kernel<BITS, 32, DT>), a, s);
+        case 64: KVC_LAUNCH((compress_v_kernel<BITS, 64, DT>), a, s);
+        case 128: KVC_LAUNCH((compress_v_kernel<BITS, 128, DT>), a, s);
+        }
+    }
+    return KVC_ERR_UNSUPPORTED;
+}
+
+template <int BITS> static int compress_bits(int is_v, int group, int dtype, const QuantArgs &a, hipStream_t s)
+{
+    return dtype == DT_F16 ? compress_bits_dt<BITS, DT_F16>(is_v, group, a, s)
+                           : compress_bits_dt<BITS, DT_BF16>(is_v, group, a, s);
+}
+
+int launch_compress_tensor(int is_v, int bits, int group, int dtype, const QuantArgs &a, hipStream_t s)
+{
+    switch (bits) {
+    case 2: return compress_bits<2>(is_v, group, dtype, a, s);
+    case 3: return compress_bits<3>(is_v, group, dtype, a, s);
+    case 4: return compress_bits<4>(is_v, group, dtype, a, s);
+    case 8: return compress_bits<8>(is_v, group, dtype, a, s);
+    case 16: KVC_LAUNCH(copy_rows_kernel<true>, a, s);
+    }
+    return KVC_ERR_UNSUPPORTED;
+}
+
+template <int BITS> static int decompress_bits(int is_v, int dtype, const QuantArgs &a, hipStream_t s)
+{
+    if (!is_v) {
+        if (dtype == DT_F16) KVC_LAUNCH((decompress_k_kernel<BITS, DT_F16>), a, s);
+        KVC_LAUNCH((decompress_k_kernel<BITS, DT_BF16>), a, s);
+    }
+    if (dtype == DT_F16) KVC_LAUNCH((decompress_v_kernel<BITS, DT_F16>), a, s);
+    KVC_LAUNCH((decompress_v_kernel<BITS, DT_BF16>), a, s);
+}
+
+int launch_decompress_tensor(int is_v, int bits, int group, int dtype, const QuantArgs &a, hipStream_t s)
+{
+    (void)group;
+    switch (bits) {
+    case 2: return decompress_bits<2>(is_v, dtype, a, s);
+    case 3: return decompress_bits<3>(is_v, dtype, a, s);
+    case 4: return decompress_bits<4>(is_v, dtype, a, s);
+    case 8: return decompress_bits<8>(is_v, dtype, a, s);
+    case 16: KVC_LAUNCH(copy_rows_kernel<false>, a, s);
+    }
+    return KVC_ERR_UNSUPPORTED;
+}
+
+int launch_write_header(uint8_t *dst, const HeaderBytes &h, hipStream_t s)
+{
+    hipLaunchKernelGGL(write_header_kernel, dim3(1), dim3(64), 0, s, (uint32_t *)dst, h);
+    return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_DEVICE;
+}
+
+int launch_check_header(const uint8_t *hdr, const HeaderBytes &expect, uint32_t mask, int *status, hipStream_t s)
+{
+    hipLaunchKernelGGL(check_header_kernel, dim3(1), dim3(64), 0, s, (const uint32_t *)hdr, expect, mask, status);
+    return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_DEVICE;
+}
+
+int launch_fill_u32(uint32_t *dst, uint32_t value, long long n, hipStream_t s)
+{
+    if (n <= 0) return KVC_OK;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dst, value, n);
+    return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_DEVICE;
+}
+
+}  // namespace kvc

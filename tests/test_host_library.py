@@ -1,0 +1,122 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, and its host
+logic (plan validation, payload size, header inspection) agrees with the oracle's geometry.
+No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2605_13734_amd import kvc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(kvc.LIB_PATH):
+        from paper_2605_13734_amd import build
+        build.build()
+    return kvc.load()
+
+
+def test_exports_every_declared_symbol(lib):
+    text = open(os.path.join(ROOT, "include", "kvc.h")).read()
+    declared = set(re.findall(r"\b(kvc_[a-z_]+)\s*\(", text))
+    assert declared == set(kvc.SYMBOLS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_plan_validation(lib):
+    ok = dict(dtype=1, layers=2, kv_heads=2)
+    kvc.Plan(**ok)
+    bad = [dict(bits_k=5), dict(bits_v=0), dict(group_k=48), dict(group_v=16), dict(dtype=3),
+           dict(layers=0), dict(codec=2), dict(max_batch=0), dict(max_tokens=-1)]
+    for kw in bad:
+        with pytest.raises(kvc.KvcError) as e:
+            kvc.Plan(**{**ok, **kw})
+        assert e.value.status == -1, kw
+    unsupported = [dict(head_dim=64), dict(transform=1), dict(bits_k=16, codec=1)]
+    for kw in unsupported:
+        with pytest.raises(kvc.KvcError) as e:
+            kvc.Plan(**{**ok, **kw})
+        assert e.value.status == -2, kw
+    assert kvc.status_string(-3) == "capacity too small"
+
+
+@pytest.mark.parametrize("codec", [0, 1])
+def test_payload_size_matches_oracle_geometry(lib, ref, codec):
+    for (L, H, T, bk, bv, gk, gv) in [(1, 8, 1024, 4, 4, 32, 32), (32, 8, 8192, 2, 2, 64, 64),
+                                      (3, 2, 1000, 4, 2, 64, 32), (1, 1, 1, 3, 3, 128, 128),
+                                      (2, 4, 77, 8, 4, 32, 64), (1, 2, 0, 4, 4, 32, 32),
+                                      (80, 8, 32768, 4, 4, 32, 32), (94, 4, 20001, 4, 2, 64, 64)]:
+        plan = kvc.Plan(2, L, H, 128, bk, bv, gk, gv, codec, max_tokens=T)
+        cfg = ref.config(dtype=2, layers=L, heads=H, bits_k=bk, bits_v=bv, group_k=gk, group_v=gv, codec=codec)
+        assert plan.payload_size(T) == ref.payload_size(cfg, T)
+        assert (plan.workspace_size() > 0) == bool(codec)
+    if not codec:
+        plan = kvc.Plan(1, 1, 1, 128, 2, 2, 32, 32, 0)
+        n, exact = plan.payload_size(1 << 20)
+        assert exact and abs(2 * (1 << 20) * 128 * 2 / n - 16 / 3) < 1e-3    # section 7.3: 5.33x
+
+
+def test_sixteen_bit_sizes(lib, ref):
+    plan = kvc.Plan(1, 2, 2, 128, 16, 4, 32, 64, 0)
+    cfg = ref.config(layers=2, heads=2, bits_k=16, bits_v=4, group_k=32, group_v=64)
+    assert plan.payload_size(77) == ref.payload_size(cfg, 77)
+
+
+def test_inspect_reads_oracle_payloads(lib, ref):
+    from paper_2605_13734_amd import kvgen
+    x = kvgen.make_kv(0, 2, 2, 128, 150)
+    xu = kvgen.as_u16(x)
+    lay = ref.contiguous_layout(2, 150, 128)
+    for codec in (0, 1):
+        cfg = ref.config(layers=2, heads=2, bits_k=4, bits_v=3, group_k=64, group_v=32, codec=codec)
+        p = ref.compress(cfg, xu[0, 0], xu[0, 1], lay, 150)
+        rc, m, s, tokens, total, sec = kvc.payload_inspect(p)
+        assert rc == 0 and tokens == 150 and total == p.size
+        assert (m.dtype, m.layers, m.kv_heads, m.head_dim) == (1, 2, 2, 128)
+        assert (s.bits_k, s.bits_v, s.group_k, s.group_v, s.codec) == (4, 3, 64, 32, codec)
+        assert sec == ref.inspect(p)[4]
+        for pos, val in [(0, 0), (4, 9), (6, 7), (20, 5), (27, 1), (48, 1), (96, 3), (40, p[40] ^ 1)]:
+            bad = p.copy()
+            bad[pos] = val
+            assert kvc.payload_inspect(bad)[0] == -4, pos
+    bad = p.copy(); bad[16] = 64          # head_dim the kernels are not built for, otherwise well formed
+    assert kvc.payload_inspect(bad)[0] in (-2, -4)
+
+
+def test_block_table_check(lib):
+    assert kvc.check_block_table([0, 5, 7], 8) == 0
+    assert kvc.check_block_table([0, 8, 7], 8) == -1
+    assert kvc.check_block_table([0, -1], 8) == -1
+
+
+def test_host_errors_before_launch(lib):
+    """Argument errors are returned without touching a device (there is none here)."""
+    plan = kvc.Plan(1, 1, 1, max_tokens=64, max_batch=1)
+    r = kvc.request(0x1000, 0x2000, 64, 128 * 64 * 2, 128 * 64, 128)
+    with pytest.raises(kvc.KvcError) as e:
+        kvc.compress(plan, [r], None, [0, 1 << 20], 0x100, 0x200)
+    assert e.value.status == -1                                   # null payload
+    with pytest.raises(kvc.KvcError) as e:
+        kvc.compress(plan, [r], 0x10000, [0, 64], 0x100, 0x200)
+    assert e.value.status == -3                                   # capacity
+    with pytest.raises(kvc.KvcError) as e:
+        kvc.compress(plan, [r, r], 0x10000, [0, 1 << 20, 2 << 20], 0x100, 0x200)
+    assert e.value.status == -3                                   # batch larger than planned
+    r2 = kvc.request(0x1000, 0x2000, 65, 128 * 64 * 2, 128 * 64, 128)
+    with pytest.raises(kvc.KvcError) as e:
+        kvc.compress(plan, [r2], 0x10000, [0, 1 << 20], 0x100, 0x200)
+    assert e.value.status == -3                                   # more tokens than planned
+    r3 = kvc.request(0x1004, 0x2000, 64, 128 * 64 * 2, 128 * 64, 128)
+    with pytest.raises(kvc.KvcError) as e:
+        kvc.compress(plan, [r3], 0x10000, [0, 1 << 20], 0x100, 0x200)
+    assert e.value.status == -1                                   # misaligned tensor
+    r4 = kvc.request(0x1000, 0x2000, 64, 0, 128, 256, 0x3000, 16 * 256, 12, 8)
+    with pytest.raises(kvc.KvcError) as e:
+        kvc.compress(plan, [r4], 0x10000, [0, 1 << 20], 0x100, 0x200)
+    assert e.value.status == -2                                   # block size not a power of two
