@@ -132,8 +132,9 @@ extern "C" int kvc_plan(const kvc_model *model, const kvc_strategy *strategy, in
     p->max_batch = max_batch;
     if (strategy->codec) {
         // histograms, encode tables, decode tables, ticket, then the scan state
+        // one state word per encode workgroup; a workgroup takes at least 2 chunks
         const long long chunks = (long long)model->layers * model->kv_heads * chunks_per_head(max_tokens);
-        const long long wgs = 2 * ((chunks + 3) / 4);
+        const long long wgs = 2 * ((chunks + 1) / 2);
         p->ws_state_off = a256(2 * 256 * 4) + a256(2 * 256 * 4) + a256(2 * 4096 * 2) + 256;
         p->ws_request = p->ws_state_off + a256((size_t)wgs * 8 + 8);
     }
@@ -289,7 +290,9 @@ static CoderArgs coder_args(const kvc_plan_t *p, const QuantArgs &q, int is_v, u
     c.capacity = capacity;
     c.chunks = is_v ? g.chunks_v : g.chunks_k;
     c.chunk_base = is_v ? g.chunks_k : 0;
-    const long long wg_k = (g.chunks_k + 3) / 4, wg_v = (g.chunks_v + 3) / 4;
+    // chunks per encode workgroup: 2 at 8 bits, 4 otherwise (LDS footprint of a chunk)
+    const int nw_k = p->strat.bits_k == 8 ? 2 : 4, nw_v = p->strat.bits_v == 8 ? 2 : 4;
+    const long long wg_k = (g.chunks_k + nw_k - 1) / nw_k, wg_v = (g.chunks_v + nw_v - 1) / nw_v;
     c.wg_base = is_v ? wg_k : 0;
     c.total_wgs = wg_k + wg_v;
     c.total_chunks = g.chunks_k + g.chunks_v;
@@ -366,6 +369,15 @@ extern "C" int kvc_compress(const kvc_plan_t *plan, const kvc_request *reqs, int
             KVC_TRY(launch_coder_tables(st.bits_k, st.bits_v, st.group_k, st.group_v, dt, ck, cv, s));
             KVC_TRY(launch_encode_section(st.bits_k, st.group_k, dt, ck, s));
             KVC_TRY(launch_encode_section(st.bits_v, st.group_v, dt, cv, s));
+            if (ck.total_chunks == 0) {
+                // empty request: no workgroup runs that could close the directory and header
+                put64((uint8_t *)hb.w + 40, (uint64_t)g.off_codes_k);
+                put64((uint8_t *)hb.w + 112, (uint64_t)g.off_codes_k);
+                KVC_TRY(launch_write_header(pl, hb, s));
+                KVC_TRY(launch_fill_u32((uint32_t *)(pl + g.off_aux + 512), 0, 1, s));
+                KVC_TRY(launch_fill_u32((uint32_t *)(out_bytes + i), (uint32_t)g.off_codes_k, 1, s));
+                KVC_TRY(launch_fill_u32((uint32_t *)(out_bytes + i) + 1, 0, 1, s));
+            }
         }
     }
     return KVC_OK;

@@ -1,9 +1,829 @@
-// placeholder until the coder kernels land
+// Lossless stage (codec C of the pipeline, KVServe section 5.1) fused with the quantizer:
+// canonical, length-limited Huffman coding of the packed code bytes.
+//
+// Format (per section K or V): chunks of 128 token rows of one head; a chunk body is
+// 64 x u16 sub-block bit counts (a sub-block = 2 rows), then the code words, most
+// significant bit first in 32-bit little-endian words, sub-blocks back to back, padded
+// to 16 bytes -- or the raw packed bytes when that is not smaller.  Bodies are stored
+// back to back; a directory of running offsets (16-byte units) locates them.
+//
+// One wave owns one chunk: it quantizes the chunk into LDS, every lane then codes one
+// sub-block, and the body is copied to its final place, which comes from a single-pass
+// prefix sum over workgroups (ticket order + look-back on a state word per workgroup).
+// Decoding mirrors it: body -> LDS, every lane decodes one sub-block with a 4096-entry
+// table, the packed rows are rebuilt in LDS and dequantized from there.
+
 #include "kvc_internal.h"
+#include "kvc_tile.h"
 #include "../../include/kvc.h"
+
 namespace kvc {
-int launch_coder_tables(int, int, int, int, int, const CoderArgs &, const CoderArgs &, hipStream_t) { return KVC_ERR_UNSUPPORTED; }
-int launch_encode_section(int, int, int, const CoderArgs &, hipStream_t) { return KVC_ERR_UNSUPPORTED; }
-int launch_decode_prepare(const CoderArgs &, hipStream_t) { return KVC_ERR_UNSUPPORTED; }
-int launch_decode_section(int, int, int, const CoderArgs &, hipStream_t) { return KVC_ERR_UNSUPPORTED; }
+
+constexpr unsigned long long kFlagAgg = 1ull << 62, kFlagPrefix = 2ull << 62, kValueMask = (1ull << 62) - 1;
+constexpr int kSpinLimit = 1 << 20;
+
+template <int BITS> struct ChunkGeom {
+    static constexpr int kRowBytes = 16 * BITS;            // packed bytes of one token row
+    static constexpr int kSubBytes = 2 * kRowBytes;        // one sub-block
+    static constexpr int kSubStride = kSubBytes + 16;      // LDS stride (bank spread, 16-byte aligned)
+    static constexpr int kWords = kSubBytes / 4;           // words a lane holds for its sub-block
+    static constexpr int kLds = kSubs * kSubStride;        // LDS bytes per wave
+    static constexpr int kWaves = BITS == 8 ? 2 : 4;       // waves (= chunks) per workgroup
+};
+
+// ---- chunk <-> LDS -------------------------------------------------------------------------
+
+template <int BITS> __device__ __forceinline__ uint8_t *lds_row(uint8_t *lds, int r)
+{
+    return lds + (r >> 1) * ChunkGeom<BITS>::kSubStride + (r & 1) * ChunkGeom<BITS>::kRowBytes;
 }
+
+struct ChunkPos {
+    long long lh, cb, head_off, row0;
+    int rows;
+};
+
+__device__ __forceinline__ ChunkPos chunk_pos(const QuantArgs &a, long long chunk)
+{
+    ChunkPos c;
+    const long long cph = (a.tokens + kChunkRows - 1) / kChunkRows;
+    c.lh = chunk / cph;
+    c.cb = chunk - c.lh * cph;
+    const long long l = c.lh / a.heads, h = c.lh - l * a.heads;
+    c.head_off = l * a.x.stride_layer + h * a.x.stride_head;
+    c.row0 = c.cb * kChunkRows;
+    const long long left = a.tokens - c.row0;
+    c.rows = left < kChunkRows ? (int)left : kChunkRows;
+    return c;
+}
+
+// Quantize and pack the chunk's rows into the wave's LDS region (sub-block layout) and,
+// when `write_meta`, store the group metadata to the payload.
+template <int BITS, int G, int DT, bool IS_V>
+__device__ __forceinline__ void quantize_chunk(const QuantArgs &a, const ChunkPos &c, uint8_t *lds,
+                                               bool write_meta, bool &bad)
+{
+    const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
+    if (!IS_V) {
+        constexpr int P = G / kPassRows;
+        const long long nb = (a.tokens + G - 1) / G;
+#pragma unroll 1
+        for (int gb = 0; gb < kChunkRows / G; ++gb) {
+            if (gb * G >= c.rows) break;
+            const long long row0 = c.row0 + gb * G;
+            u32x4 raw[P * 8];
+#pragma unroll
+            for (int p = 0; p < P; ++p) load_pass(a.x, c.head_off, row0 + p * kPassRows, a.tokens, raw + p * 8, bad);
+            float mn[8], mx[8];
+            k_stats<DT, P * 8>(raw, mn, mx);
+            GroupParams gp[8];
+            u32x4 m0, m1;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                gp[e] = make_group<BITS>(mn[e], mx[e]);
+                if (e < 4) m0[e] = gp[e].meta; else m1[e - 4] = gp[e].meta;
+            }
+            if (write_meta && rsub == 0) {
+                u32x4 *m = (u32x4 *)(a.meta + ((c.lh * nb + row0 / G) * kDim + col * 8) * 4);
+                m[0] = m0;
+                m[1] = m1;
+            }
+#pragma unroll
+            for (int p = 0; p < P; ++p)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int r = gb * G + p * kPassRows + 4 * i + rsub;
+                    u32x2 w = k_quant_row<BITS, DT>(raw[p * 8 + i], gp);
+                    if (BITS == 3) w[0] = quad_words_from_24(w[0]);
+                    if (r < c.rows) {
+                        uint8_t *row = lds_row<BITS>(lds, r);
+                        if (BITS == 3) {
+                            if ((col & 3) != 3) *(uint32_t *)(row + (col >> 2) * 12 + (col & 3) * 4) = w[0];
+                        } else {
+                            store_row_codes<BITS>(row, w);
+                        }
+                    }
+                }
+        }
+    } else {
+        constexpr int LANES = G / 8, NG = kDim / G;
+#pragma unroll 1
+        for (int p = 0; p < kChunkRows / kPassRows; ++p) {
+            if (p * kPassRows >= c.rows) break;
+            const long long row0 = c.row0 + p * kPassRows;
+            u32x4 raw[8];
+            load_pass(a.x, c.head_off, row0, a.tokens, raw, bad);
+            uint32_t *meta = (uint32_t *)a.meta + (c.lh * a.tokens + row0) * NG;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int r = p * kPassRows + 4 * i + rsub;
+                uint32_t mw;
+                u32x2 w = v_quant_row<BITS, G, DT>(raw[i], mw);
+                if (BITS == 3) w[0] = quad_words_from_24(w[0]);
+                if (r < c.rows) {
+                    uint8_t *row = lds_row<BITS>(lds, r);
+                    if (BITS == 3) {
+                        if ((col & 3) != 3) *(uint32_t *)(row + (col >> 2) * 12 + (col & 3) * 4) = w[0];
+                    } else {
+                        store_row_codes<BITS>(row, w);
+                    }
+                    if (write_meta && (col & (LANES - 1)) == 0) meta[(4 * i + rsub) * NG + col / LANES] = mw;
+                }
+            }
+        }
+    }
+}
+
+// The lane's sub-block (rows 2*lane, 2*lane+1) from LDS into registers.
+template <int BITS> __device__ __forceinline__ void load_sub(const uint8_t *lds, uint32_t *sym)
+{
+    constexpr int W = ChunkGeom<BITS>::kWords;
+    const u32x4 *p = (const u32x4 *)(lds + lane_id() * ChunkGeom<BITS>::kSubStride);
+#pragma unroll
+    for (int k = 0; k < W / 4; ++k) {
+        u32x4 v = p[k];
+        sym[4 * k] = v[0]; sym[4 * k + 1] = v[1]; sym[4 * k + 2] = v[2]; sym[4 * k + 3] = v[3];
+    }
+}
+
+template <int BITS> __device__ __forceinline__ void store_sub(uint8_t *lds, const uint32_t *sym)
+{
+    constexpr int W = ChunkGeom<BITS>::kWords;
+    u32x4 *p = (u32x4 *)(lds + lane_id() * ChunkGeom<BITS>::kSubStride);
+#pragma unroll
+    for (int k = 0; k < W / 4; ++k) {
+        u32x4 v;
+        v[0] = sym[4 * k]; v[1] = sym[4 * k + 1]; v[2] = sym[4 * k + 2]; v[3] = sym[4 * k + 3];
+        p[k] = v;
+    }
+}
+
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// inclusive prefix sum over the 64 lanes
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v)
+{
+    const int lane = lane_id();
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint32_t o = (uint32_t)__builtin_amdgcn_ds_bpermute((lane - d) << 2, (int)v);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+// ---- table sample: histogram of up to 16 chunks per section ------------------------------------
+
+template <int BITS, int G, int DT, bool IS_V>
+__global__ __launch_bounds__(64) void hist_kernel(CoderArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t lds[ChunkGeom<BITS>::kLds];
+    __shared__ uint32_t hist[256];
+    const int i = blockIdx.x, lane = lane_id();
+    const long long n = a.chunks;
+    const long long chunk = (long long)i * n / 16;
+    if (i > 0 && (long long)(i - 1) * n / 16 == chunk) return;      // each chunk counted once
+    for (int k = lane; k < 256; k += 64) hist[k] = 0;
+    ChunkPos c = chunk_pos(a.q, chunk);
+    bool bad = false;
+    quantize_chunk<BITS, G, DT, IS_V>(a.q, c, lds, false, bad);
+    wave_sync();
+    constexpr int W = ChunkGeom<BITS>::kWords;
+    uint32_t sym[W];
+    load_sub<BITS>(lds, sym);
+    const int valid = min(max(c.rows - 2 * lane, 0), 2) * (W / 2);
+#pragma unroll
+    for (int k = 0; k < W; ++k)
+        if (k < valid) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) atomicAdd(&hist[(sym[k] >> (8 * b)) & 255u], 1u);
+        }
+    wave_sync();
+    uint32_t *g = a.ws.hist + (IS_V ? 256 : 0);
+    for (int k = lane; k < 256; k += 64)
+        if (hist[k]) atomicAdd(&g[k], hist[k]);
+}
+
+// ---- code construction (one wave per section) ---------------------------------------------------
+
+// Huffman code lengths of 256 symbols from weights w[] (LDS), joining the two nodes with the
+// smallest (weight, id) each time: leaves have id = symbol, the k-th joined node id 256 + k.
+// Leaves sorted by (weight, symbol) form one queue, joined nodes (created in non-decreasing
+// weight order) the other; the heads of the two queues are the two candidates.
+struct BuildLds {
+    unsigned long long w[512];     // node weights: leaves 0..255, joined nodes 256..510
+    uint16_t sorted[256];          // leaves by (weight, symbol)
+    uint16_t parent[512];
+    uint8_t len[256];
+    uint32_t count[16], first[16], start[16];
+    uint16_t by_len[256];          // symbols by (length, symbol)
+    int longest;
+};
+
+__device__ __forceinline__ void build_lengths(BuildLds &s)
+{
+    const int lane = lane_id();
+    for (;;) {
+        // rank of each leaf among all leaves
+        for (int k = lane; k < 256; k += 64) {
+            const unsigned long long wk = s.w[k];
+            int rank = 0;
+            for (int t = 0; t < 256; ++t) {
+                const unsigned long long wt = s.w[t];
+                rank += (wt < wk || (wt == wk && t < k)) ? 1 : 0;
+            }
+            s.sorted[rank] = (uint16_t)k;
+        }
+        wave_sync();
+        if (lane == 0) {
+            int lq = 0, iq = 256, made = 256;          // queue heads; next joined-node id
+            for (int k = 0; k < 255; ++k) {
+                int pick[2];
+                for (int j = 0; j < 2; ++j) {
+                    const bool has_leaf = lq < 256, has_int = iq < made;
+                    bool take_leaf = has_leaf;
+                    if (has_leaf && has_int) take_leaf = s.w[s.sorted[lq]] <= s.w[iq];   // leaf ids are lower
+                    pick[j] = take_leaf ? (int)s.sorted[lq++] : iq++;
+                }
+                s.w[made] = s.w[pick[0]] + s.w[pick[1]];
+                s.parent[pick[0]] = s.parent[pick[1]] = (uint16_t)made;
+                ++made;
+            }
+            s.parent[510] = 0xffff;
+            s.longest = 0;
+        }
+        wave_sync();
+        for (int k = lane; k < 256; k += 64) {
+            int d = 0;
+            for (int i = k; s.parent[i] != 0xffff && d < 512; i = s.parent[i]) ++d;
+            s.len[k] = (uint8_t)d;
+            atomicMax(&s.longest, d);
+        }
+        wave_sync();
+        if (s.longest <= kMaxLen) return;
+        for (int k = lane; k < 256; k += 64) {
+            unsigned long long v = (s.w[k] + 1) >> 1;
+            s.w[k] = v < 1 ? 1 : v;
+        }
+        wave_sync();
+    }
+}
+
+// Canonical order tables from len[]: count / first code / start index per length, and the
+// symbols sorted by (length, symbol).  Returns false if the lengths are not a complete code.
+__device__ __forceinline__ bool canonical_tables(BuildLds &s)
+{
+    const int lane = lane_id();
+    if (lane < 16) s.count[lane] = 0;
+    wave_sync();
+    bool ok = true;
+    for (int k = lane; k < 256; k += 64) {
+        const int L = s.len[k];
+        if (L < 1 || L > kMaxLen) ok = false;
+        else atomicAdd(&s.count[L], 1u);
+    }
+    wave_sync();
+    if (lane == 0) {
+        uint32_t next = 0, at = 0, kraft = 0;
+        for (int L = 1; L <= kMaxLen; ++L) {
+            s.first[L] = next;
+            s.start[L] = at;
+            next = (next + s.count[L]) << 1;
+            at += s.count[L];
+            kraft += s.count[L] << (kMaxLen - L);
+        }
+        s.longest = (kraft == (1u << kMaxLen)) ? 1 : 0;
+    }
+    wave_sync();
+    ok = ok && s.longest == 1;
+    if (__builtin_amdgcn_ballot_w64(!ok) != 0) return false;
+    for (int k = lane; k < 256; k += 64) {
+        const int L = s.len[k];
+        int rank = 0;
+        for (int t = 0; t < k; ++t) rank += (s.len[t] == L) ? 1 : 0;
+        s.by_len[s.start[L] + rank] = (uint16_t)k;
+    }
+    wave_sync();
+    return true;
+}
+
+__device__ __forceinline__ uint32_t code_of(const BuildLds &s, int sym)
+{
+    const int L = s.len[sym];
+    int rank = 0;
+    for (int t = 0; t < sym; ++t) rank += (s.len[t] == L) ? 1 : 0;
+    return s.first[L] + rank;
+}
+
+// grid = 2 workgroups of one wave: 0 builds the K table, 1 the V table
+__global__ __launch_bounds__(64) void build_tables_kernel(CoderArgs a)
+{
+    __shared__ BuildLds s;
+    const int sec = blockIdx.x, lane = lane_id();
+    const uint32_t *hist = a.ws.hist + 256 * sec;
+    for (int k = lane; k < 256; k += 64) s.w[k] = (unsigned long long)hist[k] + 1;
+    wave_sync();
+    build_lengths(s);
+    canonical_tables(s);
+    uint8_t *lens = a.payload + a.off_aux + 256 * sec;
+    uint32_t *enc = a.ws.enc + 256 * sec;
+    for (int k = lane; k < 256; k += 64) {
+        lens[k] = s.len[k];
+        enc[k] = code_of(s, k) | ((uint32_t)s.len[k] << 16);
+    }
+}
+
+// grid = 2 workgroups of one wave: decode tables from the lengths stored in the payload
+__global__ __launch_bounds__(64) void decode_prepare_kernel(CoderArgs a)
+{
+    __shared__ BuildLds s;
+    const int sec = blockIdx.x, lane = lane_id();
+    if (*a.q.status & KVC_DEV_BAD_HEADER) return;
+    const uint8_t *lens = a.payload + a.off_aux + 256 * sec;
+    for (int k = lane; k < 256; k += 64) s.len[k] = lens[k];
+    wave_sync();
+    uint16_t *lut = a.ws.lut + 4096 * sec;
+    if (!canonical_tables(s)) {
+        if (lane == 0) atomicOr(a.q.status, KVC_DEV_BAD_TABLE);
+        for (int i = lane; i < 4096; i += 64) lut[i] = (uint16_t)(1u << 8);      // symbol 0, length 1
+        return;
+    }
+    // entry i describes the code word that is a prefix of the 12-bit string i
+    for (int i = lane; i < 4096; i += 64) {
+        uint16_t e = (uint16_t)(1u << 8);
+        for (int L = 1; L <= kMaxLen; ++L) {
+            const uint32_t c = (uint32_t)i >> (kMaxLen - L);
+            if (c >= s.first[L] && c - s.first[L] < s.count[L]) {
+                e = (uint16_t)(s.by_len[s.start[L] + c - s.first[L]] | (L << 8));
+                break;
+            }
+        }
+        lut[i] = e;
+    }
+}
+
+// ---- encoder ---------------------------------------------------------------------------------
+
+// bit count of HALF (0 or 1) of the lane's sub-block
+template <int W> __device__ __forceinline__ uint32_t half_bits(const uint32_t *sym, const uint8_t *enc_bytes, int half)
+{
+    uint32_t bits = 0;
+#pragma unroll
+    for (int k = 0; k < W / 2; ++k) {
+        const uint32_t w = sym[half * (W / 2) + k];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) bits += enc_bytes[((w >> (8 * b)) & 255u) * 4 + 2];
+    }
+    return bits;
+}
+
+struct BitWriter {
+    unsigned long long acc;
+    uint32_t nbits;
+    uint32_t *out;       // next word (LDS)
+};
+
+__device__ __forceinline__ void flush(BitWriter &bw)
+{
+    if (bw.nbits >= 32) {
+        atomicOr(bw.out, (uint32_t)(bw.acc >> (bw.nbits - 32)));
+        ++bw.out;
+        bw.nbits -= 32;
+    }
+}
+
+template <int W> __device__ __forceinline__ void encode_half(const uint32_t *sym, const uint32_t *enc, int half, BitWriter &bw)
+{
+#pragma unroll
+    for (int k = 0; k < W / 2; ++k) {
+        const uint32_t w = sym[half * (W / 2) + k];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const uint32_t e = enc[(w >> (8 * b)) & 255u];
+            const uint32_t len = e >> 16;
+            bw.acc = (bw.acc << len) | (e & 0xffffu);
+            bw.nbits += len;
+            if (b & 1) flush(bw);          // at most 24 new bits between checks
+        }
+    }
+}
+
+template <int BITS, int G, int DT, bool IS_V>
+__global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void encode_kernel(CoderArgs a)
+{
+    using Geo = ChunkGeom<BITS>;
+    constexpr int W = Geo::kWords, NW = Geo::kWaves;
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * Geo::kLds];
+    __shared__ uint32_t enc[256];
+    __shared__ uint32_t s_units[NW];
+    __shared__ unsigned long long s_excl;
+    __shared__ uint32_t s_ticket;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
+    if (tid == 0) s_ticket = atomicAdd(a.ws.ticket, 1u);
+    for (int k = tid; k < 256; k += NW * 64) enc[k] = a.ws.enc[(IS_V ? 256 : 0) + k];
+    __syncthreads();
+    const long long ticket = s_ticket;                 // global order over K and V workgroups
+    const long long chunk = (ticket - a.wg_base) * NW + wave;
+    const bool live = chunk < a.chunks;
+    uint8_t *lds = lds_all + wave * Geo::kLds;
+
+    uint32_t body_units = 0;      // body size in 16-byte units
+    bool coded = false;
+    int rows = 0;
+    uint32_t sym[W];
+    if (live) {
+        ChunkPos c = chunk_pos(a.q, chunk);
+        rows = c.rows;
+        bool bad = false;
+        quantize_chunk<BITS, G, DT, IS_V>(a.q, c, lds, true, bad);
+        if (bad) atomicOr(a.q.status, KVC_DEV_BAD_BLOCK);
+        wave_sync();
+        load_sub<BITS>(lds, sym);
+        const int have = min(max(rows - 2 * lane, 0), 2);        // valid rows of this sub-block
+        uint32_t bits = 0;
+        if (have > 0) bits += half_bits<W>(sym, (const uint8_t *)enc, 0);
+        if (have > 1) bits += half_bits<W>(sym, (const uint8_t *)enc, 1);
+        const uint32_t incl = wave_inclusive_sum(bits);
+        const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+        const uint32_t raw_bytes = (uint32_t)rows * Geo::kRowBytes;
+        const uint32_t coded_bytes = (2 * kSubs + 4 * ((total + 31) / 32) + 15) & ~15u;
+        coded = coded_bytes < raw_bytes;
+        body_units = (coded ? coded_bytes : raw_bytes) / 16;
+        if (coded) {
+            wave_sync();                                          // every lane holds its symbols
+            u32x4 zero = {0, 0, 0, 0};
+            for (uint32_t o = lane * 16; o < coded_bytes; o += 64 * 16) *(u32x4 *)(lds + o) = zero;
+            wave_sync();
+            ((uint16_t *)lds)[lane] = (uint16_t)bits;
+            const uint32_t start = incl - bits;
+            BitWriter bw;
+            bw.acc = 0;
+            bw.nbits = start & 31;
+            bw.out = (uint32_t *)(lds + 2 * kSubs) + (start >> 5);
+            if (have > 0) encode_half<W>(sym, enc, 0, bw);
+            if (have > 1) encode_half<W>(sym, enc, 1, bw);
+            if (bw.nbits > 0 && bits > 0) atomicOr(bw.out, (uint32_t)(bw.acc << (32 - bw.nbits)));
+            wave_sync();
+        }
+    }
+    if (lane == 0) s_units[wave] = body_units;
+    __syncthreads();
+
+    // ---- single-pass prefix sum over workgroups, in ticket order ------------------------------
+    if (wave == 0) {
+        unsigned long long agg = 0;
+        for (int w = 0; w < NW; ++w) agg += s_units[w];
+        unsigned long long excl = 0;
+        bool timeout = false;
+        if (ticket > 0) {
+            if (lane == 0)
+                __hip_atomic_store(&a.ws.state[ticket], kFlagAgg | agg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            long long idx = ticket - 1;
+            int spins = 0;
+            for (;;) {
+                const long long j = idx - lane;
+                unsigned long long v = kFlagPrefix;
+                if (j >= 0) v = __hip_atomic_load(&a.ws.state[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const unsigned flag = (unsigned)(v >> 62);
+                if (__builtin_amdgcn_ballot_w64(flag == 0) != 0) {
+                    if (++spins > kSpinLimit) { timeout = true; break; }
+                    __builtin_amdgcn_s_sleep(8);
+                    continue;
+                }
+                const unsigned long long pm = __builtin_amdgcn_ballot_w64(flag == 2);
+                const int stop = pm ? __builtin_ctzll(pm) : 63;      // nearest predecessor with a full prefix
+                unsigned long long part = (lane <= stop) ? (v & kValueMask) : 0;
+#pragma unroll
+                for (int d = 32; d >= 1; d >>= 1) {
+                    const uint32_t lo = (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ d) << 2, (int)(uint32_t)part);
+                    const uint32_t hi = (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ d) << 2, (int)(uint32_t)(part >> 32));
+                    part += ((unsigned long long)hi << 32) | lo;
+                }
+                excl += part;
+                if (pm) break;
+                idx -= 64;
+            }
+        }
+        if (timeout) {
+            excl = 0;
+            if (lane == 0) atomicOr(a.q.status, KVC_DEV_SCAN_TIMEOUT);
+        }
+        if (lane == 0) {
+            __hip_atomic_store(&a.ws.state[ticket], kFlagPrefix | ((excl + agg) & kValueMask), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+            s_excl = timeout ? ~0ull : excl;
+            if (ticket == a.total_wgs - 1 && !timeout) {
+                // the very last workgroup closes the directory and the header
+                const unsigned long long all = excl + agg;
+                uint32_t *dir = (uint32_t *)(a.payload + a.off_aux + 512);
+                dir[a.total_chunks] = (uint32_t)all;
+                unsigned long long k_units = 0;
+                if (a.wg_base > 0)
+                    k_units = __hip_atomic_load(&a.ws.state[a.wg_base - 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kValueMask;
+                else if (!IS_V)
+                    k_units = all;
+                const unsigned long long total = (unsigned long long)a.off_bodies + all * 16;
+                unsigned long long *h = (unsigned long long *)a.payload;
+                h[5] = total;                                   // byte 40: total bytes
+                h[13] = k_units * 16;                           // byte 104: K code bytes
+                h[14] = (unsigned long long)a.off_bodies + k_units * 16;   // byte 112: V code offset
+                h[15] = (all - k_units) * 16;                   // byte 120: V code bytes
+                *a.out_bytes = total;
+            }
+        }
+    }
+    __syncthreads();
+    const unsigned long long excl = s_excl;
+    if (!live || excl == ~0ull) return;
+    unsigned long long mine = excl;
+    for (int w = 0; w < wave; ++w) mine += s_units[w];
+    if (lane == 0) ((uint32_t *)(a.payload + a.off_aux + 512))[a.chunk_base + chunk] = (uint32_t)mine;
+    uint8_t *dst = a.payload + a.off_bodies + mine * 16;
+    if ((long long)(a.off_bodies + (mine + body_units) * 16) > a.capacity) return;      // cannot happen: bodies never exceed raw size
+    if (coded) {
+        for (uint32_t o = lane * 16; o < body_units * 16; o += 64 * 16) *(u32x4 *)(dst + o) = *(const u32x4 *)(lds + o);
+    } else {
+        // raw chunk: each lane still holds its sub-block (2 rows) in registers
+        const int have = min(max(rows - 2 * lane, 0), 2);
+        u32x4 *p = (u32x4 *)(dst + lane * Geo::kSubBytes);
+#pragma unroll
+        for (int k = 0; k < W / 4; ++k)
+            if (k * 2 < have * (W / 4)) {
+                u32x4 v;
+                v[0] = sym[4 * k]; v[1] = sym[4 * k + 1]; v[2] = sym[4 * k + 2]; v[3] = sym[4 * k + 3];
+                p[k] = v;
+            }
+    }
+}
+
+// ---- decoder ---------------------------------------------------------------------------------
+
+struct BitReader {
+    unsigned long long window;   // upcoming bits, left aligned
+    int avail;
+    const uint32_t *next;        // next word (LDS)
+    const uint32_t *last;        // last readable word
+};
+
+__device__ __forceinline__ void refill(BitReader &br)
+{
+    if (br.avail <= 32) {
+        br.window |= (unsigned long long)(*br.next) << (32 - br.avail);
+        br.avail += 32;
+        if (br.next < br.last) ++br.next;
+    }
+}
+
+template <int W> __device__ __forceinline__ void decode_half(uint32_t *sym, const uint16_t *lut, int half, BitReader &br)
+{
+#pragma unroll
+    for (int k = 0; k < W / 2; ++k) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const uint32_t e = lut[(uint32_t)(br.window >> 52)];
+            const uint32_t len = e >> 8;
+            w |= (e & 255u) << (8 * b);
+            br.window <<= len;
+            br.avail -= (int)len;
+            if (b & 1) refill(br);
+        }
+        sym[half * (W / 2) + k] = w;
+    }
+}
+
+template <int BITS, int DT, bool IS_V>
+__global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void decode_kernel(CoderArgs a)
+{
+    using Geo = ChunkGeom<BITS>;
+    constexpr int W = Geo::kWords, NW = Geo::kWaves;
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * Geo::kLds];
+    __shared__ uint16_t lut[4096];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id(), col = lane & 15, rsub = lane >> 4;
+    {
+        const u32x4 *src = (const u32x4 *)(a.ws.lut + (IS_V ? 4096 : 0));
+        for (int k = tid; k < 512; k += NW * 64) ((u32x4 *)lut)[k] = src[k];
+    }
+    __syncthreads();
+    const long long chunk = (long long)blockIdx.x * NW + wave;
+    if (chunk >= a.chunks) return;
+    if (*a.q.status & (KVC_DEV_BAD_HEADER | KVC_DEV_BAD_TABLE)) return;
+    uint8_t *lds = lds_all + wave * Geo::kLds;
+    const ChunkPos c = chunk_pos(a.q, chunk);
+    const uint32_t raw_bytes = (uint32_t)c.rows * Geo::kRowBytes;
+
+    const uint32_t *dir = (const uint32_t *)(a.payload + a.off_aux + 512) + a.chunk_base + chunk;
+    const unsigned long long d0 = dir[0], d1 = dir[1];
+    const unsigned long long size = (d1 - d0) * 16;
+    if (d1 < d0 || size > raw_bytes || (long long)(a.off_bodies + d1 * 16) > a.capacity ||
+        (size != raw_bytes && size < 2 * kSubs + 16)) {
+        if (lane == 0) atomicOr(a.q.status, KVC_DEV_BAD_CHUNK);
+        return;
+    }
+    const uint8_t *body = a.payload + a.off_bodies + d0 * 16;
+    if (size == raw_bytes) {
+        // stored raw: scatter the packed rows into the sub-block layout
+        for (uint32_t o = lane * 16; o < raw_bytes; o += 64 * 16) {
+            const uint32_t sub = o / Geo::kSubBytes, in = o - sub * Geo::kSubBytes;
+            *(u32x4 *)(lds + sub * Geo::kSubStride + in) = *(const u32x4 *)(body + o);
+        }
+        wave_sync();
+    } else {
+        for (uint32_t o = lane * 16; o < size; o += 64 * 16) *(u32x4 *)(lds + o) = *(const u32x4 *)(body + o);
+        wave_sync();
+        const uint32_t bits = ((const uint16_t *)lds)[lane];
+        const uint32_t incl = wave_inclusive_sum(bits);
+        const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+        if (((2 * kSubs + 4 * ((total + 31) / 32) + 15) & ~15u) != size) {
+            if (lane == 0) atomicOr(a.q.status, KVC_DEV_BAD_CHUNK);
+            return;
+        }
+        const uint32_t start = incl - bits;
+        const uint32_t *words = (const uint32_t *)(lds + 2 * kSubs);
+        BitReader br;
+        br.last = (const uint32_t *)(lds + size) - 1;
+        const uint32_t *p = words + (start >> 5);
+        p = p < br.last ? p : br.last;
+        const uint32_t w0 = *p;
+        p = p < br.last ? p + 1 : p;
+        const uint32_t w1 = *p;
+        p = p < br.last ? p + 1 : p;
+        br.window = (((unsigned long long)w0 << 32) | w1) << (start & 31);
+        br.avail = 64 - (int)(start & 31);
+        br.next = p;
+        uint32_t sym[W];
+#pragma unroll
+        for (int k = 0; k < W; ++k) sym[k] = 0;
+        const int have = min(max(c.rows - 2 * lane, 0), 2);
+        if (have > 0) decode_half<W>(sym, lut, 0, br);
+        if (have > 1) decode_half<W>(sym, lut, 1, br);
+        wave_sync();                                   // all lanes are done reading the coded words
+        store_sub<BITS>(lds, sym);
+        wave_sync();
+    }
+
+    // dequantize the rows from LDS
+    bool bad = false;
+    const int group = a.q.group;
+#pragma unroll 1
+    for (int p = 0; p < kChunkRows / kPassRows; ++p) {
+        if (p * kPassRows >= c.rows) break;
+        const long long row0 = c.row0 + p * kPassRows;
+        uint32_t meta_k[8];
+        const uint32_t *meta_v = nullptr;
+        int ng = 0, lanes_shift = 0;
+        if (!IS_V) {
+            const long long nb = (a.q.tokens + group - 1) / group;
+            const u32x4 *m = (const u32x4 *)(a.q.meta + ((c.lh * nb + row0 / group) * kDim + col * 8) * 4);
+            u32x4 m0 = m[0], m1 = m[1];
+            meta_k[0] = m0[0]; meta_k[1] = m0[1]; meta_k[2] = m0[2]; meta_k[3] = m0[3];
+            meta_k[4] = m1[0]; meta_k[5] = m1[1]; meta_k[6] = m1[2]; meta_k[7] = m1[3];
+        } else {
+            ng = kDim / group;
+            lanes_shift = group == 32 ? 2 : (group == 64 ? 3 : 4);
+            meta_v = (const uint32_t *)a.q.meta + (c.lh * a.q.tokens + row0) * ng;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int r = p * kPassRows + 4 * i + rsub;
+            const bool ok = r < c.rows;
+            const int rr = ok ? r : p * kPassRows;
+            u32x2 w = load_row_codes<BITS>(lds_row<BITS>(lds, rr));
+            u32x4 out;
+            if (!IS_V) {
+                out = dequant_row<BITS, DT>(w, meta_k);
+            } else {
+                const uint32_t mw = meta_v[(rr - p * kPassRows) * ng + (col >> lanes_shift)];
+                out = dequant_row_uniform<BITS, DT>(w, mw);
+            }
+            if (ok) {
+                bool b = false;
+                const long long off = row_offset(a.q.x, c.head_off, c.row0 + r, b);
+                if (!b) *(u32x4 *)(a.q.x.base + off + col * 8) = out;
+                bad |= b;
+            }
+        }
+    }
+    if (bad) atomicOr(a.q.status, KVC_DEV_BAD_BLOCK);
+}
+
+// ---- launchers ----------------------------------------------------------------------------------
+
+static inline int launched() { return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_DEVICE; }
+
+template <int BITS, int G, int DT, bool IS_V> static int hist_launch(const CoderArgs &a, hipStream_t s)
+{
+    if (a.chunks <= 0) return KVC_OK;
+    hipLaunchKernelGGL((hist_kernel<BITS, G, DT, IS_V>), dim3(16), dim3(64), 0, s, a);
+    return launched();
+}
+
+template <int BITS, int G, int DT, bool IS_V> static int encode_launch(const CoderArgs &a, hipStream_t s)
+{
+    constexpr int NW = ChunkGeom<BITS>::kWaves;
+    const long long need = (a.chunks + NW - 1) / NW;
+    if (need <= 0) return KVC_OK;
+    hipLaunchKernelGGL((encode_kernel<BITS, G, DT, IS_V>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
+    return launched();
+}
+
+template <int BITS, int DT, bool IS_V> static int decode_launch(const CoderArgs &a, hipStream_t s)
+{
+    constexpr int NW = ChunkGeom<BITS>::kWaves;
+    const long long need = (a.chunks + NW - 1) / NW;
+    if (need <= 0) return KVC_OK;
+    hipLaunchKernelGGL((decode_kernel<BITS, DT, IS_V>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
+    return launched();
+}
+
+#define KVC_BY_GROUP(FN, BITS, DT, ISV, group, ...)                    \
+    switch (group) {                                                   \
+    case 32: return FN<BITS, 32, DT, ISV>(__VA_ARGS__);                \
+    case 64: return FN<BITS, 64, DT, ISV>(__VA_ARGS__);                \
+    case 128: return FN<BITS, 128, DT, ISV>(__VA_ARGS__);              \
+    }                                                                  \
+    return KVC_ERR_UNSUPPORTED
+
+template <int BITS, int DT, bool ISV> static int hist_g(int group, const CoderArgs &a, hipStream_t s) { KVC_BY_GROUP(hist_launch, BITS, DT, ISV, group, a, s); }
+template <int BITS, int DT, bool ISV> static int encode_g(int group, const CoderArgs &a, hipStream_t s) { KVC_BY_GROUP(encode_launch, BITS, DT, ISV, group, a, s); }
+
+template <int BITS, bool ISV> static int hist_d(int group, int dtype, const CoderArgs &a, hipStream_t s)
+{
+    return dtype == DT_F16 ? hist_g<BITS, DT_F16, ISV>(group, a, s) : hist_g<BITS, DT_BF16, ISV>(group, a, s);
+}
+template <int BITS, bool ISV> static int encode_d(int group, int dtype, const CoderArgs &a, hipStream_t s)
+{
+    return dtype == DT_F16 ? encode_g<BITS, DT_F16, ISV>(group, a, s) : encode_g<BITS, DT_BF16, ISV>(group, a, s);
+}
+template <int BITS, bool ISV> static int decode_d(int dtype, const CoderArgs &a, hipStream_t s)
+{
+    return dtype == DT_F16 ? decode_launch<BITS, DT_F16, ISV>(a, s) : decode_launch<BITS, DT_BF16, ISV>(a, s);
+}
+
+template <bool ISV> static int hist_b(int bits, int group, int dtype, const CoderArgs &a, hipStream_t s)
+{
+    switch (bits) {
+    case 2: return hist_d<2, ISV>(group, dtype, a, s);
+    case 3: return hist_d<3, ISV>(group, dtype, a, s);
+    case 4: return hist_d<4, ISV>(group, dtype, a, s);
+    case 8: return hist_d<8, ISV>(group, dtype, a, s);
+    }
+    return KVC_ERR_UNSUPPORTED;
+}
+template <bool ISV> static int encode_b(int bits, int group, int dtype, const CoderArgs &a, hipStream_t s)
+{
+    switch (bits) {
+    case 2: return encode_d<2, ISV>(group, dtype, a, s);
+    case 3: return encode_d<3, ISV>(group, dtype, a, s);
+    case 4: return encode_d<4, ISV>(group, dtype, a, s);
+    case 8: return encode_d<8, ISV>(group, dtype, a, s);
+    }
+    return KVC_ERR_UNSUPPORTED;
+}
+template <bool ISV> static int decode_b(int bits, int dtype, const CoderArgs &a, hipStream_t s)
+{
+    switch (bits) {
+    case 2: return decode_d<2, ISV>(dtype, a, s);
+    case 3: return decode_d<3, ISV>(dtype, a, s);
+    case 4: return decode_d<4, ISV>(dtype, a, s);
+    case 8: return decode_d<8, ISV>(dtype, a, s);
+    }
+    return KVC_ERR_UNSUPPORTED;
+}
+
+int launch_coder_tables(int bits_k, int bits_v, int group_k, int group_v, int dtype, const CoderArgs &k,
+                        const CoderArgs &v, hipStream_t s)
+{
+    int rc = hist_b<false>(bits_k, group_k, dtype, k, s);
+    if (rc) return rc;
+    rc = hist_b<true>(bits_v, group_v, dtype, v, s);
+    if (rc) return rc;
+    hipLaunchKernelGGL(build_tables_kernel, dim3(2), dim3(64), 0, s, k);
+    return launched();
+}
+
+int launch_encode_section(int bits, int group, int dtype, const CoderArgs &a, hipStream_t s)
+{
+    return a.is_v ? encode_b<true>(bits, group, dtype, a, s) : encode_b<false>(bits, group, dtype, a, s);
+}
+
+int launch_decode_prepare(const CoderArgs &k, hipStream_t s)
+{
+    hipLaunchKernelGGL(decode_prepare_kernel, dim3(2), dim3(64), 0, s, k);
+    return launched();
+}
+
+int launch_decode_section(int bits, int group, int dtype, const CoderArgs &a, hipStream_t s)
+{
+    (void)group;
+    return a.is_v ? decode_b<true>(bits, dtype, a, s) : decode_b<false>(bits, dtype, a, s);
+}
+
+}  // namespace kvc

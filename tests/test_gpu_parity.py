@@ -197,3 +197,122 @@ def test_determinism():
     a = gpu_compress(plan, [kvc.contiguous_request(x)], [500]).payload_of(0)
     b = gpu_compress(plan, [kvc.contiguous_request(x)], [500]).payload_of(0)
     assert np.array_equal(a, b)
+
+
+# ---- lossless stage -----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("bits,group,dtype,T", [
+    (4, 32, torch.float16, 1024), (4, 32, torch.float16, 333), (2, 64, torch.bfloat16, 700),
+    (3, 128, torch.float16, 515), (8, 32, torch.bfloat16, 260), (8, 128, torch.float16, 129),
+    (2, 32, torch.float16, 1), (4, 64, torch.bfloat16, 33), (3, 32, torch.bfloat16, 128),
+    (4, 128, torch.float16, 2500)])
+def test_codec_payload_and_round_trip(ref, bits, group, dtype, T):
+    """Tables, directory, chunk bodies and header with the coder on: byte-identical to the
+    oracle, and the reconstruction equals the codec-free one."""
+    x = kvgen.make_kv(20 + bits, 2, 3, 128, T, dtype)
+    check_contiguous(ref, x, bits, bits, group, group, codec=1)
+
+
+def test_codec_mixed_bits(ref):
+    x = kvgen.make_kv(30, 3, 2, 128, 777, torch.float16)
+    check_contiguous(ref, x, 4, 2, 64, 64, codec=1)
+    check_contiguous(ref, x, 8, 3, 32, 128, codec=1)
+    check_contiguous(ref, x, 2, 8, 128, 32, codec=1)
+
+
+def test_codec_incompressible_chunks_stored_raw(ref):
+    """8-bit codes that are uniform over 0..255 do not compress: every chunk falls back to raw."""
+    g = torch.Generator().manual_seed(5)
+    x = torch.randint(0, 256, (1, 2, 2, 256, 128), generator=g).to(torch.float16)
+    x[:, 1, :, :, 0] = 0
+    x[:, 1, :, :, 1] = 255                       # V groups span exactly 0..255 -> code = value
+    x[:, 0, :, 0::128, :] = 0
+    x[:, 0, :, 1::128, :] = 255                  # and so do the K groups
+    got = check_contiguous(ref, x, 8, 8, 128, 128, codec=1)
+    plan = kvc.Plan(1, 1, 2, 128, 8, 8, 128, 128, 1, max_tokens=256)
+    assert got.size == plan.payload_size(256)[0]           # the all-raw bound is reached
+
+
+def test_codec_many_workgroups_scan(ref):
+    """Enough chunks that the chunk-offset scan spans many workgroups and look-back windows."""
+    x = kvgen.make_kv(31, 4, 8, 128, 128 * 40 + 17, torch.float16)        # 1312 chunks per section
+    check_contiguous(ref, x, 4, 4, 32, 32, codec=1)
+
+
+def test_codec_paged_and_batch(ref):
+    L, H, bt, P = 2, 2, 16, 40
+    lens = [16 * 20 + 3, 150]
+    dt = 1
+    cfg = ref.config(dtype=dt, layers=L, heads=H, bits_k=4, bits_v=4, group_k=32, group_v=32, codec=1)
+    plan = kvc.Plan(dt, L, H, 128, 4, 4, 32, 32, 1, max_tokens=max(lens), max_batch=2)
+    xs = [kvgen.make_kv(40 + i, L, H, 128, T, torch.float16) for i, T in enumerate(lens)]
+    tabs = [kvgen.block_table(3 + i, -(-T // bt), P) for i, T in enumerate(lens)]
+    pools = [kvgen.to_paged(x, t, bt, P).cuda() for x, t in zip(xs, tabs)]
+    tabd = [t.cuda() for t in tabs]
+    buf = gpu_compress(plan, [kvc.paged_request(p, t, T) for p, t, T in zip(pools, tabd, lens)], lens)
+    outs = [torch.zeros_like(p) for p in pools]
+    buf.decompress([kvc.paged_request(o, t, T) for o, t, T in zip(outs, tabd, lens)],
+                   torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    for i, T in enumerate(lens):
+        xu = kvgen.as_u16(xs[i])
+        lay = ref.contiguous_layout(H, T, 128)
+        want = ref.compress(cfg, xu[0, 0], xu[0, 1], lay, T)
+        got = buf.payload_of(i)
+        assert int(buf.status[i]) == 0
+        assert np.array_equal(got, want), (i, first_diff(got, want))
+        ru = np.zeros_like(xu)
+        assert ref.decompress(want, ru[0, 0], ru[0, 1], lay, cfg) == 0
+        assert ulp_distance_16(kvgen.as_u16(kvgen.from_paged(outs[i].cpu(), tabs[i], T)), ru).max() == 0
+
+
+def test_codec_corrupt_payload_is_reported(ref):
+    """A damaged directory or table sets a status bit; nothing faults and nothing hangs."""
+    T = 512
+    x = kvgen.make_kv(50, 1, 2, 128, T, torch.float16).cuda()
+    plan = kvc.Plan(1, 1, 2, 128, 4, 4, 32, 32, 1, max_tokens=T)
+    buf = gpu_compress(plan, [kvc.contiguous_request(x)], [T])
+    rc, _, _, _, _, sec = kvc.payload_inspect(buf.payload_of(0))
+    assert rc == 0
+    good = buf.payload.clone()
+    y = torch.zeros_like(x)
+    stream = torch.cuda.current_stream().cuda_stream
+    # directory entry 3 pushed far beyond the payload
+    buf.payload[sec[4] + 512 + 4 * 3: sec[4] + 512 + 4 * 3 + 4] = torch.tensor([255, 255, 255, 127], dtype=torch.uint8).cuda()
+    buf.decompress([kvc.contiguous_request(y)], stream)
+    torch.cuda.synchronize()
+    assert int(buf.status[0]) & kvc.DEV_BAD_CHUNK
+    # a code-length table that is not a prefix code
+    buf.payload.copy_(good)
+    buf.payload[sec[4]: sec[4] + 256] = 3
+    buf.decompress([kvc.contiguous_request(y)], stream)
+    torch.cuda.synchronize()
+    assert int(buf.status[0]) & kvc.DEV_BAD_TABLE
+    # sub-block bit counts that do not add up to the body size
+    buf.payload.copy_(good)
+    buf.payload[sec[6] + 2] = (int(buf.payload[sec[6] + 2]) + 64) % 256
+    buf.decompress([kvc.contiguous_request(y)], stream)
+    torch.cuda.synchronize()
+    assert int(buf.status[0]) & kvc.DEV_BAD_CHUNK
+    # and the intact payload still decodes
+    buf.payload.copy_(good)
+    buf.decompress([kvc.contiguous_request(y)], stream)
+    torch.cuda.synchronize()
+    assert int(buf.status[0]) == 0
+
+
+def test_codec_empty_request(ref):
+    x = kvgen.make_kv(51, 1, 2, 128, 8, torch.float16)
+    cfg = ref.config(layers=1, heads=2, bits_k=4, bits_v=4, codec=1)
+    xu = kvgen.as_u16(x)
+    want = ref.compress(cfg, xu[0, 0], xu[0, 1], ref.contiguous_layout(2, 8, 128), 0)
+    plan = kvc.Plan(1, 1, 2, 128, 4, 4, 32, 32, 1, max_tokens=8)
+    xd = x.cuda()
+    buf = gpu_compress(plan, [kvc.contiguous_request(xd, 0)], [0])
+    assert np.array_equal(buf.payload_of(0), want)
+    for codec in (0,):
+        cfg0 = ref.config(layers=1, heads=2, bits_k=4, bits_v=4, codec=codec)
+        want0 = ref.compress(cfg0, xu[0, 0], xu[0, 1], ref.contiguous_layout(2, 8, 128), 0)
+        plan0 = kvc.Plan(1, 1, 2, 128, 4, 4, 32, 32, codec, max_tokens=8)
+        buf0 = gpu_compress(plan0, [kvc.contiguous_request(xd, 0)], [0])
+        assert np.array_equal(buf0.payload_of(0), want0)
