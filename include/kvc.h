@@ -161,6 +161,15 @@ int kvc_payload_inspect(const void *header128, kvc_model *model, kvc_strategy *s
 /* Host-side check of a block table held in HOST memory (every entry in range). */
 int kvc_check_block_table(const int32_t *table, int64_t entries, int32_t num_phys_blocks);
 
+/*
+ * Measurement hook, for benchmarks only (process-global, not thread-safe).  While an array of
+ * `capacity` hipEvent_t handles is installed, every kvc_compress / kvc_decompress records,
+ * per request and on the call's stream, four events: before the set-up kernels (tables),
+ * before the K kernel, between the K and V kernels, and after the V kernel.  Returns the
+ * number of events recorded since the previous call; NULL uninstalls.
+ */
+int kvc_trace(void **hip_events, int32_t capacity);
+
 const char *kvc_status_string(int status);
 
 #ifdef __cplusplus

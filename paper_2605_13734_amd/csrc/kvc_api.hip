@@ -19,6 +19,23 @@ struct kvc_plan_s {
     size_t ws_state_off;        // offset of the scan state inside a request's workspace
 };
 
+// Optional measurement hook (kvc_trace): events recorded between the stages of a call.
+static hipEvent_t *g_trace = nullptr;
+static int g_trace_cap = 0, g_trace_n = 0;
+static void mark(hipStream_t s)
+{
+    if (g_trace && g_trace_n < g_trace_cap) hipEventRecord(g_trace[g_trace_n++], s);
+}
+
+extern "C" int kvc_trace(void **hip_events, int32_t capacity)
+{
+    const int recorded = g_trace_n;
+    g_trace = (hipEvent_t *)hip_events;
+    g_trace_cap = hip_events ? capacity : 0;
+    g_trace_n = 0;
+    return recorded;
+}
+
 static inline long long a16(long long n) { return (n + 15) & ~15ll; }
 static inline size_t a256(size_t n) { return (n + 255) & ~(size_t)255; }
 
@@ -353,8 +370,12 @@ extern "C" int kvc_compress(const kvc_plan_t *plan, const kvc_request *reqs, int
         QuantArgs qk = quant_args(plan, r, 0, pl, g, dev_status + i, true);
         QuantArgs qv = quant_args(plan, r, 1, pl, g, dev_status + i, true);
         if (!st.codec) {
+            mark(s);
+            mark(s);
             KVC_TRY(launch_compress_tensor(0, st.bits_k, st.group_k, dt, qk, s));
+            mark(s);
             KVC_TRY(launch_compress_tensor(1, st.bits_v, st.group_v, dt, qv, s));
+            mark(s);
             KVC_TRY(launch_fill_u32((uint32_t *)(out_bytes + i), (uint32_t)g.total, 1, s));
             KVC_TRY(launch_fill_u32((uint32_t *)(out_bytes + i) + 1, (uint32_t)((uint64_t)g.total >> 32), 1, s));
         } else {
@@ -366,9 +387,13 @@ extern "C" int kvc_compress(const kvc_plan_t *plan, const kvc_request *reqs, int
             KVC_TRY(launch_fill_u32((uint32_t *)ws, 0, 2 * 256, s));
             KVC_TRY(launch_fill_u32(ck.ws.ticket, 0, 64, s));
             KVC_TRY(launch_fill_u32((uint32_t *)ck.ws.state, 0, 2 * ck.total_wgs + 2, s));
+            mark(s);
             KVC_TRY(launch_coder_tables(st.bits_k, st.bits_v, st.group_k, st.group_v, dt, ck, cv, s));
+            mark(s);
             KVC_TRY(launch_encode_section(st.bits_k, st.group_k, dt, ck, s));
+            mark(s);
             KVC_TRY(launch_encode_section(st.bits_v, st.group_v, dt, cv, s));
+            mark(s);
             if (ck.total_chunks == 0) {
                 // empty request: no workgroup runs that could close the directory and header
                 put64((uint8_t *)hb.w + 40, (uint64_t)g.off_codes_k);
@@ -411,15 +436,23 @@ extern "C" int kvc_decompress(const kvc_plan_t *plan, const void *payload, const
         QuantArgs qk = quant_args(plan, r, 0, pl, g, dev_status + i, false);
         QuantArgs qv = quant_args(plan, r, 1, pl, g, dev_status + i, false);
         if (!st.codec) {
+            mark(s);
+            mark(s);
             KVC_TRY(launch_decompress_tensor(0, st.bits_k, st.group_k, dt, qk, s));
+            mark(s);
             KVC_TRY(launch_decompress_tensor(1, st.bits_v, st.group_v, dt, qv, s));
+            mark(s);
         } else {
             uint8_t *ws = (uint8_t *)workspace + (size_t)i * plan->ws_request;
             CoderArgs ck = coder_args(plan, qk, 0, pl, g, ws, cap, nullptr);
             CoderArgs cv = coder_args(plan, qv, 1, pl, g, ws, cap, nullptr);
+            mark(s);
             KVC_TRY(launch_decode_prepare(ck, s));
+            mark(s);
             KVC_TRY(launch_decode_section(st.bits_k, st.group_k, dt, ck, s));
+            mark(s);
             KVC_TRY(launch_decode_section(st.bits_v, st.group_v, dt, cv, s));
+            mark(s);
         }
     }
     return KVC_OK;

@@ -16,7 +16,8 @@ OK = 0
 DEV_BAD_BLOCK, DEV_BAD_HEADER, DEV_BAD_CHUNK, DEV_BAD_TABLE, DEV_SCAN_TIMEOUT = 1, 2, 4, 8, 16
 
 SYMBOLS = ["kvc_plan", "kvc_plan_free", "kvc_payload_size", "kvc_workspace_size", "kvc_compress",
-           "kvc_decompress", "kvc_payload_inspect", "kvc_check_block_table", "kvc_status_string"]
+           "kvc_decompress", "kvc_payload_inspect", "kvc_check_block_table", "kvc_status_string",
+           "kvc_trace"]
 
 
 class Strategy(C.Structure):
@@ -54,6 +55,9 @@ def load():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("libkvc.so is not built: run `python __graft_entry__.py` "
                                "(hipcc --offload-arch=gfx950) first; there is no CPU fallback")
+        # PyTorch ships its own HIP runtime under the same soname; it has to be in the process
+        # first so that libkvc binds to the runtime that owns torch's streams and memory.
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         L.kvc_plan.argtypes = [C.POINTER(Model), C.POINTER(Strategy), C.c_int64, C.c_int32,
                                C.POINTER(C.c_void_p)]
@@ -70,6 +74,7 @@ def load():
                                           C.POINTER(C.c_int64), C.POINTER(C.c_uint64),
                                           C.POINTER(C.c_uint64)]
         L.kvc_check_block_table.argtypes = [C.c_void_p, C.c_int64, C.c_int32]
+        L.kvc_trace.argtypes = [C.c_void_p, C.c_int32]
         L.kvc_status_string.argtypes = [C.c_int]
         L.kvc_status_string.restype = C.c_char_p
         _lib = L
@@ -168,6 +173,11 @@ def payload_inspect(header_bytes):
     sec = (C.c_uint64 * 10)()
     rc = load().kvc_payload_inspect(buf, C.byref(m), C.byref(s), C.byref(t), C.byref(total), sec)
     return rc, m, s, t.value, total.value, list(sec)
+
+
+def trace(events, capacity):
+    """kvc_trace: install (or, with None, remove) an array of hipEvent_t handles."""
+    return load().kvc_trace(events, capacity)
 
 
 def check_block_table(table_host, num_phys_blocks):
