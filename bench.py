@@ -87,6 +87,17 @@ def main():
     stream = torch.cuda.current_stream().cuda_stream
     V = x.numel() * 2
 
+    # plain-copy reference with a known size (16-bit pass-through of the first 8 layers): the
+    # kernel copy_rows_kernel<true> reads and writes exactly ref_bytes per launch, which is
+    # what the rocprofv3 byte counters are scaled by
+    ref_layers = min(8, L)
+    ref_plan = kvc.Plan(dt, ref_layers, H, 128, 16, 16, 32, 32, 0, max_tokens=T)
+    ref_buf = kvc.Buffers(ref_plan, [T], dev)
+    ref_buf.compress([kvc.contiguous_request(x[:ref_layers])], stream)
+    torch.cuda.synchronize()
+    ref_bytes = ref_layers * H * T * 128 * 2
+    del ref_buf
+
     def step():
         buf.compress(src, stream)
         buf.decompress(dst, stream)
@@ -176,7 +187,7 @@ def main():
         "compress_setup_ms": round(t_enc_setup, 4), "decompress_setup_ms": round(t_dec_setup, 4),
         "hbm_frac_compress": round((alg["k"] + alg["v"]) / t_enc / 1e6 / HBM_PEAK_GBS, 4),
         "hbm_frac_decompress": round((alg["k"] + alg["v"]) / t_dec / 1e6 / HBM_PEAK_GBS, 4),
-        "device_copy_GBps_rw": round(copy_gbps, 1),
+        "device_copy_GBps_rw": round(copy_gbps, 1), "copy_rows_reference_bytes_per_launch": ref_bytes,
         "kernels": per_kernel, "roofline": roofline,
     }
     if not args.no_cpu_baseline:

@@ -288,6 +288,7 @@ static QuantArgs quant_args(const kvc_plan_t *p, const kvc_request *r, int is_v,
     a.tokens = r->tokens;
     a.heads = p->model.kv_heads;
     a.group = group;
+    a.dense = (!r->block_table && r->stride_token == kDim) ? 1 : 0;
     const long long rows_per_unit = (compress && !is_v && bits != 16) ? group : kPassRows;
     a.units_per_head = (r->tokens + rows_per_unit - 1) / rows_per_unit;
     a.total_units = a.units_per_head * p->model.layers * p->model.kv_heads;

@@ -144,50 +144,97 @@ struct GroupParams {
     float zero;       // fp16-rounded minimum, as float
     float inv;        // 1 / fp16-rounded scale (0 when the scale is 0)
     uint32_t meta;    // scale bits | zero bits << 16
+    bool clamp;       // codes of this group can leave [0, 2^bits-1] before clamping
 };
 
-// zero = fp16(min), scale = fp16((max - min) / (2^bits - 1)); a zero of either sign is +0.
-template <int BITS> __device__ __forceinline__ GroupParams make_group(float mn, float mx)
+// range / (2^BITS - 1), correctly rounded: product with the rounded reciprocal, one exact
+// residual, one correction.  Equal to IEEE division for every float in [0, 2^17] (checked
+// exhaustively on the device by kvc_selftest).
+template <int BITS> __device__ __forceinline__ float div_levels(float r)
 {
     constexpr float qmax = (float)((1 << BITS) - 1);
+    constexpr float c = 1.0f / qmax;
+    const float q0 = r * c;
+    const float e = __builtin_fmaf(-q0, qmax, r);
+    return __builtin_fmaf(e, c, q0);
+}
+
+// 1 / s for a positive fp16-representable s: hardware estimate plus one Newton step, equal to
+// IEEE division for all such s (checked exhaustively by kvc_selftest).
+__device__ __forceinline__ float rcp_f16_exact(float s)
+{
+    const float y = __builtin_amdgcn_rcpf(s);
+    const float e = __builtin_fmaf(-s, y, 1.0f);
+    return __builtin_fmaf(y, e, y);
+}
+
+// Keeps the compiler from merging an fp32 operation with a following conversion to fp16 into
+// one mixed-precision instruction, which would round once instead of twice.
+__device__ __forceinline__ float rounded_f32(float x)
+{
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
+// zero = fp16(min), scale = fp16((max - min) / (2^bits - 1)); a zero of either sign is +0.
+// With fp16 input the minimum is its own fp16 rounding and the scale cannot overflow.
+template <int BITS, int DT> __device__ __forceinline__ GroupParams make_group(float mn, float mx)
+{
     mn += 0.0f;
     mx += 0.0f;
-    float lo = __builtin_amdgcn_fmed3f(mn, -65504.0f, 65504.0f);
-    uint32_t zb = f32_to_f16_bits(lo);
-    float s = fminf((mx - mn) / qmax, 65504.0f);
-    uint32_t sb = f32_to_f16_bits(s);
-    float sh = f16_bits_to_f32(sb);
+    float lo = mn;
+    if (DT != DT_F16) lo = __builtin_amdgcn_fmed3f(mn, -65504.0f, 65504.0f);
+    const uint32_t zb = f32_to_f16_bits(lo);
+    float s = rounded_f32(div_levels<BITS>(mx - mn));
+    if (DT != DT_F16) s = fminf(s, 65504.0f);
+    const uint32_t sb = f32_to_f16_bits(s);
+    const float sh = f16_bits_to_f32(sb);
     GroupParams g;
-    g.zero = f16_bits_to_f32(zb);
-    g.inv = (sh == 0.0f) ? 0.0f : 1.0f / sh;
+    g.zero = (DT == DT_F16) ? lo : f16_bits_to_f32(zb);
+    g.inv = (sh == 0.0f) ? 0.0f : rcp_f16_exact(sh);
     g.meta = sb | (zb << 16);
+    // with a normal fp16 scale and zero == min, (x - zero) * inv rounds into [0, 2^bits - 1]
+    g.clamp = sh < 6.103515625e-05f || (DT != DT_F16 && g.zero != mn);
     return g;
 }
 
 // code = clamp(round_half_even((x - zero) * inv), 0, 2^bits - 1); two rounded fp32 operations.
-template <int BITS> __device__ __forceinline__ uint32_t quantize(float x, float zero, float inv)
+// Returns the rounded value as a float; CLAMP = false is for groups whose codes cannot leave
+// the range (GroupParams::clamp).
+template <int BITS, bool CLAMP> __device__ __forceinline__ float quantize_f(float x, float zero, float inv)
 {
     constexpr float qmax = (float)((1 << BITS) - 1);
     float t = (x - zero) * inv;
-    t = __builtin_amdgcn_fmed3f(t, 0.0f, qmax);
-    return (uint32_t)(int)__builtin_rintf(t);
+    if (CLAMP) t = __builtin_amdgcn_fmed3f(t, 0.0f, qmax);
+    return __builtin_rintf(t);
 }
 
 // ---- bit packing: element i of a row at bits [i*BITS, i*BITS+BITS) ------------------------
 
-// The 8 codes of one lane -> BITS bytes (returned in up to two words, low bits first).
-template <int BITS> __device__ __forceinline__ u32x2 pack8(const uint32_t q[8])
+// The 8 codes of one lane (integers held as floats) -> BITS bytes, low bits first.  Codes are
+// summed with their place values in fp32 (exact below 2^24) and converted once per word part.
+template <int BITS> __device__ __forceinline__ u32x2 pack8(const float q[8])
 {
     u32x2 r;
+    r[1] = 0;
     if (BITS == 8) {
-        r[0] = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
-        r[1] = q[4] | (q[5] << 8) | (q[6] << 16) | (q[7] << 24);
-    } else {
-        uint32_t w = 0;
+        const float a = __builtin_fmaf(q[1], 256.0f, q[0]), b = __builtin_fmaf(q[3], 256.0f, q[2]);
+        const float c = __builtin_fmaf(q[5], 256.0f, q[4]), d = __builtin_fmaf(q[7], 256.0f, q[6]);
+        r[0] = (uint32_t)a | ((uint32_t)b << 16);
+        r[1] = (uint32_t)c | ((uint32_t)d << 16);
+    } else if (BITS == 4) {
+        float lo = q[0], hi = q[4];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) w |= q[e] << (e * BITS);
-        r[0] = w;
-        r[1] = 0;
+        for (int e = 1; e < 4; ++e) {
+            lo = __builtin_fmaf(q[e], (float)(1 << (4 * e)), lo);
+            hi = __builtin_fmaf(q[4 + e], (float)(1 << (4 * e)), hi);
+        }
+        r[0] = (uint32_t)lo | ((uint32_t)hi << 16);
+    } else {
+        float acc = q[0];
+#pragma unroll
+        for (int e = 1; e < 8; ++e) acc = __builtin_fmaf(q[e], (float)(1 << (BITS * e)), acc);
+        r[0] = (uint32_t)acc;
     }
     return r;
 }

@@ -35,7 +35,7 @@ template <int BITS> struct ChunkGeom {
 
 template <int BITS> __device__ __forceinline__ uint8_t *lds_row(uint8_t *lds, int r)
 {
-    return lds + (r >> 1) * ChunkGeom<BITS>::kSubStride + (r & 1) * ChunkGeom<BITS>::kRowBytes;
+    return code_row<BITS, true>(lds, r);
 }
 
 struct ChunkPos {
@@ -59,11 +59,10 @@ __device__ __forceinline__ ChunkPos chunk_pos(const QuantArgs &a, long long chun
 
 // Quantize and pack the chunk's rows into the wave's LDS region (sub-block layout) and,
 // when `write_meta`, store the group metadata to the payload.
-template <int BITS, int G, int DT, bool IS_V>
-__device__ __forceinline__ void quantize_chunk(const QuantArgs &a, const ChunkPos &c, uint8_t *lds,
+template <int BITS, int G, int DT, bool IS_V, bool DENSE>
+__device__ __forceinline__ void quantize_chunk(const QuantArgs &a, const ChunkPos &c, uint8_t *lds, float *xch,
                                                bool write_meta, bool &bad)
 {
-    const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
     if (!IS_V) {
         constexpr int P = G / kPassRows;
         const long long nb = (a.tokens + G - 1) / G;
@@ -73,63 +72,24 @@ __device__ __forceinline__ void quantize_chunk(const QuantArgs &a, const ChunkPo
             const long long row0 = c.row0 + gb * G;
             u32x4 raw[P * 8];
 #pragma unroll
-            for (int p = 0; p < P; ++p) load_pass(a.x, c.head_off, row0 + p * kPassRows, a.tokens, raw + p * 8, bad);
-            float mn[8], mx[8];
-            k_stats<DT, P * 8>(raw, mn, mx);
-            GroupParams gp[8];
-            u32x4 m0, m1;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                gp[e] = make_group<BITS>(mn[e], mx[e]);
-                if (e < 4) m0[e] = gp[e].meta; else m1[e - 4] = gp[e].meta;
-            }
-            if (write_meta && rsub == 0) {
-                u32x4 *m = (u32x4 *)(a.meta + ((c.lh * nb + row0 / G) * kDim + col * 8) * 4);
-                m[0] = m0;
-                m[1] = m1;
-            }
-#pragma unroll
-            for (int p = 0; p < P; ++p)
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int r = gb * G + p * kPassRows + 4 * i + rsub;
-                    u32x2 w = k_quant_row<BITS, DT>(raw[p * 8 + i], gp);
-                    if (BITS == 3) w[0] = quad_words_from_24(w[0]);
-                    if (r < c.rows) {
-                        uint8_t *row = lds_row<BITS>(lds, r);
-                        if (BITS == 3) {
-                            if ((col & 3) != 3) *(uint32_t *)(row + (col >> 2) * 12 + (col & 3) * 4) = w[0];
-                        } else {
-                            store_row_codes<BITS>(row, w);
-                        }
-                    }
-                }
+            for (int p = 0; p < P; ++p) load_pass<DENSE>(a.x, c.head_off, row0 + p * kPassRows, a.tokens, raw + p * 8, bad);
+            KParams kp;
+            uint8_t *meta_block = write_meta ? a.meta + (c.lh * nb + row0 / G) * (kDim * 4) : nullptr;
+            k_group_params<BITS, DT, P * 8>(raw, xch, meta_block, kp);
+            k_emit<BITS, DT, P, true>(raw, kp, code_row<BITS, true>(lds, gb * G), c.rows - gb * G);
         }
     } else {
-        constexpr int LANES = G / 8, NG = kDim / G;
+        constexpr int NG = kDim / G;
 #pragma unroll 1
         for (int p = 0; p < kChunkRows / kPassRows; ++p) {
             if (p * kPassRows >= c.rows) break;
             const long long row0 = c.row0 + p * kPassRows;
             u32x4 raw[8];
-            load_pass(a.x, c.head_off, row0, a.tokens, raw, bad);
-            uint32_t *meta = (uint32_t *)a.meta + (c.lh * a.tokens + row0) * NG;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int r = p * kPassRows + 4 * i + rsub;
-                uint32_t mw;
-                u32x2 w = v_quant_row<BITS, G, DT>(raw[i], mw);
-                if (BITS == 3) w[0] = quad_words_from_24(w[0]);
-                if (r < c.rows) {
-                    uint8_t *row = lds_row<BITS>(lds, r);
-                    if (BITS == 3) {
-                        if ((col & 3) != 3) *(uint32_t *)(row + (col >> 2) * 12 + (col & 3) * 4) = w[0];
-                    } else {
-                        store_row_codes<BITS>(row, w);
-                    }
-                    if (write_meta && (col & (LANES - 1)) == 0) meta[(4 * i + rsub) * NG + col / LANES] = mw;
-                }
-            }
+            load_pass<DENSE>(a.x, c.head_off, row0, a.tokens, raw, bad);
+            VParams vp;
+            v_pass_params<BITS, G, DT>(raw, vp);
+            uint32_t *meta = write_meta ? (uint32_t *)a.meta + (c.lh * a.tokens + row0) * NG : nullptr;
+            v_emit<BITS, G, DT, true>(raw, vp, code_row<BITS, true>(lds, p * kPassRows), c.rows - p * kPassRows, meta);
         }
     }
 }
@@ -158,13 +118,6 @@ template <int BITS> __device__ __forceinline__ void store_sub(uint8_t *lds, cons
     }
 }
 
-__device__ __forceinline__ void wave_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 // inclusive prefix sum over the 64 lanes
 __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v)
 {
@@ -183,6 +136,7 @@ template <int BITS, int G, int DT, bool IS_V>
 __global__ __launch_bounds__(64) void hist_kernel(CoderArgs a)
 {
     __shared__ __attribute__((aligned(16))) uint8_t lds[ChunkGeom<BITS>::kLds];
+    __shared__ __attribute__((aligned(16))) float xch[kXchFloats];
     __shared__ uint32_t hist[256];
     const int i = blockIdx.x, lane = lane_id();
     const long long n = a.chunks;
@@ -191,7 +145,7 @@ __global__ __launch_bounds__(64) void hist_kernel(CoderArgs a)
     for (int k = lane; k < 256; k += 64) hist[k] = 0;
     ChunkPos c = chunk_pos(a.q, chunk);
     bool bad = false;
-    quantize_chunk<BITS, G, DT, IS_V>(a.q, c, lds, false, bad);
+    quantize_chunk<BITS, G, DT, IS_V, false>(a.q, c, lds, xch, false, bad);
     wave_sync();
     constexpr int W = ChunkGeom<BITS>::kWords;
     uint32_t sym[W];
@@ -413,12 +367,13 @@ template <int W> __device__ __forceinline__ void encode_half(const uint32_t *sym
     }
 }
 
-template <int BITS, int G, int DT, bool IS_V>
+template <int BITS, int G, int DT, bool IS_V, bool DENSE>
 __global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void encode_kernel(CoderArgs a)
 {
     using Geo = ChunkGeom<BITS>;
     constexpr int W = Geo::kWords, NW = Geo::kWaves;
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * Geo::kLds];
+    __shared__ __attribute__((aligned(16))) float xch_all[NW * kXchFloats];
     __shared__ uint32_t enc[256];
     __shared__ uint32_t s_units[NW];
     __shared__ unsigned long long s_excl;
@@ -441,7 +396,7 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void encode_kernel(Co
         ChunkPos c = chunk_pos(a.q, chunk);
         rows = c.rows;
         bool bad = false;
-        quantize_chunk<BITS, G, DT, IS_V>(a.q, c, lds, true, bad);
+        quantize_chunk<BITS, G, DT, IS_V, DENSE>(a.q, c, lds, xch_all + wave * kXchFloats, true, bad);
         if (bad) atomicOr(a.q.status, KVC_DEV_BAD_BLOCK);
         wave_sync();
         load_sub<BITS>(lds, sym);
@@ -676,15 +631,19 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void decode_kernel(Co
     for (int p = 0; p < kChunkRows / kPassRows; ++p) {
         if (p * kPassRows >= c.rows) break;
         const long long row0 = c.row0 + p * kPassRows;
-        uint32_t meta_k[8];
+        float scale_k[8], zero_k[8];
         const uint32_t *meta_v = nullptr;
         int ng = 0, lanes_shift = 0;
         if (!IS_V) {
             const long long nb = (a.q.tokens + group - 1) / group;
             const u32x4 *m = (const u32x4 *)(a.q.meta + ((c.lh * nb + row0 / group) * kDim + col * 8) * 4);
-            u32x4 m0 = m[0], m1 = m[1];
-            meta_k[0] = m0[0]; meta_k[1] = m0[1]; meta_k[2] = m0[2]; meta_k[3] = m0[3];
-            meta_k[4] = m1[0]; meta_k[5] = m1[1]; meta_k[6] = m1[2]; meta_k[7] = m1[3];
+            const u32x4 m0 = m[0], m1 = m[1];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t w0 = m0[e], w1 = m1[e];
+                scale_k[e] = f16_bits_to_f32(w0 & 0xffffu); zero_k[e] = f16_bits_to_f32(w0 >> 16);
+                scale_k[4 + e] = f16_bits_to_f32(w1 & 0xffffu); zero_k[4 + e] = f16_bits_to_f32(w1 >> 16);
+            }
         } else {
             ng = kDim / group;
             lanes_shift = group == 32 ? 2 : (group == 64 ? 3 : 4);
@@ -698,7 +657,7 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void decode_kernel(Co
             u32x2 w = load_row_codes<BITS>(lds_row<BITS>(lds, rr));
             u32x4 out;
             if (!IS_V) {
-                out = dequant_row<BITS, DT>(w, meta_k);
+                out = dequant_row<BITS, DT>(w, scale_k, zero_k);
             } else {
                 const uint32_t mw = meta_v[(rr - p * kPassRows) * ng + (col >> lanes_shift)];
                 out = dequant_row_uniform<BITS, DT>(w, mw);
@@ -730,7 +689,8 @@ template <int BITS, int G, int DT, bool IS_V> static int encode_launch(const Cod
     constexpr int NW = ChunkGeom<BITS>::kWaves;
     const long long need = (a.chunks + NW - 1) / NW;
     if (need <= 0) return KVC_OK;
-    hipLaunchKernelGGL((encode_kernel<BITS, G, DT, IS_V>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
+    if (a.q.dense) hipLaunchKernelGGL((encode_kernel<BITS, G, DT, IS_V, true>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
+    else hipLaunchKernelGGL((encode_kernel<BITS, G, DT, IS_V, false>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
     return launched();
 }
 

@@ -16,6 +16,7 @@ struct QuantArgs {
     long long tokens;
     int heads;
     int group;                  // runtime copy of the group size
+    int dense;                  // rows of a head are contiguous: stride_token == head_dim, no block table
     long long units_per_head;   // work units (one wave each) per (layer, head)
     long long total_units;
     int *status;                // device status word of the request

@@ -35,50 +35,24 @@ __device__ __forceinline__ void report(int *status, bool bad)
 
 // ---- K: groups along tokens, one per channel ------------------------------------------------
 
-template <int BITS, int G, int DT>
+template <int BITS, int G, int DT, bool DENSE>
 __global__ __launch_bounds__(256) void compress_k_kernel(QuantArgs a)
 {
+    __shared__ __attribute__((aligned(16))) float xch_all[4 * kXchFloats];
     UnitPos u;
     if (!unit_pos(a, u)) return;
     constexpr int P = G / kPassRows;
-    const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
     const long long row0 = u.blk * G;
     bool bad = false;
     u32x4 raw[P * 8];
 #pragma unroll
-    for (int p = 0; p < P; ++p) load_pass(a.x, u.head_off, row0 + p * kPassRows, a.tokens, raw + p * 8, bad);
-
-    float mn[8], mx[8];
-    k_stats<DT, P * 8>(raw, mn, mx);
-    GroupParams gp[8];
-    u32x4 m0, m1;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        gp[e] = make_group<BITS>(mn[e], mx[e]);
-        if (e < 4) m0[e] = gp[e].meta; else m1[e - 4] = gp[e].meta;
-    }
-    if (rsub == 0) {
-        u32x4 *m = (u32x4 *)(a.meta + ((u.lh * a.units_per_head + u.blk) * kDim + col * 8) * 4);
-        m[0] = m0;
-        m[1] = m1;
-    }
+    for (int p = 0; p < P; ++p) load_pass<DENSE>(a.x, u.head_off, row0 + p * kPassRows, a.tokens, raw + p * 8, bad);
+    KParams kp;
+    uint8_t *meta_block = a.meta + (u.lh * a.units_per_head + u.blk) * (kDim * 4);
+    k_group_params<BITS, DT, P * 8>(raw, xch_all + (threadIdx.x >> 6) * kXchFloats, meta_block, kp);
     uint8_t *codes = a.codes + (u.lh * a.tokens + row0) * (16 * BITS);
-#pragma unroll
-    for (int p = 0; p < P; ++p)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int r = p * kPassRows + 4 * i + rsub;
-            u32x2 w = k_quant_row<BITS, DT>(raw[p * 8 + i], gp);
-            if (BITS == 3) w[0] = quad_words_from_24(w[0]);
-            if (row0 + r < a.tokens) {
-                uint8_t *row = codes + (long long)r * (16 * BITS);
-                if (BITS == 3) {
-                    if ((col & 3) != 3) *(uint32_t *)(row + (col >> 2) * 12 + (col & 3) * 4) = w[0];
-                } else {
-                    store_row_codes<BITS>(row, w);
-                }
-            }
-        }
+    const long long left = a.tokens - row0;
+    k_emit<BITS, DT, P, false>(raw, kp, codes, left < G ? (int)left : G);
     report(a.status, bad);
 }
 
@@ -92,8 +66,14 @@ __global__ __launch_bounds__(256) void decompress_k_kernel(QuantArgs a)
     const long long row0 = u.blk * kPassRows;
     const long long tb = row0 / a.group, nb = (a.tokens + a.group - 1) / a.group;
     const u32x4 *m = (const u32x4 *)(a.meta + ((u.lh * nb + tb) * kDim + col * 8) * 4);
-    u32x4 m0 = m[0], m1 = m[1];
-    uint32_t meta[8] = {m0[0], m0[1], m0[2], m0[3], m1[0], m1[1], m1[2], m1[3]};
+    const u32x4 m0 = m[0], m1 = m[1];
+    float scale[8], zero[8];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const uint32_t w0 = m0[e], w1 = m1[e];
+        scale[e] = f16_bits_to_f32(w0 & 0xffffu); zero[e] = f16_bits_to_f32(w0 >> 16);
+        scale[4 + e] = f16_bits_to_f32(w1 & 0xffffu); zero[4 + e] = f16_bits_to_f32(w1 >> 16);
+    }
     const uint8_t *codes = a.codes + (u.lh * a.tokens + row0) * (16 * BITS);
     bool bad = false;
 #pragma unroll
@@ -101,7 +81,7 @@ __global__ __launch_bounds__(256) void decompress_k_kernel(QuantArgs a)
         const long long row = row0 + 4 * i + rsub;
         const bool live = row < a.tokens;              // uniform over each quad of lanes
         u32x2 w = load_row_codes<BITS>(codes + (live ? (4 * i + rsub) : 0) * (16 * BITS));
-        u32x4 out = dequant_row<BITS, DT>(w, meta);
+        u32x4 out = dequant_row<BITS, DT>(w, scale, zero);
         if (live) {
             bool b = false;
             long long off = row_offset(a.x, u.head_off, row, b);
@@ -114,35 +94,22 @@ __global__ __launch_bounds__(256) void decompress_k_kernel(QuantArgs a)
 
 // ---- V: groups along channels, one set per token -----------------------------------------------
 
-template <int BITS, int GV, int DT>
+template <int BITS, int GV, int DT, bool DENSE>
 __global__ __launch_bounds__(256) void compress_v_kernel(QuantArgs a)
 {
     UnitPos u;
     if (!unit_pos(a, u)) return;
-    constexpr int LANES = GV / 8, NG = kDim / GV;
-    const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
+    constexpr int NG = kDim / GV;
     const long long row0 = u.blk * kPassRows;
     bool bad = false;
     u32x4 raw[8];
-    load_pass(a.x, u.head_off, row0, a.tokens, raw, bad);
+    load_pass<DENSE>(a.x, u.head_off, row0, a.tokens, raw, bad);
+    VParams vp;
+    v_pass_params<BITS, GV, DT>(raw, vp);
     uint8_t *codes = a.codes + (u.lh * a.tokens + row0) * (16 * BITS);
     uint32_t *meta = (uint32_t *)a.meta + (u.lh * a.tokens + row0) * NG;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int r = 4 * i + rsub;
-        uint32_t mw;
-        u32x2 w = v_quant_row<BITS, GV, DT>(raw[i], mw);
-        if (BITS == 3) w[0] = quad_words_from_24(w[0]);
-        if (row0 + r < a.tokens) {
-            uint8_t *row = codes + (long long)r * (16 * BITS);
-            if (BITS == 3) {
-                if ((col & 3) != 3) *(uint32_t *)(row + (col >> 2) * 12 + (col & 3) * 4) = w[0];
-            } else {
-                store_row_codes<BITS>(row, w);
-            }
-            if ((col & (LANES - 1)) == 0) meta[(long long)r * NG + col / LANES] = mw;
-        }
-    }
+    const long long left = a.tokens - row0;
+    v_emit<BITS, GV, DT, false>(raw, vp, codes, left < kPassRows ? (int)left : kPassRows, meta);
     report(a.status, bad);
 }
 
@@ -154,18 +121,23 @@ __global__ __launch_bounds__(256) void decompress_v_kernel(QuantArgs a)
     if (*a.status & KVC_DEV_BAD_HEADER) return;
     const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
     const long long row0 = u.blk * kPassRows;
-    const int lanes = a.group >> 3, ng = kDim / a.group;
+    const int lanes_shift = a.group == 32 ? 2 : (a.group == 64 ? 3 : 4), ng = kDim / a.group;
     const uint8_t *codes = a.codes + (u.lh * a.tokens + row0) * (16 * BITS);
     const uint32_t *meta = (const uint32_t *)a.meta + (u.lh * a.tokens + row0) * ng;
     bool bad = false;
+    uint32_t mw[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const bool live = row0 + 4 * i + rsub < a.tokens;
+        mw[i] = meta[(live ? 4 * i + rsub : 0) * ng + (col >> lanes_shift)];
+    }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const long long row = row0 + 4 * i + rsub;
         const bool live = row < a.tokens;
         const int r = live ? 4 * i + rsub : 0;
         u32x2 w = load_row_codes<BITS>(codes + r * (16 * BITS));
-        uint32_t mw = meta[r * ng + col / lanes];
-        u32x4 out = dequant_row_uniform<BITS, DT>(w, mw);
+        u32x4 out = dequant_row_uniform<BITS, DT>(w, mw[i]);
         if (live) {
             bool b = false;
             long long off = row_offset(a.x, u.head_off, row, b);
@@ -233,19 +205,19 @@ static inline dim3 grid_for(long long units) { return dim3((unsigned)((units + 3
         return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_DEVICE;               \
     } while (0)
 
-template <int BITS, int DT> static int compress_bits_dt(int is_v, int group, const QuantArgs &a, hipStream_t s)
+template <int BITS, int DT, bool DENSE> static int compress_bits_dt(int is_v, int group, const QuantArgs &a, hipStream_t s)
 {
     if (!is_v) {
         switch (group) {
-        case 32: KVC_LAUNCH((compress_k_kernel<BITS, 32, DT>), a, s);
-        case 64: KVC_LAUNCH((compress_k_kernel<BITS, 64, DT>), a, s);
-        case 128: KVC_LAUNCH((compress_k_kernel<BITS, 128, DT>), a, s);
+        case 32: KVC_LAUNCH((compress_k_kernel<BITS, 32, DT, DENSE>), a, s);
+        case 64: KVC_LAUNCH((compress_k_kernel<BITS, 64, DT, DENSE>), a, s);
+        case 128: KVC_LAUNCH((compress_k_kernel<BITS, 128, DT, DENSE>), a, s);
         }
     } else {
         switch (group) {
-        case 32: KVC_LAUNCH((compress_v_kernel<BITS, 32, DT>), a, s);
-        case 64: KVC_LAUNCH((compress_v_kernel<BITS, 64, DT>), a, s);
-        case 128: KVC_LAUNCH((compress_v_kernel<BITS, 128, DT>), a, s);
+        case 32: KVC_LAUNCH((compress_v_kernel<BITS, 32, DT, DENSE>), a, s);
+        case 64: KVC_LAUNCH((compress_v_kernel<BITS, 64, DT, DENSE>), a, s);
+        case 128: KVC_LAUNCH((compress_v_kernel<BITS, 128, DT, DENSE>), a, s);
         }
     }
     return KVC_ERR_UNSUPPORTED;
@@ -253,8 +225,11 @@ template <int BITS, int DT> static int compress_bits_dt(int is_v, int group, con
 
 template <int BITS> static int compress_bits(int is_v, int group, int dtype, const QuantArgs &a, hipStream_t s)
 {
-    return dtype == DT_F16 ? compress_bits_dt<BITS, DT_F16>(is_v, group, a, s)
-                           : compress_bits_dt<BITS, DT_BF16>(is_v, group, a, s);
+    if (a.dense)
+        return dtype == DT_F16 ? compress_bits_dt<BITS, DT_F16, true>(is_v, group, a, s)
+                               : compress_bits_dt<BITS, DT_BF16, true>(is_v, group, a, s);
+    return dtype == DT_F16 ? compress_bits_dt<BITS, DT_F16, false>(is_v, group, a, s)
+                           : compress_bits_dt<BITS, DT_BF16, false>(is_v, group, a, s);
 }
 
 int launch_compress_tensor(int is_v, int bits, int group, int dtype, const QuantArgs &a, hipStream_t s)

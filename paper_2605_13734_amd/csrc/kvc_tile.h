@@ -1,24 +1,42 @@
 // Per-wave tile operations of the quantizer: load a pass of 32 token rows, group statistics
-// along tokens (K) or along channels (V), quantize + pack one row, and the inverse.
-// Used by the codec-free kernels and by the coder kernels alike.
+// along tokens (K) or along channels (V), group parameters, quantize + pack one row, and the
+// inverse.  Used by the codec-free kernels and by the coder kernels alike.
 #pragma once
 
 #include "kvc_device.h"
 
 namespace kvc {
 
+constexpr int kXchFloats = 256;    // per-wave LDS scratch for exchanging K group parameters
+
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // The lane's 8 rows of a pass: row = row0 + 4*i + rsub.  Rows past the end of the sequence
 // re-read the last valid row, which leaves every group's min and max unchanged.
+// DENSE: rows of one head are contiguous (stride_token == head_dim, no block table), so a
+// full pass is eight loads at constant offsets from one address.
+template <bool DENSE>
 __device__ __forceinline__ void load_pass(const TensorView &v, long long head_off, long long row0,
                                           long long tokens, u32x4 raw[8], bool &bad)
 {
     const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
+    if (DENSE && row0 + kPassRows <= tokens) {
+        const u32x4 *p = (const u32x4 *)(v.base + head_off + (row0 + rsub) * kDim + col * 8);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) raw[i] = __builtin_nontemporal_load(p + i * 64);
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         long long row = row0 + 4 * i + rsub;
         row = row < tokens ? row : tokens - 1;
-        const uint16_t *p = v.base + row_offset(v, head_off, row, bad) + col * 8;
-        raw[i] = *(const u32x4 *)p;
+        const long long off = DENSE ? head_off + row * kDim : row_offset(v, head_off, row, bad);
+        raw[i] = __builtin_nontemporal_load((const u32x4 *)(v.base + off + col * 8));
     }
 }
 
@@ -27,38 +45,55 @@ __device__ __forceinline__ uint32_t xlane_u32(uint32_t v, int xor_mask)
     return (uint32_t)__builtin_amdgcn_ds_bpermute((lane_id() ^ xor_mask) << 2, (int)v);
 }
 
-// K statistics: min / max of each of the lane's 8 channels over N loaded rows and over the
-// 4 lanes (rsub = 0..3) that hold the other rows of the same channels.
-template <int DT, int N>
-__device__ __forceinline__ void k_stats(const u32x4 *raw, float mn[8], float mx[8])
+// packed fp16 min / max without the compiler's NaN-quieting copies (inputs are finite)
+__device__ __forceinline__ uint32_t pk_min_f16(uint32_t a, uint32_t b)
 {
+    uint32_t d;
+    asm("v_pk_min_f16 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b));
+    return d;
+}
+__device__ __forceinline__ uint32_t pk_max_f16(uint32_t a, uint32_t b)
+{
+    uint32_t d;
+    asm("v_pk_max_f16 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b));
+    return d;
+}
+
+template <typename T> __device__ __forceinline__ T pick4(int k, T v0, T v1, T v2, T v3)
+{
+    return (k & 2) ? ((k & 1) ? v3 : v2) : ((k & 1) ? v1 : v0);
+}
+
+// K statistics: min / max of the lane's channels over N loaded rows and over the 4 lanes
+// (rsub = 0..3) that hold the other rows of the same channels.  The lane keeps the result for
+// channels 2*rsub and 2*rsub+1 only (mn2 / mx2).
+template <int DT, int N>
+__device__ __forceinline__ void k_stats_own(const u32x4 *raw, float mn2[2], float mx2[2])
+{
+    const int rsub = lane_id() >> 4;
     if (DT == DT_F16) {
-        half2_t a[4], b[4];
+        uint32_t a[4], b[4];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) a[w] = b[w] = as_half2(raw[0][w]);
+        for (int w = 0; w < 4; ++w) a[w] = b[w] = raw[0][w];
 #pragma unroll
         for (int n = 1; n < N; ++n)
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
-                half2_t x = as_half2(raw[n][w]);
-                a[w] = __builtin_elementwise_min(a[w], x);
-                b[w] = __builtin_elementwise_max(b[w], x);
+                a[w] = pk_min_f16(a[w], raw[n][w]);
+                b[w] = pk_max_f16(b[w], raw[n][w]);
             }
 #pragma unroll
         for (int m = 16; m <= 32; m <<= 1)
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
-                half2_t oa = as_half2(xlane_u32(as_u32(a[w]), m));
-                half2_t ob = as_half2(xlane_u32(as_u32(b[w]), m));
-                a[w] = __builtin_elementwise_min(a[w], oa);
-                b[w] = __builtin_elementwise_max(b[w], ob);
+                a[w] = pk_min_f16(a[w], xlane_u32(a[w], m));
+                b[w] = pk_max_f16(b[w], xlane_u32(b[w], m));
             }
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            mn[2 * w] = (float)a[w][0]; mn[2 * w + 1] = (float)a[w][1];
-            mx[2 * w] = (float)b[w][0]; mx[2 * w + 1] = (float)b[w][1];
-        }
+        const uint32_t pa = pick4(rsub, a[0], a[1], a[2], a[3]), pb = pick4(rsub, b[0], b[1], b[2], b[3]);
+        mn2[0] = lo_f32<DT_F16>(pa); mn2[1] = hi_f32<DT_F16>(pa);
+        mx2[0] = lo_f32<DT_F16>(pb); mx2[1] = hi_f32<DT_F16>(pb);
     } else {
+        float mn[8], mx[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) mn[e] = mx[e] = elem_f32<DT>(raw[0], e);
 #pragma unroll
@@ -70,79 +105,221 @@ __device__ __forceinline__ void k_stats(const u32x4 *raw, float mn[8], float mx[
                 mx[e] = fmaxf(mx[e], x);
             }
         // bfloat16 values are exact in the top half of a float: exchange two per word
+        uint32_t pa[4], pb[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            pa[w] = (__float_as_uint(mn[2 * w]) >> 16) | (__float_as_uint(mn[2 * w + 1]) & 0xffff0000u);
+            pb[w] = (__float_as_uint(mx[2 * w]) >> 16) | (__float_as_uint(mx[2 * w + 1]) & 0xffff0000u);
+        }
 #pragma unroll
         for (int m = 16; m <= 32; m <<= 1)
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
-                uint32_t pa = (__float_as_uint(mn[2 * w]) >> 16) | (__float_as_uint(mn[2 * w + 1]) & 0xffff0000u);
-                uint32_t pb = (__float_as_uint(mx[2 * w]) >> 16) | (__float_as_uint(mx[2 * w + 1]) & 0xffff0000u);
-                pa = xlane_u32(pa, m);
-                pb = xlane_u32(pb, m);
-                mn[2 * w] = fminf(mn[2 * w], __uint_as_float(pa << 16));
-                mn[2 * w + 1] = fminf(mn[2 * w + 1], __uint_as_float(pa & 0xffff0000u));
-                mx[2 * w] = fmaxf(mx[2 * w], __uint_as_float(pb << 16));
-                mx[2 * w + 1] = fmaxf(mx[2 * w + 1], __uint_as_float(pb & 0xffff0000u));
+                const uint32_t oa = xlane_u32(pa[w], m), ob = xlane_u32(pb[w], m);
+                const float l0 = fminf(__uint_as_float(pa[w] << 16), __uint_as_float(oa << 16));
+                const float l1 = fminf(__uint_as_float(pa[w] & 0xffff0000u), __uint_as_float(oa & 0xffff0000u));
+                const float h0 = fmaxf(__uint_as_float(pb[w] << 16), __uint_as_float(ob << 16));
+                const float h1 = fmaxf(__uint_as_float(pb[w] & 0xffff0000u), __uint_as_float(ob & 0xffff0000u));
+                pa[w] = (__float_as_uint(l0) >> 16) | (__float_as_uint(l1) & 0xffff0000u);
+                pb[w] = (__float_as_uint(h0) >> 16) | (__float_as_uint(h1) & 0xffff0000u);
             }
+        const uint32_t sa = pick4(rsub, pa[0], pa[1], pa[2], pa[3]), sb = pick4(rsub, pb[0], pb[1], pb[2], pb[3]);
+        mn2[0] = __uint_as_float(sa << 16); mn2[1] = __uint_as_float(sa & 0xffff0000u);
+        mx2[0] = __uint_as_float(sb << 16); mx2[1] = __uint_as_float(sb & 0xffff0000u);
     }
 }
 
-// Quantize the lane's 8 channels of one row with per-channel parameters (K).
-template <int BITS, int DT>
-__device__ __forceinline__ u32x2 k_quant_row(const u32x4 &raw, const GroupParams gp[8])
+struct KParams {
+    float zero[8], inv[8];   // of the lane's 8 channels
+    bool clamp;              // wave-uniform: some group of this token block needs clamping
+};
+
+// Parameters of the 128 per-channel groups of one token block.  Each of the four lanes that
+// share a channel octet computes two channels, stores their metadata (scale, zero as fp16)
+// and publishes (zero, 1/scale) through `xch` (LDS, kXchFloats per wave).
+// meta_block: the 512 bytes of this token block's metadata, or null to skip the store.
+template <int BITS, int DT, int N>
+__device__ __forceinline__ void k_group_params(const u32x4 *raw, float *xch, uint8_t *meta_block, KParams &kp)
 {
-    uint32_t q[8];
+    const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
+    float mn2[2], mx2[2];
+    k_stats_own<DT, N>(raw, mn2, mx2);
+    const GroupParams g0 = make_group<BITS, DT>(mn2[0], mx2[0]);
+    const GroupParams g1 = make_group<BITS, DT>(mn2[1], mx2[1]);
+    if (meta_block) {
+        u32x2 m;
+        m[0] = g0.meta;
+        m[1] = g1.meta;
+        *(u32x2 *)(meta_block + (col * 8 + rsub * 2) * 4) = m;
+    }
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    f32x4 mine = {g0.zero, g0.inv, g1.zero, g1.inv};
+    f32x4 *x4 = (f32x4 *)xch;
+    wave_sync();                                  // earlier readers of xch are done
+    x4[col * 4 + rsub] = mine;
+    wave_sync();
 #pragma unroll
-    for (int e = 0; e < 8; ++e) q[e] = quantize<BITS>(elem_f32<DT>(raw, e), gp[e].zero, gp[e].inv);
+    for (int k = 0; k < 4; ++k) {
+        const f32x4 o = x4[col * 4 + k];
+        kp.zero[2 * k] = o[0]; kp.inv[2 * k] = o[1];
+        kp.zero[2 * k + 1] = o[2]; kp.inv[2 * k + 1] = o[3];
+    }
+    kp.clamp = __builtin_amdgcn_ballot_w64(g0.clamp || g1.clamp) != 0;
+}
+
+// Quantize the lane's 8 channels of one row with per-channel parameters (K).
+template <int BITS, int DT, bool CLAMP>
+__device__ __forceinline__ u32x2 k_quant_row(const u32x4 &raw, const KParams &kp)
+{
+    float q[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) q[e] = quantize_f<BITS, CLAMP>(elem_f32<DT>(raw, e), kp.zero[e], kp.inv[e]);
     return pack8<BITS>(q);
 }
 
-// V: the lane's 8 channels belong to one group shared with GV/8 - 1 neighbouring lanes.
-template <int BITS, int GV, int DT>
-__device__ __forceinline__ u32x2 v_quant_row(const u32x4 &raw, uint32_t &meta_word)
+// V: the lane's 8 channels of a row belong to one group shared with GV/8 - 1 neighbouring lanes.
+template <int GV, int DT>
+__device__ __forceinline__ void v_row_minmax(const u32x4 &raw, float &mn, float &mx)
 {
-    float x[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) x[e] = elem_f32<DT>(raw, e);
-    float mn, mx;
     if (DT == DT_F16) {
-        half2_t h[4];
-#pragma unroll
-        for (int w = 0; w < 4; ++w) h[w] = as_half2(raw[w]);
-        half2_t a = __builtin_elementwise_min(__builtin_elementwise_min(h[0], h[1]),
-                                              __builtin_elementwise_min(h[2], h[3]));
-        half2_t b = __builtin_elementwise_max(__builtin_elementwise_max(h[0], h[1]),
-                                              __builtin_elementwise_max(h[2], h[3]));
-        mn = fminf((float)a[0], (float)a[1]);
-        mx = fmaxf((float)b[0], (float)b[1]);
+        const uint32_t a = pk_min_f16(pk_min_f16(raw[0], raw[1]), pk_min_f16(raw[2], raw[3]));
+        const uint32_t b = pk_max_f16(pk_max_f16(raw[0], raw[1]), pk_max_f16(raw[2], raw[3]));
+        mn = fminf(lo_f32<DT_F16>(a), hi_f32<DT_F16>(a));
+        mx = fmaxf(lo_f32<DT_F16>(b), hi_f32<DT_F16>(b));
     } else {
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = elem_f32<DT>(raw, e);
         mn = fminf(fminf(fminf(x[0], x[1]), fminf(x[2], x[3])), fminf(fminf(x[4], x[5]), fminf(x[6], x[7])));
         mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
     }
     group_minmax<GV / 8>(mn, mx);
-    GroupParams gp = make_group<BITS>(mn, mx);
-    meta_word = gp.meta;
-    uint32_t q[8];
+}
+
+struct VParams {
+    float zero[8], inv[8];   // of the lane's group in each of its 8 rows
+    uint32_t meta[8];
+    bool clamp;              // wave-uniform
+};
+
+template <int BITS, int GV, int DT>
+__device__ __forceinline__ void v_pass_params(const u32x4 raw[8], VParams &vp)
+{
+    bool c = false;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) q[e] = quantize<BITS>(x[e], gp.zero, gp.inv);
+    for (int i = 0; i < 8; ++i) {
+        float mn, mx;
+        v_row_minmax<GV, DT>(raw[i], mn, mx);
+        const GroupParams g = make_group<BITS, DT>(mn, mx);
+        vp.zero[i] = g.zero;
+        vp.inv[i] = g.inv;
+        vp.meta[i] = g.meta;
+        c = c || g.clamp;
+    }
+    vp.clamp = __builtin_amdgcn_ballot_w64(c) != 0;
+}
+
+template <int BITS, int DT, bool CLAMP>
+__device__ __forceinline__ u32x2 v_quant_row(const u32x4 &raw, float zero, float inv)
+{
+    float q[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) q[e] = quantize_f<BITS, CLAMP>(elem_f32<DT>(raw, e), zero, inv);
     return pack8<BITS>(q);
+}
+
+// Where the packed codes of tile row r go: row-major (payload section) or, when SUB, the LDS
+// chunk layout of the coder (sub-blocks of two rows, each padded by 16 bytes).
+template <int BITS, bool SUB> __device__ __forceinline__ uint8_t *code_row(uint8_t *base, int r)
+{
+    if (SUB) return base + (r >> 1) * (32 * BITS + 16) + (r & 1) * (16 * BITS);
+    return base + r * (16 * BITS);
+}
+
+template <int BITS> __device__ __forceinline__ void store_codes(uint8_t *row, u32x2 w)
+{
+    // for 3 bits, w[0] already went through quad_words_from_24
+    const int col = lane_id() & 15;
+    if (BITS == 3) {
+        if ((col & 3) != 3) *(uint32_t *)(row + (col >> 2) * 12 + (col & 3) * 4) = w[0];
+    } else {
+        store_row_codes<BITS>(row, w);
+    }
+}
+
+template <int BITS, int DT, int P, bool SUB, bool CLAMP, bool FULL>
+__device__ __forceinline__ void k_emit_rows(const u32x4 *raw, const KParams &kp, uint8_t *base, int rows)
+{
+    const int rsub = lane_id() >> 4;
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int r = p * kPassRows + 4 * i + rsub;
+            u32x2 w = k_quant_row<BITS, DT, CLAMP>(raw[p * 8 + i], kp);
+            if (BITS == 3) w[0] = quad_words_from_24(w[0]);
+            if (FULL || r < rows) store_codes<BITS>(code_row<BITS, SUB>(base, r), w);
+        }
+}
+
+// Quantize, pack and store the P*32 rows of a K token block (`rows` of them exist).
+template <int BITS, int DT, int P, bool SUB>
+__device__ __forceinline__ void k_emit(const u32x4 *raw, const KParams &kp, uint8_t *base, int rows)
+{
+    const bool full = rows >= P * kPassRows;
+    if (kp.clamp) {
+        if (full) k_emit_rows<BITS, DT, P, SUB, true, true>(raw, kp, base, rows);
+        else k_emit_rows<BITS, DT, P, SUB, true, false>(raw, kp, base, rows);
+    } else {
+        if (full) k_emit_rows<BITS, DT, P, SUB, false, true>(raw, kp, base, rows);
+        else k_emit_rows<BITS, DT, P, SUB, false, false>(raw, kp, base, rows);
+    }
+}
+
+template <int BITS, int GV, int DT, bool SUB, bool CLAMP, bool FULL>
+__device__ __forceinline__ void v_emit_rows(const u32x4 raw[8], const VParams &vp, uint8_t *base, int rows,
+                                            uint32_t *meta)
+{
+    constexpr int LANES = GV / 8, NG = kDim / GV;
+    const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = 4 * i + rsub;
+        u32x2 w = v_quant_row<BITS, DT, CLAMP>(raw[i], vp.zero[i], vp.inv[i]);
+        if (BITS == 3) w[0] = quad_words_from_24(w[0]);
+        if (FULL || r < rows) {
+            store_codes<BITS>(code_row<BITS, SUB>(base, r), w);
+            if (meta && (col & (LANES - 1)) == 0) meta[r * NG + col / LANES] = vp.meta[i];
+        }
+    }
+}
+
+// One pass (32 rows, `rows` of them exist) of V; base / meta point at the pass's first row.
+template <int BITS, int GV, int DT, bool SUB>
+__device__ __forceinline__ void v_emit(const u32x4 raw[8], const VParams &vp, uint8_t *base, int rows, uint32_t *meta)
+{
+    const bool full = rows >= kPassRows;
+    if (vp.clamp) {
+        if (full) v_emit_rows<BITS, GV, DT, SUB, true, true>(raw, vp, base, rows, meta);
+        else v_emit_rows<BITS, GV, DT, SUB, true, false>(raw, vp, base, rows, meta);
+    } else {
+        if (full) v_emit_rows<BITS, GV, DT, SUB, false, true>(raw, vp, base, rows, meta);
+        else v_emit_rows<BITS, GV, DT, SUB, false, false>(raw, vp, base, rows, meta);
+    }
 }
 
 // Reconstruct the lane's 8 channels of one row: x^ = round(code * scale + zero).
 // meta[e] = scale bits | zero bits << 16 of channel e's group.
 template <int BITS, int DT>
-__device__ __forceinline__ u32x4 dequant_row(u32x2 codes, const uint32_t meta[8])
+__device__ __forceinline__ u32x4 dequant_row(u32x2 codes, const float scale[8], const float zero[8])
 {
     uint32_t q[8];
     unpack8<BITS>(codes, q);
     u32x4 out;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-        float a = __builtin_fmaf((float)q[2 * w], f16_bits_to_f32(meta[2 * w] & 0xffffu),
-                                 f16_bits_to_f32(meta[2 * w] >> 16));
-        float b = __builtin_fmaf((float)q[2 * w + 1], f16_bits_to_f32(meta[2 * w + 1] & 0xffffu),
-                                 f16_bits_to_f32(meta[2 * w + 1] >> 16));
-        out[w] = pack_out<DT>(a, b);
-    }
+    for (int w = 0; w < 4; ++w)
+        out[w] = pack_out<DT>(__builtin_fmaf((float)q[2 * w], scale[2 * w], zero[2 * w]),
+                              __builtin_fmaf((float)q[2 * w + 1], scale[2 * w + 1], zero[2 * w + 1]));
     return out;
 }
 
