@@ -24,6 +24,7 @@ HBM_PEAK_GBS = 8000.0
 WORKLOADS = {
     # name: (layers, heads, tokens, dtype, bits_k, bits_v, group_k, group_v, codec)
     "llama70b_32k_fp16_int4g32_huff8": (80, 8, 32768, "f16", 4, 4, 32, 32, 1),
+    "llama70b_32k_fp16_int4g32": (80, 8, 32768, "f16", 4, 4, 32, 32, 0),
     "llama8b_8k_bf16_int4g32": (32, 8, 8192, "bf16", 4, 4, 32, 32, 0),
     "llama8b_8k_bf16_int2g64": (32, 8, 8192, "bf16", 2, 2, 64, 64, 0),
     "tiny_fp16_int4g32": (1, 8, 1024, "f16", 4, 4, 32, 32, 0),

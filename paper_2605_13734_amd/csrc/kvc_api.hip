@@ -149,11 +149,10 @@ extern "C" int kvc_plan(const kvc_model *model, const kvc_strategy *strategy, in
     p->max_batch = max_batch;
     if (strategy->codec) {
         // histograms, encode tables, decode tables, ticket, then the scan state
-        // one state word per encode workgroup; a workgroup takes at least 2 chunks
+        // one scan-state word per chunk of K and of V
         const long long chunks = (long long)model->layers * model->kv_heads * chunks_per_head(max_tokens);
-        const long long wgs = 2 * ((chunks + 1) / 2);
         p->ws_state_off = a256(2 * 256 * 4) + a256(2 * 256 * 4) + a256(2 * 4096 * 2) + 256;
-        p->ws_request = p->ws_state_off + a256((size_t)wgs * 8 + 8);
+        p->ws_request = p->ws_state_off + a256((size_t)(2 * chunks) * 8 + 8);
     }
     *out = p;
     return KVC_OK;
@@ -308,12 +307,12 @@ static CoderArgs coder_args(const kvc_plan_t *p, const QuantArgs &q, int is_v, u
     c.capacity = capacity;
     c.chunks = is_v ? g.chunks_v : g.chunks_k;
     c.chunk_base = is_v ? g.chunks_k : 0;
+    c.total_chunks = g.chunks_k + g.chunks_v;
     // chunks per encode workgroup: 2 at 8 bits, 4 otherwise (LDS footprint of a chunk)
     const int nw_k = p->strat.bits_k == 8 ? 2 : 4, nw_v = p->strat.bits_v == 8 ? 2 : 4;
     const long long wg_k = (g.chunks_k + nw_k - 1) / nw_k, wg_v = (g.chunks_v + nw_v - 1) / nw_v;
     c.wg_base = is_v ? wg_k : 0;
     c.total_wgs = wg_k + wg_v;
-    c.total_chunks = g.chunks_k + g.chunks_v;
     c.is_v = is_v;
     c.ws.hist = (uint32_t *)ws;
     c.ws.enc = (uint32_t *)(ws + a256(2 * 256 * 4));

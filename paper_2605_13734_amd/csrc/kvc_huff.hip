@@ -28,7 +28,8 @@ template <int BITS> struct ChunkGeom {
     static constexpr int kSubStride = kSubBytes + 16;      // LDS stride (bank spread, 16-byte aligned)
     static constexpr int kWords = kSubBytes / 4;           // words a lane holds for its sub-block
     static constexpr int kLds = kSubs * kSubStride;        // LDS bytes per wave
-    static constexpr int kWaves = BITS == 8 ? 2 : 4;       // waves (= chunks) per workgroup
+    static constexpr int kWaves = BITS == 8 ? 2 : 4;       // encoder: waves (= chunks) per workgroup
+    static constexpr int kDecWaves = BITS == 8 ? 2 : 4;    // decoder: waves (= chunks) per workgroup
 };
 
 // ---- chunk <-> LDS -------------------------------------------------------------------------
@@ -58,38 +59,32 @@ __device__ __forceinline__ ChunkPos chunk_pos(const QuantArgs &a, long long chun
 }
 
 // Quantize and pack the chunk's rows into the wave's LDS region (sub-block layout) and,
-// when `write_meta`, store the group metadata to the payload.
+// when `write_meta`, store the group metadata to the payload.  K group parameters are
+// exchanged through the 16 padding bytes that follow each sub-block.
 template <int BITS, int G, int DT, bool IS_V, bool DENSE>
-__device__ __forceinline__ void quantize_chunk(const QuantArgs &a, const ChunkPos &c, uint8_t *lds, float *xch,
-                                               bool write_meta, bool &bad)
+__device__ __forceinline__ void quantize_chunk(const QuantArgs &a, const ChunkPos &c, uint8_t *lds, bool write_meta,
+                                               bool &bad)
 {
-    if (!IS_V) {
-        constexpr int P = G / kPassRows;
-        const long long nb = (a.tokens + G - 1) / G;
+    constexpr int RU = IS_V ? kPassRows : G, PU = RU / kPassRows, NU = kChunkRows / RU;
 #pragma unroll 1
-        for (int gb = 0; gb < kChunkRows / G; ++gb) {
-            if (gb * G >= c.rows) break;
-            const long long row0 = c.row0 + gb * G;
-            u32x4 raw[P * 8];
+    for (int u = 0; u < NU; ++u) {
+        if (u * RU >= c.rows) break;
+        const long long row0 = c.row0 + u * RU;
+        u32x4 raw[PU * 8];
 #pragma unroll
-            for (int p = 0; p < P; ++p) load_pass<DENSE>(a.x, c.head_off, row0 + p * kPassRows, a.tokens, raw + p * 8, bad);
+        for (int p = 0; p < PU; ++p) load_pass<DENSE>(a.x, c.head_off, row0 + p * kPassRows, a.tokens, raw + p * 8, bad);
+        if (!IS_V) {
+            const long long nb = (a.tokens + G - 1) / G;
             KParams kp;
             uint8_t *meta_block = write_meta ? a.meta + (c.lh * nb + row0 / G) * (kDim * 4) : nullptr;
-            k_group_params<BITS, DT, P * 8>(raw, xch, meta_block, kp);
-            k_emit<BITS, DT, P, true>(raw, kp, code_row<BITS, true>(lds, gb * G), c.rows - gb * G);
-        }
-    } else {
-        constexpr int NG = kDim / G;
-#pragma unroll 1
-        for (int p = 0; p < kChunkRows / kPassRows; ++p) {
-            if (p * kPassRows >= c.rows) break;
-            const long long row0 = c.row0 + p * kPassRows;
-            u32x4 raw[8];
-            load_pass<DENSE>(a.x, c.head_off, row0, a.tokens, raw, bad);
+            k_group_params<BITS, DT, PU * 8, ChunkGeom<BITS>::kSubStride>(raw, lds + ChunkGeom<BITS>::kSubBytes, meta_block, kp);
+            k_emit<BITS, DT, PU, true>(raw, kp, code_row<BITS, true>(lds, u * RU), c.rows - u * RU);
+        } else {
+            constexpr int NG = kDim / G;
             VParams vp;
             v_pass_params<BITS, G, DT>(raw, vp);
             uint32_t *meta = write_meta ? (uint32_t *)a.meta + (c.lh * a.tokens + row0) * NG : nullptr;
-            v_emit<BITS, G, DT, true>(raw, vp, code_row<BITS, true>(lds, p * kPassRows), c.rows - p * kPassRows, meta);
+            v_emit<BITS, G, DT, true>(raw, vp, code_row<BITS, true>(lds, u * RU), c.rows - u * RU, meta);
         }
     }
 }
@@ -136,7 +131,6 @@ template <int BITS, int G, int DT, bool IS_V>
 __global__ __launch_bounds__(64) void hist_kernel(CoderArgs a)
 {
     __shared__ __attribute__((aligned(16))) uint8_t lds[ChunkGeom<BITS>::kLds];
-    __shared__ __attribute__((aligned(16))) float xch[kXchFloats];
     __shared__ uint32_t hist[256];
     const int i = blockIdx.x, lane = lane_id();
     const long long n = a.chunks;
@@ -145,7 +139,7 @@ __global__ __launch_bounds__(64) void hist_kernel(CoderArgs a)
     for (int k = lane; k < 256; k += 64) hist[k] = 0;
     ChunkPos c = chunk_pos(a.q, chunk);
     bool bad = false;
-    quantize_chunk<BITS, G, DT, IS_V, false>(a.q, c, lds, xch, false, bad);
+    quantize_chunk<BITS, G, DT, IS_V, false>(a.q, c, lds, false, bad);
     wave_sync();
     constexpr int W = ChunkGeom<BITS>::kWords;
     uint32_t sym[W];
@@ -323,15 +317,22 @@ __global__ __launch_bounds__(64) void decode_prepare_kernel(CoderArgs a)
 
 // ---- encoder ---------------------------------------------------------------------------------
 
+// Encoder tables in LDS: code lengths as bytes, and code | length << 12 as 16-bit entries
+// (narrow entries keep the hot byte values of a section in distinct banks).
+struct EncTables {
+    uint8_t len[256];
+    uint16_t code[256];
+};
+
 // bit count of HALF (0 or 1) of the lane's sub-block
-template <int W> __device__ __forceinline__ uint32_t half_bits(const uint32_t *sym, const uint8_t *enc_bytes, int half)
+template <int W> __device__ __forceinline__ uint32_t half_bits(const uint32_t *sym, const EncTables &t, int half)
 {
     uint32_t bits = 0;
 #pragma unroll
     for (int k = 0; k < W / 2; ++k) {
         const uint32_t w = sym[half * (W / 2) + k];
 #pragma unroll
-        for (int b = 0; b < 4; ++b) bits += enc_bytes[((w >> (8 * b)) & 255u) * 4 + 2];
+        for (int b = 0; b < 4; ++b) bits += t.len[(w >> (8 * b)) & 255u];
     }
     return bits;
 }
@@ -342,6 +343,20 @@ struct BitWriter {
     uint32_t *out;       // next word (LDS)
 };
 
+__device__ __forceinline__ void writer_start(BitWriter &bw, uint32_t *words, uint32_t bit)
+{
+    bw.acc = 0;
+    bw.nbits = bit & 31;          // the leading bits of the first word belong to the previous stream
+    bw.out = words + (bit >> 5);
+}
+
+__device__ __forceinline__ void put(BitWriter &bw, uint32_t e)
+{
+    const uint32_t len = e >> 12;
+    bw.acc = (bw.acc << len) | (e & 0xfffu);
+    bw.nbits += len;
+}
+
 __device__ __forceinline__ void flush(BitWriter &bw)
 {
     if (bw.nbits >= 32) {
@@ -351,37 +366,65 @@ __device__ __forceinline__ void flush(BitWriter &bw)
     }
 }
 
-template <int W> __device__ __forceinline__ void encode_half(const uint32_t *sym, const uint32_t *enc, int half, BitWriter &bw)
+__device__ __forceinline__ void writer_finish(BitWriter &bw)
+{
+    if (bw.nbits > 0) atomicOr(bw.out, (uint32_t)(bw.acc << (32 - bw.nbits)));
+}
+
+// Code the words [first, first + n) of the lane's sub-block.  Words of streams that share a
+// boundary word are merged with LDS atomic OR (the region is zeroed beforehand).
+template <int N> __device__ __forceinline__ void encode_words(const uint32_t *sym, const EncTables &t, BitWriter &bw)
 {
 #pragma unroll
-    for (int k = 0; k < W / 2; ++k) {
-        const uint32_t w = sym[half * (W / 2) + k];
+    for (int k = 0; k < N; ++k) {
+        const uint32_t w = sym[k];
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
-            const uint32_t e = enc[(w >> (8 * b)) & 255u];
-            const uint32_t len = e >> 16;
-            bw.acc = (bw.acc << len) | (e & 0xffffu);
-            bw.nbits += len;
+            put(bw, t.code[(w >> (8 * b)) & 255u]);
             if (b & 1) flush(bw);          // at most 24 new bits between checks
         }
     }
 }
 
+// Both halves of the sub-block as two independent streams (instruction-level parallelism).
+template <int W> __device__ __forceinline__ void encode_two(const uint32_t *sym, const EncTables &t, BitWriter &b0, BitWriter &b1)
+{
+#pragma unroll
+    for (int k = 0; k < W / 2; ++k) {
+        const uint32_t w0 = sym[k], w1 = sym[W / 2 + k];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            put(b0, t.code[(w0 >> (8 * b)) & 255u]);
+            put(b1, t.code[(w1 >> (8 * b)) & 255u]);
+            if (b & 1) { flush(b0); flush(b1); }
+        }
+    }
+}
+
+// One workgroup = kWaves chunks.  A chunk's body offset is the sum of all earlier bodies of the
+// request (K chunks first, then V): a single-pass scan over one state word per workgroup.
+// Workgroups take a ticket from a counter; wave 0 publishes the workgroup's total size, looks
+// back over earlier tickets until it meets one that knows its inclusive prefix, and publishes
+// its own.  Ticket order guarantees that every predecessor is already running, so the wait
+// always ends; it is bounded by kSpinLimit all the same.
 template <int BITS, int G, int DT, bool IS_V, bool DENSE>
 __global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void encode_kernel(CoderArgs a)
 {
     using Geo = ChunkGeom<BITS>;
     constexpr int W = Geo::kWords, NW = Geo::kWaves;
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * Geo::kLds];
-    __shared__ __attribute__((aligned(16))) float xch_all[NW * kXchFloats];
-    __shared__ uint32_t enc[256];
+    __shared__ EncTables enc;
     __shared__ uint32_t s_units[NW];
     __shared__ unsigned long long s_excl;
     __shared__ uint32_t s_ticket;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
     if (tid == 0) s_ticket = atomicAdd(a.ws.ticket, 1u);
-    for (int k = tid; k < 256; k += NW * 64) enc[k] = a.ws.enc[(IS_V ? 256 : 0) + k];
+    for (int k = tid; k < 256; k += NW * 64) {
+        const uint32_t e = a.ws.enc[(IS_V ? 256 : 0) + k];       // code | length << 16
+        enc.len[k] = (uint8_t)(e >> 16);
+        enc.code[k] = (uint16_t)((e & 0xfffu) | ((e >> 16) << 12));
+    }
     __syncthreads();
     const long long ticket = s_ticket;                 // global order over K and V workgroups
     const long long chunk = (ticket - a.wg_base) * NW + wave;
@@ -396,14 +439,15 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void encode_kernel(Co
         ChunkPos c = chunk_pos(a.q, chunk);
         rows = c.rows;
         bool bad = false;
-        quantize_chunk<BITS, G, DT, IS_V, DENSE>(a.q, c, lds, xch_all + wave * kXchFloats, true, bad);
+        quantize_chunk<BITS, G, DT, IS_V, DENSE>(a.q, c, lds, true, bad);
         if (bad) atomicOr(a.q.status, KVC_DEV_BAD_BLOCK);
         wave_sync();
         load_sub<BITS>(lds, sym);
         const int have = min(max(rows - 2 * lane, 0), 2);        // valid rows of this sub-block
-        uint32_t bits = 0;
-        if (have > 0) bits += half_bits<W>(sym, (const uint8_t *)enc, 0);
-        if (have > 1) bits += half_bits<W>(sym, (const uint8_t *)enc, 1);
+        uint32_t bits0 = 0, bits = 0;
+        if (have > 0) bits0 = half_bits<W>(sym, enc, 0);
+        bits = bits0;
+        if (have > 1) bits += half_bits<W>(sym, enc, 1);
         const uint32_t incl = wave_inclusive_sum(bits);
         const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
         const uint32_t raw_bytes = (uint32_t)rows * Geo::kRowBytes;
@@ -417,13 +461,20 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void encode_kernel(Co
             wave_sync();
             ((uint16_t *)lds)[lane] = (uint16_t)bits;
             const uint32_t start = incl - bits;
-            BitWriter bw;
-            bw.acc = 0;
-            bw.nbits = start & 31;
-            bw.out = (uint32_t *)(lds + 2 * kSubs) + (start >> 5);
-            if (have > 0) encode_half<W>(sym, enc, 0, bw);
-            if (have > 1) encode_half<W>(sym, enc, 1, bw);
-            if (bw.nbits > 0 && bits > 0) atomicOr(bw.out, (uint32_t)(bw.acc << (32 - bw.nbits)));
+            uint32_t *words = (uint32_t *)(lds + 2 * kSubs);
+            if (have > 1) {
+                BitWriter b0, b1;
+                writer_start(b0, words, start);
+                writer_start(b1, words, start + bits0);
+                encode_two<W>(sym, enc, b0, b1);
+                writer_finish(b0);
+                writer_finish(b1);
+            } else if (have > 0) {
+                BitWriter b0;
+                writer_start(b0, words, start);
+                encode_words<W / 2>(sym, enc, b0);
+                writer_finish(b0);
+            }
             wave_sync();
         }
     }
@@ -544,7 +595,7 @@ template <int W> __device__ __forceinline__ void decode_half(uint32_t *sym, cons
         for (int b = 0; b < 4; ++b) {
             const uint32_t e = lut[(uint32_t)(br.window >> 52)];
             const uint32_t len = e >> 8;
-            w |= (e & 255u) << (8 * b);
+            w = __builtin_amdgcn_alignbit(e, w, 8);      // symbol byte enters at the top; after 4 symbols the first is lowest
             br.window <<= len;
             br.avail -= (int)len;
             if (b & 1) refill(br);
@@ -553,11 +604,34 @@ template <int W> __device__ __forceinline__ void decode_half(uint32_t *sym, cons
     }
 }
 
-template <int BITS, int DT, bool IS_V>
-__global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void decode_kernel(CoderArgs a)
+// metadata of the 32 rows starting at chunk row `r0`: K = the lane's 8 channels of that token
+// block (two 16-byte loads), V = the lane's group in each of its 8 rows
+__device__ __forceinline__ void load_meta_k(const QuantArgs &q, const ChunkPos &c, int r0, u32x4 &m0, u32x4 &m1)
+{
+    const int col = lane_id() & 15;
+    const long long nb = (q.tokens + q.group - 1) / q.group;
+    const u32x4 *m = (const u32x4 *)(q.meta + ((c.lh * nb + (c.row0 + r0) / q.group) * kDim + col * 8) * 4);
+    m0 = m[0];
+    m1 = m[1];
+}
+
+__device__ __forceinline__ void load_meta_v(const QuantArgs &q, const ChunkPos &c, int r0, uint32_t mv[8])
+{
+    const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
+    const int ng = kDim / q.group, shift = q.group == 32 ? 2 : (q.group == 64 ? 3 : 4);
+    const uint32_t *m = (const uint32_t *)q.meta + (c.lh * q.tokens + c.row0 + r0) * ng + (col >> shift);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = 4 * i + rsub;
+        mv[i] = m[(r0 + r < c.rows ? r : 0) * ng];
+    }
+}
+
+template <int BITS, int DT, bool IS_V, bool DENSE>
+__global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel(CoderArgs a)
 {
     using Geo = ChunkGeom<BITS>;
-    constexpr int W = Geo::kWords, NW = Geo::kWaves;
+    constexpr int W = Geo::kWords, NW = Geo::kDecWaves;
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * Geo::kLds];
     __shared__ uint16_t lut[4096];
 
@@ -583,6 +657,11 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void decode_kernel(Co
         return;
     }
     const uint8_t *body = a.payload + a.off_bodies + d0 * 16;
+    // metadata of the first pass: requested now, used after the chunk is decoded
+    u32x4 meta0 = {0, 0, 0, 0}, meta1 = {0, 0, 0, 0};
+    uint32_t metav[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (!IS_V) load_meta_k(a.q, c, 0, meta0, meta1);
+    else load_meta_v(a.q, c, 0, metav);
     if (size == raw_bytes) {
         // stored raw: scatter the packed rows into the sub-block layout
         for (uint32_t o = lane * 16; o < raw_bytes; o += 64 * 16) {
@@ -624,49 +703,55 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void decode_kernel(Co
         wave_sync();
     }
 
-    // dequantize the rows from LDS
+    // dequantize the rows from LDS; the metadata of a pass is in flight one pass ahead
     bool bad = false;
-    const int group = a.q.group;
+    u32x4 mk0 = meta0, mk1 = meta1;
+    uint32_t mv[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) mv[i] = metav[i];
 #pragma unroll 1
     for (int p = 0; p < kChunkRows / kPassRows; ++p) {
         if (p * kPassRows >= c.rows) break;
-        const long long row0 = c.row0 + p * kPassRows;
         float scale_k[8], zero_k[8];
-        const uint32_t *meta_v = nullptr;
-        int ng = 0, lanes_shift = 0;
+        uint32_t mw[8];
         if (!IS_V) {
-            const long long nb = (a.q.tokens + group - 1) / group;
-            const u32x4 *m = (const u32x4 *)(a.q.meta + ((c.lh * nb + row0 / group) * kDim + col * 8) * 4);
-            const u32x4 m0 = m[0], m1 = m[1];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const uint32_t w0 = m0[e], w1 = m1[e];
+                const uint32_t w0 = mk0[e], w1 = mk1[e];
                 scale_k[e] = f16_bits_to_f32(w0 & 0xffffu); zero_k[e] = f16_bits_to_f32(w0 >> 16);
                 scale_k[4 + e] = f16_bits_to_f32(w1 & 0xffffu); zero_k[4 + e] = f16_bits_to_f32(w1 >> 16);
             }
         } else {
-            ng = kDim / group;
-            lanes_shift = group == 32 ? 2 : (group == 64 ? 3 : 4);
-            meta_v = (const uint32_t *)a.q.meta + (c.lh * a.q.tokens + row0) * ng;
-        }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int r = p * kPassRows + 4 * i + rsub;
-            const bool ok = r < c.rows;
-            const int rr = ok ? r : p * kPassRows;
-            u32x2 w = load_row_codes<BITS>(lds_row<BITS>(lds, rr));
-            u32x4 out;
-            if (!IS_V) {
-                out = dequant_row<BITS, DT>(w, scale_k, zero_k);
-            } else {
-                const uint32_t mw = meta_v[(rr - p * kPassRows) * ng + (col >> lanes_shift)];
-                out = dequant_row_uniform<BITS, DT>(w, mw);
+            for (int i = 0; i < 8; ++i) mw[i] = mv[i];
+        }
+        if ((p + 1) * kPassRows < c.rows) {
+            if (!IS_V) load_meta_k(a.q, c, (p + 1) * kPassRows, mk0, mk1);
+            else load_meta_v(a.q, c, (p + 1) * kPassRows, mv);
+        }
+        const int left = c.rows - p * kPassRows;
+        if (DENSE && left >= kPassRows) {
+            u32x4 *dst = (u32x4 *)(a.q.x.base + c.head_off + (c.row0 + p * kPassRows + rsub) * kDim + col * 8);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int r = p * kPassRows + 4 * i + rsub;
+                u32x2 w = load_row_codes<BITS>(lds_row<BITS>(lds, r));
+                const u32x4 out = IS_V ? dequant_row_uniform<BITS, DT>(w, mw[i]) : dequant_row<BITS, DT>(w, scale_k, zero_k);
+                __builtin_nontemporal_store(out, dst + i * 64);
             }
-            if (ok) {
-                bool b = false;
-                const long long off = row_offset(a.q.x, c.head_off, c.row0 + r, b);
-                if (!b) *(u32x4 *)(a.q.x.base + off + col * 8) = out;
-                bad |= b;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int r = p * kPassRows + 4 * i + rsub;
+                const bool ok = r < c.rows;
+                u32x2 w = load_row_codes<BITS>(lds_row<BITS>(lds, ok ? r : p * kPassRows));
+                const u32x4 out = IS_V ? dequant_row_uniform<BITS, DT>(w, mw[i]) : dequant_row<BITS, DT>(w, scale_k, zero_k);
+                if (ok) {
+                    bool b = false;
+                    const long long off = row_offset(a.q.x, c.head_off, c.row0 + r, b);
+                    if (!b) *(u32x4 *)(a.q.x.base + off + col * 8) = out;
+                    bad |= b;
+                }
             }
         }
     }
@@ -696,10 +781,11 @@ template <int BITS, int G, int DT, bool IS_V> static int encode_launch(const Cod
 
 template <int BITS, int DT, bool IS_V> static int decode_launch(const CoderArgs &a, hipStream_t s)
 {
-    constexpr int NW = ChunkGeom<BITS>::kWaves;
+    constexpr int NW = ChunkGeom<BITS>::kDecWaves;
     const long long need = (a.chunks + NW - 1) / NW;
     if (need <= 0) return KVC_OK;
-    hipLaunchKernelGGL((decode_kernel<BITS, DT, IS_V>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
+    if (a.q.dense) hipLaunchKernelGGL((decode_kernel<BITS, DT, IS_V, true>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
+    else hipLaunchKernelGGL((decode_kernel<BITS, DT, IS_V, false>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
     return launched();
 }
 

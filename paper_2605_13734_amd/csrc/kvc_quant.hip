@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void compress_k_kernel(QuantArgs a)
     for (int p = 0; p < P; ++p) load_pass<DENSE>(a.x, u.head_off, row0 + p * kPassRows, a.tokens, raw + p * 8, bad);
     KParams kp;
     uint8_t *meta_block = a.meta + (u.lh * a.units_per_head + u.blk) * (kDim * 4);
-    k_group_params<BITS, DT, P * 8>(raw, xch_all + (threadIdx.x >> 6) * kXchFloats, meta_block, kp);
+    k_group_params<BITS, DT, P * 8, 16>(raw, (uint8_t *)(xch_all + (threadIdx.x >> 6) * kXchFloats), meta_block, kp);
     uint8_t *codes = a.codes + (u.lh * a.tokens + row0) * (16 * BITS);
     const long long left = a.tokens - row0;
     k_emit<BITS, DT, P, false>(raw, kp, codes, left < G ? (int)left : G);

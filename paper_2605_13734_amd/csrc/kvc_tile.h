@@ -136,10 +136,10 @@ struct KParams {
 
 // Parameters of the 128 per-channel groups of one token block.  Each of the four lanes that
 // share a channel octet computes two channels, stores their metadata (scale, zero as fp16)
-// and publishes (zero, 1/scale) through `xch` (LDS, kXchFloats per wave).
+// and publishes (zero, 1/scale) through 64 LDS slots of 16 bytes, XSTRIDE bytes apart, at `xch`.
 // meta_block: the 512 bytes of this token block's metadata, or null to skip the store.
-template <int BITS, int DT, int N>
-__device__ __forceinline__ void k_group_params(const u32x4 *raw, float *xch, uint8_t *meta_block, KParams &kp)
+template <int BITS, int DT, int N, int XSTRIDE>
+__device__ __forceinline__ void k_group_params(const u32x4 *raw, uint8_t *xch, uint8_t *meta_block, KParams &kp)
 {
     const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
     float mn2[2], mx2[2];
@@ -154,13 +154,12 @@ __device__ __forceinline__ void k_group_params(const u32x4 *raw, float *xch, uin
     }
     typedef float f32x4 __attribute__((ext_vector_type(4)));
     f32x4 mine = {g0.zero, g0.inv, g1.zero, g1.inv};
-    f32x4 *x4 = (f32x4 *)xch;
     wave_sync();                                  // earlier readers of xch are done
-    x4[col * 4 + rsub] = mine;
+    *(f32x4 *)(xch + lane * XSTRIDE) = mine;
     wave_sync();
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        const f32x4 o = x4[col * 4 + k];
+        const f32x4 o = *(const f32x4 *)(xch + (k * 16 + col) * XSTRIDE);
         kp.zero[2 * k] = o[0]; kp.inv[2 * k] = o[1];
         kp.zero[2 * k + 1] = o[2]; kp.inv[2 * k + 1] = o[3];
     }
@@ -198,23 +197,53 @@ __device__ __forceinline__ void v_row_minmax(const u32x4 &raw, float &mn, float 
 
 struct VParams {
     float zero[8], inv[8];   // of the lane's group in each of its 8 rows
-    uint32_t meta[8];
+    uint32_t meta[8];        // meta[i] is meaningful on the lane that owns row i
+    uint32_t owner_mask;     // bit i: this lane computed (and stores the metadata of) row i
     bool clamp;              // wave-uniform
 };
 
+// Parameters of the lane's group in each of its 8 rows.  The GV/8 lanes of a group hold the
+// same (min, max) after the reduction; each of them finishes one or two of the 8 rows and the
+// results travel back through ds_bpermute.  vp.meta[i] is valid on the lane that owns row i
+// (vp.owner_mask bit i).
 template <int BITS, int GV, int DT>
 __device__ __forceinline__ void v_pass_params(const u32x4 raw[8], VParams &vp)
 {
-    bool c = false;
+    constexpr int LANES = GV / 8;
+    const int lane = lane_id(), k = lane & (LANES - 1), base = lane & ~(LANES - 1);
+    float mn[8], mx[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        float mn, mx;
-        v_row_minmax<GV, DT>(raw[i], mn, mx);
-        const GroupParams g = make_group<BITS, DT>(mn, mx);
-        vp.zero[i] = g.zero;
-        vp.inv[i] = g.inv;
-        vp.meta[i] = g.meta;
-        c = c || g.clamp;
+    for (int i = 0; i < 8; ++i) v_row_minmax<GV, DT>(raw[i], mn[i], mx[i]);
+    bool c = false;
+    if (LANES == 4) {
+        // lane k of the quad finishes rows k and k + 4
+        const GroupParams g0 = make_group<BITS, DT>(pick4(k, mn[0], mn[1], mn[2], mn[3]), pick4(k, mx[0], mx[1], mx[2], mx[3]));
+        const GroupParams g1 = make_group<BITS, DT>(pick4(k, mn[4], mn[5], mn[6], mn[7]), pick4(k, mx[4], mx[5], mx[6], mx[7]));
+        c = g0.clamp || g1.clamp;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const GroupParams &g = i < 4 ? g0 : g1;
+            const int src = (base + (i & 3)) << 2;
+            vp.zero[i] = __uint_as_float((uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)__float_as_uint(g.zero)));
+            vp.inv[i] = __uint_as_float((uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)__float_as_uint(g.inv)));
+            vp.meta[i] = g.meta;
+        }
+        vp.owner_mask = (0x11u << k);
+    } else {
+        // lanes 0..7 of the group finish row k
+        const int r = k & 7;
+        const float a = (r & 4) ? pick4(r, mn[4], mn[5], mn[6], mn[7]) : pick4(r, mn[0], mn[1], mn[2], mn[3]);
+        const float b = (r & 4) ? pick4(r, mx[4], mx[5], mx[6], mx[7]) : pick4(r, mx[0], mx[1], mx[2], mx[3]);
+        const GroupParams g = make_group<BITS, DT>(a, b);
+        c = g.clamp;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int src = (base + i) << 2;
+            vp.zero[i] = __uint_as_float((uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)__float_as_uint(g.zero)));
+            vp.inv[i] = __uint_as_float((uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)__float_as_uint(g.inv)));
+            vp.meta[i] = g.meta;
+        }
+        vp.owner_mask = k < 8 ? (1u << k) : 0u;
     }
     vp.clamp = __builtin_amdgcn_ballot_w64(c) != 0;
 }
@@ -289,7 +318,7 @@ __device__ __forceinline__ void v_emit_rows(const u32x4 raw[8], const VParams &v
         if (BITS == 3) w[0] = quad_words_from_24(w[0]);
         if (FULL || r < rows) {
             store_codes<BITS>(code_row<BITS, SUB>(base, r), w);
-            if (meta && (col & (LANES - 1)) == 0) meta[r * NG + col / LANES] = vp.meta[i];
+            if (meta && ((vp.owner_mask >> i) & 1u)) meta[r * NG + col / LANES] = vp.meta[i];
         }
     }
 }
