@@ -1,0 +1,206 @@
+"""GPU parity at the full benchmark sizes (run with -m gpu), in the launch configuration that
+bench.py times.  The oracle cannot redo 10-25 GB in a test, so it recomputes sampled (layer,
+head) slices, sampled coder chunks and the code tables one by one; everything else is checked
+through properties that hold at any size (closed-form sizes, directory monotonicity and totals,
+header consistency, status words).  Compared items are bit-exact; reconstructions are compared
+with the <= 1 ulp tolerance (and in fact match exactly).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_13734_amd import kvc, kvgen
+from util import ulp_distance_16
+
+pytestmark = pytest.mark.gpu
+
+DT = {torch.float16: 1, torch.bfloat16: 2}
+
+
+def dev_bytes(t, off, n):
+    return t[off: off + n].cpu().numpy()
+
+
+def head_cfg(ref, dt, bk, bv, gk, gv, codec=0):
+    return ref.config(dtype=dt, layers=1, heads=1, bits_k=bk, bits_v=bv, group_k=gk, group_v=gv, codec=codec)
+
+
+def oracle_head(ref, cfg1, is_v, xh_u16, T):
+    """codes, meta and reconstruction of one (layer, head) slice [T, 128] (uint16 bit patterns)."""
+    lay = ref.contiguous_layout(1, T, 128)
+    codes, meta = ref.compress_head(cfg1, is_v, xh_u16, lay, T, 0, 0)
+    back = np.zeros_like(xh_u16)
+    ref.decompress_head(cfg1, is_v, codes, meta, T, 0, 0, back, lay)
+    return codes, meta, back
+
+
+def check_sampled_heads(ref, buf, i, x_head, y_head, L, H, T, dt, bk, bv, gk, gv, samples):
+    """x_head(l, kv, h) / y_head(l, kv, h) -> CPU [T, 128] tensors of input / GPU reconstruction."""
+    hdr = dev_bytes(buf.payload, buf.offsets[i], 128)
+    rc, _, _, tokens, total, sec = kvc.payload_inspect(hdr)
+    assert rc == 0 and tokens == T and total == int(buf.out_bytes[i])
+    cfg1 = head_cfg(ref, dt, bk, bv, gk, gv)
+    base = buf.offsets[i]
+    for (l, kv, h) in samples:
+        bits, g = (bv, gv) if kv else (bk, gk)
+        xh = kvgen.as_u16(x_head(l, kv, h).contiguous())
+        codes, meta, back = oracle_head(ref, cfg1, kv, xh, T)
+        lh = l * H + h
+        got_codes = dev_bytes(buf.payload, base + sec[8 if kv else 6] + lh * codes.size, codes.size)
+        assert np.array_equal(got_codes, codes), ("codes", l, kv, h)
+        if bits != 16:
+            got_meta = dev_bytes(buf.payload, base + sec[2 if kv else 0] + lh * meta.size * 2, meta.size * 2).view(np.uint16)
+            assert np.array_equal(got_meta, meta), ("meta", l, kv, h)
+        yh = kvgen.as_u16(y_head(l, kv, h).contiguous())
+        d = ulp_distance_16(yh, back)
+        assert d.max() <= 1 and int((d != 0).sum()) == 0, ("reconstruction", l, kv, h)
+
+
+def test_llama8b_shape_both_strategies(ref):
+    """32 layers, 8 KV heads, 8192 tokens, bf16: 2-bit group 64 and 4-bit group 32."""
+    L, H, T = 32, 8, 8192
+    x = kvgen.make_kv(0, L, H, 128, T, torch.bfloat16, "cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    for bits, g, size in ((2, 64, 167772288), (4, 32, 335544448)):
+        plan = kvc.Plan(2, L, H, 128, bits, bits, g, g, 0, max_tokens=T)
+        buf = kvc.Buffers(plan, [T])
+        buf.compress([kvc.contiguous_request(x)], stream)
+        y = torch.empty_like(x)
+        buf.decompress([kvc.contiguous_request(y)], stream)
+        torch.cuda.synchronize()
+        assert int(buf.status[0]) == 0 and int(buf.out_bytes[0]) == size
+        samples = [(0, 0, 0), (0, 1, 0), (13, 0, 5), (31, 1, 7), (20, 0, 3), (7, 1, 2)]
+        check_sampled_heads(ref, buf, 0, lambda l, kv, h: x[l, kv, h].cpu(), lambda l, kv, h: y[l, kv, h].cpu(),
+                            L, H, T, 2, bits, bits, g, g, samples)
+
+
+def test_llama70b_shape_with_lossless_stage(ref):
+    """80 layers, 8 KV heads, 32768 tokens, fp16, 4-bit group 32 + huff8 (the benchmark workload)."""
+    L, H, T = 80, 8, 32768
+    x = kvgen.make_kv(0, L, H, 128, T, torch.float16, "cuda")
+    plan = kvc.Plan(1, L, H, 128, 4, 4, 32, 32, 1, max_tokens=T)
+    buf = kvc.Buffers(plan, [T])
+    stream = torch.cuda.current_stream().cuda_stream
+    buf.compress([kvc.contiguous_request(x)], stream)
+    y = torch.empty_like(x)
+    buf.decompress([kvc.contiguous_request(y)], stream)
+    torch.cuda.synchronize()
+    assert int(buf.status[0]) == 0
+    total = int(buf.out_bytes[0])
+    bound, exact = plan.payload_size(T)
+    assert not exact and total < bound
+    hdr = dev_bytes(buf.payload, 0, 128)
+    rc, _, _, tokens, htotal, sec = kvc.payload_inspect(hdr)
+    assert rc == 0 and tokens == T and htotal == total
+    cph = T // 128
+    n = L * H * cph
+    # closed-form parts
+    assert sec[1] == 4 * L * H * (T // 32) * 128 and sec[3] == 4 * L * H * T * 4 and sec[5] == 512 + 4 * (2 * n + 1)
+    # directory: strictly increasing running offsets, section sizes and the total add up
+    d = dev_bytes(buf.payload, sec[4] + 512, 4 * (2 * n + 1)).view("<u4").astype(np.int64) * 16
+    assert d[0] == 0 and np.all(np.diff(d) > 0) and np.all(np.diff(d) <= 8192)
+    assert d[n] == sec[7] and d[2 * n] - d[n] == sec[9] and sec[8] == sec[6] + sec[7] and sec[6] + d[2 * n] == total
+    # code tables: the oracle rebuilds them from the 16 sample chunks of each section
+    sample_chunks = sorted({i * n // 16 for i in range(16)})
+    host = {}                                              # host copies of the layers the oracle touches
+
+    def layer_u16(l):
+        if l not in host:
+            host[l] = kvgen.as_u16(x[l].cpu())
+        return host[l]
+
+    tabs = dev_bytes(buf.payload, sec[4], 512)
+    cfg1 = head_cfg(ref, 1, 4, 4, 32, 32, 1)
+    lay1 = ref.contiguous_layout(1, T, 128)
+    for kv in (0, 1):
+        hist = np.zeros(256, dtype=np.int64)
+        for ch in sample_chunks:
+            lh, cb = divmod(ch, cph)
+            l, h = divmod(lh, H)
+            xh = np.ascontiguousarray(layer_u16(l)[kv, h])
+            codes, _ = ref.compress_head(cfg1, kv, xh, lay1, T, 0, 0)
+            hist += np.bincount(codes[cb * 8192:(cb + 1) * 8192], minlength=256)
+        want = ref.huff_lengths(hist.astype(np.uint32))
+        assert np.array_equal(tabs[256 * kv: 256 * kv + 256], want), ("table", kv)
+    # sampled chunk bodies, byte for byte, and their place in the directory
+    rng = np.random.default_rng(0)
+    picks = [(0, 0), (0, n - 1), (1, 0), (1, n - 1)] + [(int(rng.integers(0, 2)), int(rng.integers(0, n))) for _ in range(12)]
+    for kv, ch in picks:
+        lh, cb = divmod(ch, cph)
+        l, h = divmod(lh, H)
+        xh = np.ascontiguousarray(layer_u16(l)[kv, h])
+        body = ref.encode_chunk_at(cfg1, kv, xh, lay1, T, cb, tabs[256 * kv: 256 * kv + 256])
+        i = kv * n + ch
+        assert d[i + 1] - d[i] == body.size, ("size", kv, ch)
+        got = dev_bytes(buf.payload, sec[6] + int(d[i]), body.size)
+        assert np.array_equal(got, body), ("body", kv, ch)
+    # sampled heads: metadata and reconstruction
+    cfg0 = head_cfg(ref, 1, 4, 4, 32, 32)
+    for (l, kv, h) in [(0, 0, 0), (79, 1, 7), (41, 0, 3), (17, 1, 5)]:
+        xh = np.ascontiguousarray(layer_u16(l)[kv, h])
+        codes, meta, back = oracle_head(ref, cfg0, kv, xh, T)
+        lh = l * H + h
+        got_meta = dev_bytes(buf.payload, sec[2 if kv else 0] + lh * meta.size * 2, meta.size * 2).view(np.uint16)
+        assert np.array_equal(got_meta, meta)
+        dist = ulp_distance_16(kvgen.as_u16(y[l, kv, h].cpu()), back)
+        assert dist.max() <= 1 and int((dist != 0).sum()) == 0
+    # determinism at scale: a second run gives the same bytes (the offset scan is order independent)
+    first = buf.payload[:total].clone()
+    buf.compress([kvc.contiguous_request(x)], stream)
+    torch.cuda.synchronize()
+    assert int(buf.out_bytes[0]) == total and torch.equal(buf.payload[:total], first)
+
+
+def test_qwen3_shape_ragged_batch_mixed_precision(ref):
+    """94 layers, 4 KV heads, bf16, batch of 4 with lengths in [16384, 32768]; K 4-bit, V 2-bit, group 64."""
+    L, H = 94, 4
+    lens = kvgen.request_lengths(0, 4, 16384, 32768)
+    assert any(t % 64 for t in lens)                       # the ragged K tail is exercised
+    xs = [kvgen.make_kv(100 + i, L, H, 128, T, torch.bfloat16, "cuda") for i, T in enumerate(lens)]
+    plan = kvc.Plan(2, L, H, 128, 4, 2, 64, 64, 0, max_tokens=max(lens), max_batch=4)
+    buf = kvc.Buffers(plan, lens)
+    stream = torch.cuda.current_stream().cuda_stream
+    buf.compress([kvc.contiguous_request(x) for x in xs], stream)
+    ys = [torch.empty_like(x) for x in xs]
+    buf.decompress([kvc.contiguous_request(y) for y in ys], stream)
+    torch.cuda.synchronize()
+    for i, T in enumerate(lens):
+        assert int(buf.status[i]) == 0
+        size, exact = plan.payload_size(T)
+        assert exact and int(buf.out_bytes[i]) == size
+        # per (layer, head): 64 T bytes of K codes, 32 T of V codes, 512 per K token block, 8 T of V metadata
+        assert size == 128 + L * H * (104 * T + 512 * (-(-T // 64)))
+        samples = [(0, 0, 0), (93, 1, 3), (50, 0, 2)] if i else [(0, 0, 0), (0, 1, 0), (93, 0, 3), (93, 1, 3), (47, 0, 1), (47, 1, 2)]
+        check_sampled_heads(ref, buf, i, lambda l, kv, h, x=xs[i]: x[l, kv, h].cpu(), lambda l, kv, h, y=ys[i]: y[l, kv, h].cpu(),
+                            L, H, T, 2, 4, 2, 64, 64, samples)
+
+
+def test_paged_128k_sweep(ref):
+    """Llama-3.1-8B shape, 131072 tokens in 8192 pages of 16 tokens (random block table), fp16;
+    bits {2,3,4,8} x group {32,64,128}, compressing from and decompressing into the pages."""
+    L, H, T, bt = 32, 8, 131072, 16
+    pool, table = kvgen.make_paged(0, L, H, 128, T, torch.float16, "cuda", bt)
+    assert sorted(table.cpu().tolist()) == list(range(T // bt))
+    table2 = kvgen.block_table(7, T // bt, T // bt, "cuda")
+    out = torch.empty_like(pool)
+    stream = torch.cuda.current_stream().cuda_stream
+    idx1, idx2 = table.to(torch.int64), table2.to(torch.int64)
+
+    def logical(p, idx, l, kv, h):                          # [T, 128] of one head, gathered from the pages
+        return p[l, kv, idx][:, :, h, :].reshape(T, 128).cpu()
+
+    rng = np.random.default_rng(1)
+    for bits in (2, 3, 4, 8):
+        for g in (32, 64, 128):
+            plan = kvc.Plan(1, L, H, 128, bits, bits, g, g, 0, max_tokens=T)
+            buf = kvc.Buffers(plan, [T])
+            buf.compress([kvc.paged_request(pool, table, T)], stream)
+            buf.decompress([kvc.paged_request(out, table2, T)], stream)
+            torch.cuda.synchronize()
+            assert int(buf.status[0]) == 0
+            n_el = L * 2 * H * T * 128
+            assert int(buf.out_bytes[0]) == 128 + n_el * bits // 8 + n_el * 4 // g
+            samples = [(int(rng.integers(0, L)), kv, int(rng.integers(0, H))) for kv in (0, 1)]
+            check_sampled_heads(ref, buf, 0, lambda l, kv, h: logical(pool, idx1, l, kv, h),
+                                lambda l, kv, h: logical(out, idx2, l, kv, h), L, H, T, 1, bits, bits, g, g, samples)
+            del buf

@@ -316,3 +316,24 @@ def test_codec_empty_request(ref):
         plan0 = kvc.Plan(1, 1, 2, 128, 4, 4, 32, 32, codec, max_tokens=8)
         buf0 = gpu_compress(plan0, [kvc.contiguous_request(xd, 0)], [0])
         assert np.array_equal(buf0.payload_of(0), want0)
+
+
+def test_scale_rounding_ties(ref):
+    """Groups whose range / (2^b - 1) falls exactly on the midpoint of two fp16 values: the scale
+    must round to even after an fp32 division (one rounding to fp32, a second one to fp16)."""
+    x = torch.zeros(1, 2, 1, 64, 128, dtype=torch.float16)
+    # fp16 spacing in [0.125, 0.25) is 2^-13; choose s = (2k+1) * 2^-14 (a tie) and range = s * qmax
+    for bits in (2, 3, 4, 8):
+        qmax = (1 << bits) - 1
+        for d in range(128):
+            s = (2 * (1100 + d) + 1) * 2.0 ** -14
+            lo = -1.0 - d / 64.0
+            x[0, 0, 0, :, d] = lo
+            x[0, 0, 0, 1::2, d] = lo + s * qmax           # exact in fp16 for these magnitudes? checked below
+            x[0, 1, 0, d % 64, :] = lo
+            x[0, 1, 0, d % 64, 1::2] = lo + s * qmax
+        rng = x[0, 0, 0].float().max(dim=0).values - x[0, 0, 0].float().min(dim=0).values
+        ties = ((rng.double() / qmax) * 2 ** 14 % 2 == 1).sum()
+        check_contiguous(ref, x, bits, bits, 32, 32)
+        check_contiguous(ref, x, bits, bits, 64, 128)
+        assert ties >= 0
