@@ -83,18 +83,35 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;                  // nearest even, finite input
 }
 
-// Two reconstructed values -> one packed word of the output type, kept finite.
-template <int DT> __device__ __forceinline__ uint32_t pack_out(float a, float b)
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+// Keeps the compiler from merging an fp32 operation with a following conversion to fp16 into
+// one mixed-precision instruction, which would round once instead of twice.
+__device__ __forceinline__ float rounded_f32(float x)
+{
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
+// Two reconstructed values (results of code * scale + zero with fp16 scale and zero, code >= 0)
+// -> one packed word of the output type, round to nearest even.  Such a value is never below
+// zero >= -65504, so only the upper end of the fp16 range can be exceeded (CLAMP); it cannot
+// leave the bfloat16 range at all.
+template <int DT, bool CLAMP> __device__ __forceinline__ uint32_t pack_out(float a, float b)
 {
     if (DT == DT_F16) {
-        a = __builtin_amdgcn_fmed3f(a, -65504.0f, 65504.0f);
-        b = __builtin_amdgcn_fmed3f(b, -65504.0f, 65504.0f);
+        if (CLAMP) {
+            a = fminf(a, 65504.0f);
+            b = fminf(b, 65504.0f);
+        } else {
+            a = rounded_f32(a);
+            b = rounded_f32(b);
+        }
         return f32_to_f16_bits(a) | (f32_to_f16_bits(b) << 16);
     }
-    const float m = 3.3895313892515355e38f;
-    a = __builtin_amdgcn_fmed3f(a, -m, m);
-    b = __builtin_amdgcn_fmed3f(b, -m, m);
-    return f32_to_bf16_bits(a) | (f32_to_bf16_bits(b) << 16);
+    f32x2_t v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));      // v_cvt_pk_bf16_f32
 }
 
 // ---- cross-lane helpers -----------------------------------------------------------------
@@ -168,14 +185,6 @@ __device__ __forceinline__ float rcp_f16_exact(float s)
     return __builtin_fmaf(y, e, y);
 }
 
-// Keeps the compiler from merging an fp32 operation with a following conversion to fp16 into
-// one mixed-precision instruction, which would round once instead of twice.
-__device__ __forceinline__ float rounded_f32(float x)
-{
-    asm volatile("" : "+v"(x));
-    return x;
-}
-
 // zero = fp16(min), scale = fp16((max - min) / (2^bits - 1)); a zero of either sign is +0.
 // With fp16 input the minimum is its own fp16 rounding and the scale cannot overflow.
 template <int BITS, int DT> __device__ __forceinline__ GroupParams make_group(float mn, float mx)
@@ -239,14 +248,22 @@ template <int BITS> __device__ __forceinline__ u32x2 pack8(const float q[8])
     return r;
 }
 
-template <int BITS> __device__ __forceinline__ void unpack8(u32x2 w, uint32_t q[8])
+// The lane's 8 codes as floats.  4- and 8-bit codes go through the byte-to-float conversions.
+template <int BITS> __device__ __forceinline__ void unpack8(u32x2 w, float q[8])
 {
     if (BITS == 8) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) q[e] = (w[e >> 2] >> ((e & 3) * 8)) & 0xffu;
+        for (int e = 0; e < 8; ++e) q[e] = (float)((w[e >> 2] >> ((e & 3) * 8)) & 0xffu);
+    } else if (BITS == 4) {
+        const uint32_t lo = w[0] & 0x0f0f0f0fu, hi = (w[0] >> 4) & 0x0f0f0f0fu;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            q[2 * k] = (float)((lo >> (8 * k)) & 0xffu);
+            q[2 * k + 1] = (float)((hi >> (8 * k)) & 0xffu);
+        }
     } else {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) q[e] = (w[0] >> (e * BITS)) & ((1u << BITS) - 1u);
+        for (int e = 0; e < 8; ++e) q[e] = (float)((w[0] >> (e * BITS)) & ((1u << BITS) - 1u));
     }
 }
 

@@ -635,42 +635,74 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * Geo::kLds];
     __shared__ uint16_t lut[4096];
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id(), col = lane & 15, rsub = lane >> 4;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
+    const long long chunk = (long long)blockIdx.x * NW + wave;
+    const bool live = chunk < a.chunks;
+    uint8_t *lds = lds_all + wave * Geo::kLds;
+
+    // Round trip 1: the chunk's two directory entries and the status word, with the decode
+    // table right behind them.
+    unsigned long long d0 = 0, d1 = 0;
+    int st = 0;
+    if (live) {
+        const uint32_t *dir = (const uint32_t *)(a.payload + a.off_aux + 512) + a.chunk_base + chunk;
+        d0 = dir[0];
+        d1 = dir[1];
+        st = *a.q.status;
+    }
+    constexpr int LUTN = 512 / (NW * 64);
+    u32x4 lutv[LUTN];
     {
         const u32x4 *src = (const u32x4 *)(a.ws.lut + (IS_V ? 4096 : 0));
-        for (int k = tid; k < 512; k += NW * 64) ((u32x4 *)lut)[k] = src[k];
+#pragma unroll
+        for (int i = 0; i < LUTN; ++i) lutv[i] = src[tid + i * NW * 64];
     }
-    __syncthreads();
-    const long long chunk = (long long)blockIdx.x * NW + wave;
-    if (chunk >= a.chunks) return;
-    if (*a.q.status & (KVC_DEV_BAD_HEADER | KVC_DEV_BAD_TABLE)) return;
-    uint8_t *lds = lds_all + wave * Geo::kLds;
-    const ChunkPos c = chunk_pos(a.q, chunk);
+    ChunkPos c = chunk_pos(a.q, live ? chunk : 0);
     const uint32_t raw_bytes = (uint32_t)c.rows * Geo::kRowBytes;
-
-    const uint32_t *dir = (const uint32_t *)(a.payload + a.off_aux + 512) + a.chunk_base + chunk;
-    const unsigned long long d0 = dir[0], d1 = dir[1];
     const unsigned long long size = (d1 - d0) * 16;
-    if (d1 < d0 || size > raw_bytes || (long long)(a.off_bodies + d1 * 16) > a.capacity ||
-        (size != raw_bytes && size < 2 * kSubs + 16)) {
+    bool ok = live && !(st & (KVC_DEV_BAD_HEADER | KVC_DEV_BAD_TABLE));
+    if (ok && (d1 < d0 || size > raw_bytes || (long long)(a.off_bodies + d1 * 16) > a.capacity ||
+               (size != raw_bytes && size < 2 * kSubs + 16))) {
         if (lane == 0) atomicOr(a.q.status, KVC_DEV_BAD_CHUNK);
-        return;
+        ok = false;
     }
-    const uint8_t *body = a.payload + a.off_bodies + d0 * 16;
-    // metadata of the first pass: requested now, used after the chunk is decoded
+    // Round trip 2: the body (into registers) and the metadata of the first pass.
+    constexpr int NB = 2 * BITS;                       // 16-byte pieces per lane of a full raw chunk
+    u32x4 bodyv[NB];
     u32x4 meta0 = {0, 0, 0, 0}, meta1 = {0, 0, 0, 0};
     uint32_t metav[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (!IS_V) load_meta_k(a.q, c, 0, meta0, meta1);
-    else load_meta_v(a.q, c, 0, metav);
+    if (ok) {
+        const uint8_t *body = a.payload + a.off_bodies + d0 * 16;
+#pragma unroll
+        for (int k = 0; k < NB; ++k) {
+            const uint32_t o = (k * 64 + lane) * 16;
+            if (o < size) bodyv[k] = __builtin_nontemporal_load((const u32x4 *)(body + o));
+        }
+        if (!IS_V) load_meta_k(a.q, c, 0, meta0, meta1);
+        else load_meta_v(a.q, c, 0, metav);
+    }
+#pragma unroll
+    for (int i = 0; i < LUTN; ++i) ((u32x4 *)lut)[tid + i * NW * 64] = lutv[i];
+    __syncthreads();
+    if (!ok) return;
+
     if (size == raw_bytes) {
         // stored raw: scatter the packed rows into the sub-block layout
-        for (uint32_t o = lane * 16; o < raw_bytes; o += 64 * 16) {
-            const uint32_t sub = o / Geo::kSubBytes, in = o - sub * Geo::kSubBytes;
-            *(u32x4 *)(lds + sub * Geo::kSubStride + in) = *(const u32x4 *)(body + o);
+#pragma unroll
+        for (int k = 0; k < NB; ++k) {
+            const uint32_t o = (k * 64 + lane) * 16;
+            if (o < raw_bytes) {
+                const uint32_t sub = o / Geo::kSubBytes, in = o - sub * Geo::kSubBytes;
+                *(u32x4 *)(lds + sub * Geo::kSubStride + in) = bodyv[k];
+            }
         }
         wave_sync();
     } else {
-        for (uint32_t o = lane * 16; o < size; o += 64 * 16) *(u32x4 *)(lds + o) = *(const u32x4 *)(body + o);
+#pragma unroll
+        for (int k = 0; k < NB; ++k) {
+            const uint32_t o = (k * 64 + lane) * 16;
+            if (o < size) *(u32x4 *)(lds + o) = bodyv[k];
+        }
         wave_sync();
         const uint32_t bits = ((const uint16_t *)lds)[lane];
         const uint32_t incl = wave_inclusive_sum(bits);
@@ -712,48 +744,14 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
 #pragma unroll 1
     for (int p = 0; p < kChunkRows / kPassRows; ++p) {
         if (p * kPassRows >= c.rows) break;
-        float scale_k[8], zero_k[8];
-        uint32_t mw[8];
-        if (!IS_V) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const uint32_t w0 = mk0[e], w1 = mk1[e];
-                scale_k[e] = f16_bits_to_f32(w0 & 0xffffu); zero_k[e] = f16_bits_to_f32(w0 >> 16);
-                scale_k[4 + e] = f16_bits_to_f32(w1 & 0xffffu); zero_k[4 + e] = f16_bits_to_f32(w1 >> 16);
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) mw[i] = mv[i];
-        }
+        float scale[8], zero[8];
+        const bool clamp = IS_V ? v_meta_floats<BITS, DT>(mv, scale, zero) : k_meta_floats<BITS, DT>(mk0, mk1, scale, zero);
         if ((p + 1) * kPassRows < c.rows) {
             if (!IS_V) load_meta_k(a.q, c, (p + 1) * kPassRows, mk0, mk1);
             else load_meta_v(a.q, c, (p + 1) * kPassRows, mv);
         }
-        const int left = c.rows - p * kPassRows;
-        if (DENSE && left >= kPassRows) {
-            u32x4 *dst = (u32x4 *)(a.q.x.base + c.head_off + (c.row0 + p * kPassRows + rsub) * kDim + col * 8);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int r = p * kPassRows + 4 * i + rsub;
-                u32x2 w = load_row_codes<BITS>(lds_row<BITS>(lds, r));
-                const u32x4 out = IS_V ? dequant_row_uniform<BITS, DT>(w, mw[i]) : dequant_row<BITS, DT>(w, scale_k, zero_k);
-                __builtin_nontemporal_store(out, dst + i * 64);
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int r = p * kPassRows + 4 * i + rsub;
-                const bool ok = r < c.rows;
-                u32x2 w = load_row_codes<BITS>(lds_row<BITS>(lds, ok ? r : p * kPassRows));
-                const u32x4 out = IS_V ? dequant_row_uniform<BITS, DT>(w, mw[i]) : dequant_row<BITS, DT>(w, scale_k, zero_k);
-                if (ok) {
-                    bool b = false;
-                    const long long off = row_offset(a.q.x, c.head_off, c.row0 + r, b);
-                    if (!b) *(u32x4 *)(a.q.x.base + off + col * 8) = out;
-                    bad |= b;
-                }
-            }
-        }
+        dequant_pass<BITS, DT, IS_V, DENSE, true>(lds_row<BITS>(lds, p * kPassRows), scale, zero, clamp, a.q.x, c.head_off,
+                                                  c.row0 + p * kPassRows, c.rows - p * kPassRows, bad);
     }
     if (bad) atomicOr(a.q.status, KVC_DEV_BAD_BLOCK);
 }

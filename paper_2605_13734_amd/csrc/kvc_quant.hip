@@ -56,39 +56,24 @@ __global__ __launch_bounds__(256) void compress_k_kernel(QuantArgs a)
     report(a.status, bad);
 }
 
-template <int BITS, int DT>
+template <int BITS, int DT, bool DENSE>
 __global__ __launch_bounds__(256) void decompress_k_kernel(QuantArgs a)
 {
     UnitPos u;
     if (!unit_pos(a, u)) return;
     if (*a.status & KVC_DEV_BAD_HEADER) return;
-    const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
+    const int col = lane_id() & 15;
     const long long row0 = u.blk * kPassRows;
     const long long tb = row0 / a.group, nb = (a.tokens + a.group - 1) / a.group;
     const u32x4 *m = (const u32x4 *)(a.meta + ((u.lh * nb + tb) * kDim + col * 8) * 4);
     const u32x4 m0 = m[0], m1 = m[1];
     float scale[8], zero[8];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const uint32_t w0 = m0[e], w1 = m1[e];
-        scale[e] = f16_bits_to_f32(w0 & 0xffffu); zero[e] = f16_bits_to_f32(w0 >> 16);
-        scale[4 + e] = f16_bits_to_f32(w1 & 0xffffu); zero[4 + e] = f16_bits_to_f32(w1 >> 16);
-    }
-    const uint8_t *codes = a.codes + (u.lh * a.tokens + row0) * (16 * BITS);
+    const bool clamp = k_meta_floats<BITS, DT>(m0, m1, scale, zero);
+    uint8_t *codes = a.codes + (u.lh * a.tokens + row0) * (16 * BITS);
+    const long long left = a.tokens - row0;
     bool bad = false;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const long long row = row0 + 4 * i + rsub;
-        const bool live = row < a.tokens;              // uniform over each quad of lanes
-        u32x2 w = load_row_codes<BITS>(codes + (live ? (4 * i + rsub) : 0) * (16 * BITS));
-        u32x4 out = dequant_row<BITS, DT>(w, scale, zero);
-        if (live) {
-            bool b = false;
-            long long off = row_offset(a.x, u.head_off, row, b);
-            if (!b) *(u32x4 *)(a.x.base + off + col * 8) = out;
-            bad |= b;
-        }
-    }
+    dequant_pass<BITS, DT, false, DENSE, false>(codes, scale, zero, clamp, a.x, u.head_off, row0,
+                                                left < kPassRows ? (int)left : kPassRows, bad);
     report(a.status, bad);
 }
 
@@ -113,7 +98,7 @@ __global__ __launch_bounds__(256) void compress_v_kernel(QuantArgs a)
     report(a.status, bad);
 }
 
-template <int BITS, int DT>
+template <int BITS, int DT, bool DENSE>
 __global__ __launch_bounds__(256) void decompress_v_kernel(QuantArgs a)
 {
     UnitPos u;
@@ -122,29 +107,17 @@ __global__ __launch_bounds__(256) void decompress_v_kernel(QuantArgs a)
     const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
     const long long row0 = u.blk * kPassRows;
     const int lanes_shift = a.group == 32 ? 2 : (a.group == 64 ? 3 : 4), ng = kDim / a.group;
-    const uint8_t *codes = a.codes + (u.lh * a.tokens + row0) * (16 * BITS);
-    const uint32_t *meta = (const uint32_t *)a.meta + (u.lh * a.tokens + row0) * ng;
-    bool bad = false;
+    const uint32_t *meta = (const uint32_t *)a.meta + (u.lh * a.tokens + row0) * ng + (col >> lanes_shift);
+    const long long left = a.tokens - row0;
+    const int rows = left < kPassRows ? (int)left : kPassRows;
     uint32_t mw[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const bool live = row0 + 4 * i + rsub < a.tokens;
-        mw[i] = meta[(live ? 4 * i + rsub : 0) * ng + (col >> lanes_shift)];
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const long long row = row0 + 4 * i + rsub;
-        const bool live = row < a.tokens;
-        const int r = live ? 4 * i + rsub : 0;
-        u32x2 w = load_row_codes<BITS>(codes + r * (16 * BITS));
-        u32x4 out = dequant_row_uniform<BITS, DT>(w, mw[i]);
-        if (live) {
-            bool b = false;
-            long long off = row_offset(a.x, u.head_off, row, b);
-            if (!b) *(u32x4 *)(a.x.base + off + col * 8) = out;
-            bad |= b;
-        }
-    }
+    for (int i = 0; i < 8; ++i) mw[i] = meta[(4 * i + rsub < rows ? 4 * i + rsub : 0) * ng];
+    float scale[8], zero[8];
+    const bool clamp = v_meta_floats<BITS, DT>(mw, scale, zero);
+    uint8_t *codes = a.codes + (u.lh * a.tokens + row0) * (16 * BITS);
+    bool bad = false;
+    dequant_pass<BITS, DT, true, DENSE, false>(codes, scale, zero, clamp, a.x, u.head_off, row0, rows, bad);
     report(a.status, bad);
 }
 
@@ -244,14 +217,19 @@ int launch_compress_tensor(int is_v, int bits, int group, int dtype, const Quant
     return KVC_ERR_UNSUPPORTED;
 }
 
-template <int BITS> static int decompress_bits(int is_v, int dtype, const QuantArgs &a, hipStream_t s)
+template <int BITS, bool DENSE> static int decompress_bits_dense(int is_v, int dtype, const QuantArgs &a, hipStream_t s)
 {
     if (!is_v) {
-        if (dtype == DT_F16) KVC_LAUNCH((decompress_k_kernel<BITS, DT_F16>), a, s);
-        KVC_LAUNCH((decompress_k_kernel<BITS, DT_BF16>), a, s);
+        if (dtype == DT_F16) KVC_LAUNCH((decompress_k_kernel<BITS, DT_F16, DENSE>), a, s);
+        KVC_LAUNCH((decompress_k_kernel<BITS, DT_BF16, DENSE>), a, s);
     }
-    if (dtype == DT_F16) KVC_LAUNCH((decompress_v_kernel<BITS, DT_F16>), a, s);
-    KVC_LAUNCH((decompress_v_kernel<BITS, DT_BF16>), a, s);
+    if (dtype == DT_F16) KVC_LAUNCH((decompress_v_kernel<BITS, DT_F16, DENSE>), a, s);
+    KVC_LAUNCH((decompress_v_kernel<BITS, DT_BF16, DENSE>), a, s);
+}
+
+template <int BITS> static int decompress_bits(int is_v, int dtype, const QuantArgs &a, hipStream_t s)
+{
+    return a.dense ? decompress_bits_dense<BITS, true>(is_v, dtype, a, s) : decompress_bits_dense<BITS, false>(is_v, dtype, a, s);
 }
 
 int launch_decompress_tensor(int is_v, int bits, int group, int dtype, const QuantArgs &a, hipStream_t s)

@@ -337,32 +337,111 @@ __device__ __forceinline__ void v_emit(const u32x4 raw[8], const VParams &vp, ui
     }
 }
 
-// Reconstruct the lane's 8 channels of one row: x^ = round(code * scale + zero).
-// meta[e] = scale bits | zero bits << 16 of channel e's group.
-template <int BITS, int DT>
+// Reconstruct the lane's 8 channels of one row: x^ = round(code * scale + zero), one fused fp32
+// multiply-add, then the output rounding.  CLAMP: see pack_out.
+template <int BITS, int DT, bool CLAMP>
 __device__ __forceinline__ u32x4 dequant_row(u32x2 codes, const float scale[8], const float zero[8])
 {
-    uint32_t q[8];
+    float q[8];
     unpack8<BITS>(codes, q);
     u32x4 out;
 #pragma unroll
     for (int w = 0; w < 4; ++w)
-        out[w] = pack_out<DT>(__builtin_fmaf((float)q[2 * w], scale[2 * w], zero[2 * w]),
-                              __builtin_fmaf((float)q[2 * w + 1], scale[2 * w + 1], zero[2 * w + 1]));
+        out[w] = pack_out<DT, CLAMP>(__builtin_fmaf(q[2 * w], scale[2 * w], zero[2 * w]),
+                                     __builtin_fmaf(q[2 * w + 1], scale[2 * w + 1], zero[2 * w + 1]));
     return out;
 }
 
-template <int BITS, int DT>
-__device__ __forceinline__ u32x4 dequant_row_uniform(u32x2 codes, uint32_t meta_word)
+template <int BITS, int DT, bool CLAMP>
+__device__ __forceinline__ u32x4 dequant_row_uniform(u32x2 codes, float s, float z)
 {
-    uint32_t q[8];
+    float q[8];
     unpack8<BITS>(codes, q);
-    const float s = f16_bits_to_f32(meta_word & 0xffffu), z = f16_bits_to_f32(meta_word >> 16);
     u32x4 out;
 #pragma unroll
     for (int w = 0; w < 4; ++w)
-        out[w] = pack_out<DT>(__builtin_fmaf((float)q[2 * w], s, z), __builtin_fmaf((float)q[2 * w + 1], s, z));
+        out[w] = pack_out<DT, CLAMP>(__builtin_fmaf(q[2 * w], s, z), __builtin_fmaf(q[2 * w + 1], s, z));
     return out;
+}
+
+// Scale and zero of the lane's 8 channels from two 16-byte metadata loads (K), and whether any
+// reconstruction of this token block can exceed the fp16 range (largest code * scale + zero).
+template <int BITS, int DT>
+__device__ __forceinline__ bool k_meta_floats(const u32x4 &m0, const u32x4 &m1, float scale[8], float zero[8])
+{
+    constexpr float qmax = (float)((1 << BITS) - 1);
+    float top = -65504.0f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const uint32_t w0 = m0[e], w1 = m1[e];
+        scale[e] = f16_bits_to_f32(w0 & 0xffffu); zero[e] = f16_bits_to_f32(w0 >> 16);
+        scale[4 + e] = f16_bits_to_f32(w1 & 0xffffu); zero[4 + e] = f16_bits_to_f32(w1 >> 16);
+    }
+    if (DT != DT_F16) return false;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) top = fmaxf(top, __builtin_fmaf(qmax, scale[e], zero[e]));
+    return __builtin_amdgcn_ballot_w64(top > 65504.0f) != 0;
+}
+
+// Same for the lane's group in each of its 8 rows (V), from one metadata word per row.
+template <int BITS, int DT>
+__device__ __forceinline__ bool v_meta_floats(const uint32_t mw[8], float scale[8], float zero[8])
+{
+    constexpr float qmax = (float)((1 << BITS) - 1);
+    float top = -65504.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        scale[i] = f16_bits_to_f32(mw[i] & 0xffffu);
+        zero[i] = f16_bits_to_f32(mw[i] >> 16);
+    }
+    if (DT != DT_F16) return false;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) top = fmaxf(top, __builtin_fmaf(qmax, scale[i], zero[i]));
+    return __builtin_amdgcn_ballot_w64(top > 65504.0f) != 0;
+}
+
+template <int BITS, int DT, bool IS_V, bool DENSE, bool SUB, bool CLAMP>
+__device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float scale[8], const float zero[8],
+                                                  const TensorView &x, long long head_off, long long row0, int rows,
+                                                  bool &bad)
+{
+    const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
+    if (DENSE && rows >= kPassRows) {
+        u32x4 *dst = (u32x4 *)(x.base + head_off + (row0 + rsub) * kDim + col * 8);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const u32x2 w = load_row_codes<BITS>(code_row<BITS, SUB>(codes, 4 * i + rsub));
+            const u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w, scale[i], zero[i])
+                                   : dequant_row<BITS, DT, CLAMP>(w, scale, zero);
+            __builtin_nontemporal_store(out, dst + i * 64);
+        }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = 4 * i + rsub;
+        const bool ok = r < rows;                       // uniform over each quad of lanes
+        const u32x2 w = load_row_codes<BITS>(code_row<BITS, SUB>(codes, ok ? r : 0));
+        const u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w, scale[i], zero[i])
+                               : dequant_row<BITS, DT, CLAMP>(w, scale, zero);
+        if (ok) {
+            bool b = false;
+            const long long off = DENSE ? head_off + (row0 + r) * kDim : row_offset(x, head_off, row0 + r, b);
+            if (!b) *(u32x4 *)(x.base + off + col * 8) = out;
+            bad |= b;
+        }
+    }
+}
+
+// Dequantize the pass whose packed rows start at `codes` (row-major, or the coder's LDS layout
+// when SUB) and store its `rows` existing rows at token rows row0... of head `head_off`.
+// K: scale / zero per channel of the lane; V: per row of the lane.
+template <int BITS, int DT, bool IS_V, bool DENSE, bool SUB>
+__device__ __forceinline__ void dequant_pass(uint8_t *codes, const float scale[8], const float zero[8], bool clamp,
+                                             const TensorView &x, long long head_off, long long row0, int rows, bool &bad)
+{
+    if (clamp) dequant_pass_rows<BITS, DT, IS_V, DENSE, SUB, true>(codes, scale, zero, x, head_off, row0, rows, bad);
+    else dequant_pass_rows<BITS, DT, IS_V, DENSE, SUB, false>(codes, scale, zero, x, head_off, row0, rows, bad);
 }
 
 }  // namespace kvc

@@ -113,6 +113,10 @@ def test_degenerate_values(ref):
     x[0, 1, 1, 6] = x[0, 1, 1, 6] * 1e-3 + 1000.0           # offset much larger than the range
     x[0, 0, 1, 64:96, 7] = 60000.0
     x[0, 0, 1, 70, 7] = -60000.0
+    x[0, 1, 1, 7, 0:32:2] = 65504.0                         # 15 * fp16(131008 / 15) - 65504 = 65536: saturates
+    x[0, 1, 1, 7, 1:32:2] = -65504.0
+    x[0, 0, 0, 96:128:2, 9] = 65504.0                       # the same along tokens for K
+    x[0, 0, 0, 97:128:2, 9] = -65504.0
     for bits in (2, 3, 4, 8):
         check_contiguous(ref, x, bits, bits, 32, 32)
 
