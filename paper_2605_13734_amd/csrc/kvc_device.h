@@ -69,6 +69,23 @@ template <int DT> __device__ __forceinline__ float elem_f32(const u32x4 &r, int 
     return (e & 1) ? hi_f32<DT>(r[e >> 1]) : lo_f32<DT>(r[e >> 1]);
 }
 
+// 1.0f in a register the optimizer cannot see through
+__device__ __forceinline__ float opaque_one()
+{
+    float v;
+    asm("v_mov_b32 %0, 1.0" : "=v"(v));
+    return v;
+}
+
+// element e minus `zero`, rounded once to fp32.  For fp16 this is written as fma(x, 1, -zero),
+// which the mixed-precision FMA computes straight from the 16-bit half of the register (the
+// product with one is exact, so the result equals the rounded difference).
+template <int DT> __device__ __forceinline__ float elem_minus(const u32x4 &r, int e, float zero, float one)
+{
+    if (DT == DT_F16) return __builtin_fmaf(elem_f32<DT>(r, e), one, -zero);
+    return elem_f32<DT>(r, e) - zero;
+}
+
 __device__ __forceinline__ float f16_bits_to_f32(uint32_t h)
 {
     return (float)__builtin_bit_cast(_Float16, (uint16_t)h);
@@ -207,13 +224,14 @@ template <int BITS, int DT> __device__ __forceinline__ GroupParams make_group(fl
     return g;
 }
 
-// code = clamp(round_half_even((x - zero) * inv), 0, 2^bits - 1); two rounded fp32 operations.
+// code = clamp(round_half_even((x - zero) * inv), 0, 2^bits - 1); two rounded fp32 operations
+// (`centered` is the first).
 // Returns the rounded value as a float; CLAMP = false is for groups whose codes cannot leave
 // the range (GroupParams::clamp).
-template <int BITS, bool CLAMP> __device__ __forceinline__ float quantize_f(float x, float zero, float inv)
+template <int BITS, bool CLAMP> __device__ __forceinline__ float quantize_f(float centered, float inv)
 {
     constexpr float qmax = (float)((1 << BITS) - 1);
-    float t = (x - zero) * inv;
+    float t = centered * inv;
     if (CLAMP) t = __builtin_amdgcn_fmed3f(t, 0.0f, qmax);
     return __builtin_rintf(t);
 }

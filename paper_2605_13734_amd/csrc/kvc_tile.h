@@ -168,11 +168,11 @@ __device__ __forceinline__ void k_group_params(const u32x4 *raw, uint8_t *xch, u
 
 // Quantize the lane's 8 channels of one row with per-channel parameters (K).
 template <int BITS, int DT, bool CLAMP>
-__device__ __forceinline__ u32x2 k_quant_row(const u32x4 &raw, const KParams &kp)
+__device__ __forceinline__ u32x2 k_quant_row(const u32x4 &raw, const KParams &kp, float one)
 {
     float q[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) q[e] = quantize_f<BITS, CLAMP>(elem_f32<DT>(raw, e), kp.zero[e], kp.inv[e]);
+    for (int e = 0; e < 8; ++e) q[e] = quantize_f<BITS, CLAMP>(elem_minus<DT>(raw, e, kp.zero[e], one), kp.inv[e]);
     return pack8<BITS>(q);
 }
 
@@ -249,11 +249,11 @@ __device__ __forceinline__ void v_pass_params(const u32x4 raw[8], VParams &vp)
 }
 
 template <int BITS, int DT, bool CLAMP>
-__device__ __forceinline__ u32x2 v_quant_row(const u32x4 &raw, float zero, float inv)
+__device__ __forceinline__ u32x2 v_quant_row(const u32x4 &raw, float zero, float inv, float one)
 {
     float q[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) q[e] = quantize_f<BITS, CLAMP>(elem_f32<DT>(raw, e), zero, inv);
+    for (int e = 0; e < 8; ++e) q[e] = quantize_f<BITS, CLAMP>(elem_minus<DT>(raw, e, zero, one), inv);
     return pack8<BITS>(q);
 }
 
@@ -280,12 +280,13 @@ template <int BITS, int DT, int P, bool SUB, bool CLAMP, bool FULL>
 __device__ __forceinline__ void k_emit_rows(const u32x4 *raw, const KParams &kp, uint8_t *base, int rows)
 {
     const int rsub = lane_id() >> 4;
+    const float one = opaque_one();
 #pragma unroll
     for (int p = 0; p < P; ++p)
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int r = p * kPassRows + 4 * i + rsub;
-            u32x2 w = k_quant_row<BITS, DT, CLAMP>(raw[p * 8 + i], kp);
+            u32x2 w = k_quant_row<BITS, DT, CLAMP>(raw[p * 8 + i], kp, one);
             if (BITS == 3) w[0] = quad_words_from_24(w[0]);
             if (FULL || r < rows) store_codes<BITS>(code_row<BITS, SUB>(base, r), w);
         }
@@ -311,10 +312,11 @@ __device__ __forceinline__ void v_emit_rows(const u32x4 raw[8], const VParams &v
 {
     constexpr int LANES = GV / 8, NG = kDim / GV;
     const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
+    const float one = opaque_one();
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int r = 4 * i + rsub;
-        u32x2 w = v_quant_row<BITS, DT, CLAMP>(raw[i], vp.zero[i], vp.inv[i]);
+        u32x2 w = v_quant_row<BITS, DT, CLAMP>(raw[i], vp.zero[i], vp.inv[i], one);
         if (BITS == 3) w[0] = quad_words_from_24(w[0]);
         if (FULL || r < rows) {
             store_codes<BITS>(code_row<BITS, SUB>(base, r), w);
