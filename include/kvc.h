@@ -170,6 +170,22 @@ int kvc_check_block_table(const int32_t *table, int64_t entries, int32_t num_phy
  */
 int kvc_trace(void **hip_events, int32_t capacity);
 
+/*
+ * Device self-test of the quantizer's arithmetic shortcuts (stage Q of section 5.1 fixes the
+ * results; the kernels reach them with cheaper instruction sequences).  Each count is the
+ * number of inputs, over the whole domain a shortcut is used on, for which it differs from
+ * the plain IEEE operation; every count must be zero.
+ *   counts[0..3]  (max - min) / (2^b - 1) for b = 2, 3, 4, 8: all floats in [0, 2^17]
+ *   counts[4]     1 / scale: all positive finite fp16 scales
+ *   counts[5]     x - zero read from a packed fp16 pair: all pairs of finite fp16 values
+ *   counts[6]     float -> byte with insertion: round-to-nearest-even, all floats in [0, 255]
+ * `counts` is DEVICE memory, KVC_SELFTEST_COUNTS 64-bit words, 8-byte aligned, owned by the
+ * caller; it is cleared and filled on `stream` (asynchronous: synchronize before reading).
+ * Returns KVC_OK, KVC_ERR_ARG for a null pointer, KVC_ERR_DEVICE if a launch failed.
+ */
+#define KVC_SELFTEST_COUNTS 8
+int kvc_selftest(uint64_t *counts, void *stream);
+
 const char *kvc_status_string(int status);
 
 #ifdef __cplusplus

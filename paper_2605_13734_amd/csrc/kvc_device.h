@@ -225,42 +225,55 @@ template <int BITS, int DT> __device__ __forceinline__ GroupParams make_group(fl
 }
 
 // code = clamp(round_half_even((x - zero) * inv), 0, 2^bits - 1); two rounded fp32 operations
-// (`centered` is the first).
-// Returns the rounded value as a float; CLAMP = false is for groups whose codes cannot leave
-// the range (GroupParams::clamp).
-template <int BITS, bool CLAMP> __device__ __forceinline__ float quantize_f(float centered, float inv)
+// (the centered value x - zero is the first, its product with inv the second).
+//
+// codes8 turns the 8 products of one lane into BITS bytes, element i at bits
+// [i*BITS, i*BITS+BITS), low bits first.  CLAMP = false is for groups whose codes cannot leave
+// the range (GroupParams::clamp).  For 2, 4 and 8 bits the rounding is done by the
+// float-to-byte conversion that inserts its result into a chosen byte of a word (round to
+// nearest even on [0, 255], checked by kvc_selftest); the bytes are laid out so that one or
+// two shifted ORs finish the word.  3-bit codes are rounded as floats, summed with their place
+// values in fp32 (exact below 2^24) and converted once.
+template <int BITS, bool CLAMP> __device__ __forceinline__ u32x2 codes8(float t[8])
 {
     constexpr float qmax = (float)((1 << BITS) - 1);
-    float t = centered * inv;
-    if (CLAMP) t = __builtin_amdgcn_fmed3f(t, 0.0f, qmax);
-    return __builtin_rintf(t);
-}
-
-// ---- bit packing: element i of a row at bits [i*BITS, i*BITS+BITS) ------------------------
-
-// The 8 codes of one lane (integers held as floats) -> BITS bytes, low bits first.  Codes are
-// summed with their place values in fp32 (exact below 2^24) and converted once per word part.
-template <int BITS> __device__ __forceinline__ u32x2 pack8(const float q[8])
-{
+    if (CLAMP) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t[e] = __builtin_amdgcn_fmed3f(t[e], 0.0f, qmax);
+    }
     u32x2 r;
     r[1] = 0;
     if (BITS == 8) {
-        const float a = __builtin_fmaf(q[1], 256.0f, q[0]), b = __builtin_fmaf(q[3], 256.0f, q[2]);
-        const float c = __builtin_fmaf(q[5], 256.0f, q[4]), d = __builtin_fmaf(q[7], 256.0f, q[6]);
-        r[0] = (uint32_t)a | ((uint32_t)b << 16);
-        r[1] = (uint32_t)c | ((uint32_t)d << 16);
-    } else if (BITS == 4) {
-        float lo = q[0], hi = q[4];
+        uint32_t a = 0, b = 0;
 #pragma unroll
-        for (int e = 1; e < 4; ++e) {
-            lo = __builtin_fmaf(q[e], (float)(1 << (4 * e)), lo);
-            hi = __builtin_fmaf(q[4 + e], (float)(1 << (4 * e)), hi);
+        for (int e = 0; e < 4; ++e) {
+            a = __builtin_amdgcn_cvt_pk_u8_f32(t[e], e, a);
+            b = __builtin_amdgcn_cvt_pk_u8_f32(t[4 + e], e, b);
         }
-        r[0] = (uint32_t)lo | ((uint32_t)hi << 16);
-    } else {
-        float acc = q[0];
+        r[0] = a;
+        r[1] = b;
+    } else if (BITS == 4) {
+        uint32_t even = 0, odd = 0;                 // bytes: codes 0 2 4 6 and 1 3 5 7
 #pragma unroll
-        for (int e = 1; e < 8; ++e) acc = __builtin_fmaf(q[e], (float)(1 << (BITS * e)), acc);
+        for (int e = 0; e < 4; ++e) {
+            even = __builtin_amdgcn_cvt_pk_u8_f32(t[2 * e], e, even);
+            odd = __builtin_amdgcn_cvt_pk_u8_f32(t[2 * e + 1], e, odd);
+        }
+        r[0] = (odd << 4) | even;
+    } else if (BITS == 2) {
+        uint32_t even = 0, odd = 0;                 // bytes: codes 0 4 2 6 and 1 5 3 7
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int byte = ((e & 1) << 1) | (e >> 1);       // 0 2 1 3
+            even = __builtin_amdgcn_cvt_pk_u8_f32(t[2 * e], byte, even);
+            odd = __builtin_amdgcn_cvt_pk_u8_f32(t[2 * e + 1], byte, odd);
+        }
+        const uint32_t pairs = (odd << 2) | even;   // bytes: codes 01, 45, 23, 67
+        r[0] = (pairs | (pairs >> 12)) & 0xffffu;
+    } else {
+        float acc = __builtin_rintf(t[0]);
+#pragma unroll
+        for (int e = 1; e < 8; ++e) acc = __builtin_fmaf(__builtin_rintf(t[e]), (float)(1 << (BITS * e)), acc);
         r[0] = (uint32_t)acc;
     }
     return r;

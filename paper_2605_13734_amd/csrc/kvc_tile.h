@@ -170,10 +170,10 @@ __device__ __forceinline__ void k_group_params(const u32x4 *raw, uint8_t *xch, u
 template <int BITS, int DT, bool CLAMP>
 __device__ __forceinline__ u32x2 k_quant_row(const u32x4 &raw, const KParams &kp, float one)
 {
-    float q[8];
+    float t[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) q[e] = quantize_f<BITS, CLAMP>(elem_minus<DT>(raw, e, kp.zero[e], one), kp.inv[e]);
-    return pack8<BITS>(q);
+    for (int e = 0; e < 8; ++e) t[e] = elem_minus<DT>(raw, e, kp.zero[e], one) * kp.inv[e];
+    return codes8<BITS, CLAMP>(t);
 }
 
 // V: the lane's 8 channels of a row belong to one group shared with GV/8 - 1 neighbouring lanes.
@@ -251,10 +251,10 @@ __device__ __forceinline__ void v_pass_params(const u32x4 raw[8], VParams &vp)
 template <int BITS, int DT, bool CLAMP>
 __device__ __forceinline__ u32x2 v_quant_row(const u32x4 &raw, float zero, float inv, float one)
 {
-    float q[8];
+    float t[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) q[e] = quantize_f<BITS, CLAMP>(elem_minus<DT>(raw, e, zero, one), inv);
-    return pack8<BITS>(q);
+    for (int e = 0; e < 8; ++e) t[e] = elem_minus<DT>(raw, e, zero, one) * inv;
+    return codes8<BITS, CLAMP>(t);
 }
 
 // Where the packed codes of tile row r go: row-major (payload section) or, when SUB, the LDS

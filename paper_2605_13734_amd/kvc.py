@@ -17,7 +17,7 @@ DEV_BAD_BLOCK, DEV_BAD_HEADER, DEV_BAD_CHUNK, DEV_BAD_TABLE, DEV_SCAN_TIMEOUT = 
 
 SYMBOLS = ["kvc_plan", "kvc_plan_free", "kvc_payload_size", "kvc_workspace_size", "kvc_compress",
            "kvc_decompress", "kvc_payload_inspect", "kvc_check_block_table", "kvc_status_string",
-           "kvc_trace"]
+           "kvc_trace", "kvc_selftest"]
 
 
 class Strategy(C.Structure):
@@ -75,6 +75,7 @@ def load():
                                           C.POINTER(C.c_uint64)]
         L.kvc_check_block_table.argtypes = [C.c_void_p, C.c_int64, C.c_int32]
         L.kvc_trace.argtypes = [C.c_void_p, C.c_int32]
+        L.kvc_selftest.argtypes = [C.c_void_p, C.c_void_p]
         L.kvc_status_string.argtypes = [C.c_int]
         L.kvc_status_string.restype = C.c_char_p
         _lib = L
@@ -178,6 +179,14 @@ def payload_inspect(header_bytes):
 def trace(events, capacity):
     """kvc_trace: install (or, with None, remove) an array of hipEvent_t handles."""
     return load().kvc_trace(events, capacity)
+
+
+SELFTEST_COUNTS = 8
+
+
+def selftest(counts_dev_ptr, stream=0):
+    """kvc_selftest: counts_dev_ptr is the device address of SELFTEST_COUNTS 64-bit words."""
+    return load().kvc_selftest(counts_dev_ptr, stream)
 
 
 def check_block_table(table_host, num_phys_blocks):
