@@ -19,6 +19,31 @@
 
 namespace kvc {
 
+// Optional per-phase cycle counts of the coder kernels (development builds only: compile with
+// -DKVC_PHASE_CLOCKS and read g_phase_clocks through kvc_phase_clocks).
+#ifdef KVC_PHASE_CLOCKS
+__device__ unsigned long long g_phase_clocks[1024][2][16];      // rows spread the atomics
+#define PHASE_START()                                             \
+    unsigned long long phase_t = clock64(), phase_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}
+#define PHASE(k, i)                                               \
+    do {                                                          \
+        const unsigned long long phase_n = clock64();             \
+        phase_acc[i] += phase_n - phase_t;                        \
+        phase_t = phase_n;                                        \
+    } while (0)
+#define PHASE_END(k)                                                                              \
+    do {                                                                                          \
+        if (lane_id() == 0)                                                                       \
+            for (int i = 0; i < 8; ++i)                                                           \
+                if (phase_acc[i]) atomicAdd(&g_phase_clocks[blockIdx.x & 1023][k][i], phase_acc[i]); \
+    } while (0)
+#else
+#define PHASE_START() do {} while (0)
+#define PHASE(k, i) do {} while (0)
+#define PHASE_END(k) do {} while (0)
+#endif
+
+
 constexpr unsigned long long kFlagAgg = 1ull << 62, kFlagPrefix = 2ull << 62, kValueMask = (1ull << 62) - 1;
 constexpr int kSpinLimit = 1 << 20;
 
@@ -29,7 +54,23 @@ template <int BITS> struct ChunkGeom {
     static constexpr int kWords = kSubBytes / 4;           // words a lane holds for its sub-block
     static constexpr int kLds = kSubs * kSubStride;        // LDS bytes per wave
     static constexpr int kWaves = BITS == 8 ? 2 : 4;       // encoder: waves (= chunks) per workgroup
-    static constexpr int kDecWaves = BITS == 8 ? 2 : 4;    // decoder: waves (= chunks) per workgroup
+    static constexpr int kDecWaves = BITS == 8 ? 2 : 4;    // decoder: waves per workgroup (they share the 8 KB table)
+};
+
+// The decoder's LDS layout of a chunk.  4-bit codes: sub-blocks without padding, pieces rotated
+// (fetch_codes, LAYOUT 2), 8 KB per wave, so that four workgroups of four waves and their 8 KB
+// tables fill a compute unit's 160 KB exactly.  Other widths: the encoder's padded layout.
+template <int BITS> struct DecGeom {
+    static constexpr bool kRotated = BITS == 4;
+    static constexpr int kLayout = kRotated ? 2 : 1;
+    static constexpr int kStride = kRotated ? ChunkGeom<BITS>::kSubBytes : ChunkGeom<BITS>::kSubStride;
+    static constexpr int kLds = kSubs * kStride;
+    // address of 16-byte piece `piece` of sub-block `sub`
+    static __device__ __forceinline__ uint8_t *piece_ptr(uint8_t *lds, uint32_t sub, uint32_t piece)
+    {
+        if (kRotated) return lds + sub * kStride + (((piece + sub) & 7u) << 4);
+        return lds + sub * kStride + piece * 16;
+    }
 };
 
 // ---- chunk <-> LDS -------------------------------------------------------------------------
@@ -419,6 +460,7 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void encode_kernel(Co
     __shared__ uint32_t s_ticket;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
+    PHASE_START();
     if (tid == 0) s_ticket = atomicAdd(a.ws.ticket, 1u);
     for (int k = tid; k < 256; k += NW * 64) {
         const uint32_t e = a.ws.enc[(IS_V ? 256 : 0) + k];       // code | length << 16
@@ -426,6 +468,7 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void encode_kernel(Co
         enc.code[k] = (uint16_t)((e & 0xfffu) | ((e >> 16) << 12));
     }
     __syncthreads();
+    PHASE(0, 0);
     const long long ticket = s_ticket;                 // global order over K and V workgroups
     const long long chunk = (ticket - a.wg_base) * NW + wave;
     const bool live = chunk < a.chunks;
@@ -442,6 +485,7 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void encode_kernel(Co
         quantize_chunk<BITS, G, DT, IS_V, DENSE>(a.q, c, lds, true, bad);
         if (bad) atomicOr(a.q.status, KVC_DEV_BAD_BLOCK);
         wave_sync();
+        PHASE(0, 1);
         load_sub<BITS>(lds, sym);
         const int have = min(max(rows - 2 * lane, 0), 2);        // valid rows of this sub-block
         uint32_t bits0 = 0, bits = 0;
@@ -454,6 +498,7 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void encode_kernel(Co
         const uint32_t coded_bytes = (2 * kSubs + 4 * ((total + 31) / 32) + 15) & ~15u;
         coded = coded_bytes < raw_bytes;
         body_units = (coded ? coded_bytes : raw_bytes) / 16;
+        PHASE(0, 2);
         if (coded) {
             wave_sync();                                          // every lane holds its symbols
             u32x4 zero = {0, 0, 0, 0};
@@ -478,8 +523,10 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void encode_kernel(Co
             wave_sync();
         }
     }
+    PHASE(0, 3);
     if (lane == 0) s_units[wave] = body_units;
     __syncthreads();
+    PHASE(0, 4);
 
     // ---- single-pass prefix sum over workgroups, in ticket order ------------------------------
     if (wave == 0) {
@@ -544,7 +591,9 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void encode_kernel(Co
             }
         }
     }
+    if (wave == 0) PHASE(0, 5);
     __syncthreads();
+    PHASE(0, 6);
     const unsigned long long excl = s_excl;
     if (!live || excl == ~0ull) return;
     unsigned long long mine = excl;
@@ -566,6 +615,8 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void encode_kernel(Co
                 p[k] = v;
             }
     }
+    PHASE(0, 7);
+    PHASE_END(0);
 }
 
 // ---- decoder ---------------------------------------------------------------------------------
@@ -631,14 +682,16 @@ template <int BITS, int DT, bool IS_V, bool DENSE>
 __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel(CoderArgs a)
 {
     using Geo = ChunkGeom<BITS>;
+    using Dec = DecGeom<BITS>;
     constexpr int W = Geo::kWords, NW = Geo::kDecWaves;
-    __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * Geo::kLds];
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * Dec::kLds];
     __shared__ uint16_t lut[4096];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
     const long long chunk = (long long)blockIdx.x * NW + wave;
     const bool live = chunk < a.chunks;
-    uint8_t *lds = lds_all + wave * Geo::kLds;
+    uint8_t *lds = lds_all + wave * Dec::kLds;
+    PHASE_START();
 
     // Round trip 1: the chunk's two directory entries and the status word, with the decode
     // table right behind them.
@@ -685,6 +738,7 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
     for (int i = 0; i < LUTN; ++i) ((u32x4 *)lut)[tid + i * NW * 64] = lutv[i];
     __syncthreads();
     if (!ok) return;
+    PHASE(1, 0);
 
     if (size == raw_bytes) {
         // stored raw: scatter the packed rows into the sub-block layout
@@ -693,7 +747,7 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
             const uint32_t o = (k * 64 + lane) * 16;
             if (o < raw_bytes) {
                 const uint32_t sub = o / Geo::kSubBytes, in = o - sub * Geo::kSubBytes;
-                *(u32x4 *)(lds + sub * Geo::kSubStride + in) = bodyv[k];
+                *(u32x4 *)Dec::piece_ptr(lds, sub, in / 16) = bodyv[k];
             }
         }
         wave_sync();
@@ -704,6 +758,7 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
             if (o < size) *(u32x4 *)(lds + o) = bodyv[k];
         }
         wave_sync();
+        PHASE(1, 1);
         const uint32_t bits = ((const uint16_t *)lds)[lane];
         const uint32_t incl = wave_inclusive_sum(bits);
         const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
@@ -731,8 +786,16 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
         if (have > 0) decode_half<W>(sym, lut, 0, br);
         if (have > 1) decode_half<W>(sym, lut, 1, br);
         wave_sync();                                   // all lanes are done reading the coded words
-        store_sub<BITS>(lds, sym);
+        {
+#pragma unroll
+            for (int q = 0; q < W / 4; ++q) {
+                u32x4 v;
+                v[0] = sym[4 * q]; v[1] = sym[4 * q + 1]; v[2] = sym[4 * q + 2]; v[3] = sym[4 * q + 3];
+                *(u32x4 *)Dec::piece_ptr(lds, lane, q) = v;
+            }
+        }
         wave_sync();
+        PHASE(1, 2);
     }
 
     // dequantize the rows from LDS; the metadata of a pass is in flight one pass ahead
@@ -750,10 +813,12 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
             if (!IS_V) load_meta_k(a.q, c, (p + 1) * kPassRows, mk0, mk1);
             else load_meta_v(a.q, c, (p + 1) * kPassRows, mv);
         }
-        dequant_pass<BITS, DT, IS_V, DENSE, true>(lds_row<BITS>(lds, p * kPassRows), scale, zero, clamp, a.q.x, c.head_off,
-                                                  c.row0 + p * kPassRows, c.rows - p * kPassRows, bad);
+        dequant_pass<BITS, DT, IS_V, DENSE, Dec::kLayout>(lds, scale, zero, clamp, a.q.x, c.head_off, c.row0 + p * kPassRows,
+                                                          c.rows - p * kPassRows, bad, p * kPassRows);
     }
     if (bad) atomicOr(a.q.status, KVC_DEV_BAD_BLOCK);
+    PHASE(1, 3);
+    PHASE_END(1);
 }
 
 // ---- launchers ----------------------------------------------------------------------------------
@@ -871,3 +936,24 @@ int launch_decode_section(int bits, int group, int dtype, const CoderArgs &a, hi
 }
 
 }  // namespace kvc
+
+#ifdef KVC_PHASE_CLOCKS
+// out: HOST memory, 32 64-bit words (encoder phases 0..15, decoder phases 0..15); reset != 0 clears
+extern "C" int kvc_phase_clocks(uint64_t *out, int reset)
+{
+    static uint64_t rows[1024][2][16];
+    if (hipDeviceSynchronize() != hipSuccess) return -1;
+    if (out) {
+        if (hipMemcpyFromSymbol(rows, HIP_SYMBOL(kvc::g_phase_clocks), sizeof(rows)) != hipSuccess) return -1;
+        for (int i = 0; i < 32; ++i) out[i] = 0;
+        for (int r = 0; r < 1024; ++r)
+            for (int i = 0; i < 32; ++i) out[i] += rows[r][i / 16][i % 16];
+    }
+    if (reset) {
+        for (int r = 0; r < 1024; ++r)
+            for (int i = 0; i < 32; ++i) rows[r][i / 16][i % 16] = 0;
+        if (hipMemcpyToSymbol(HIP_SYMBOL(kvc::g_phase_clocks), rows, sizeof(rows)) != hipSuccess) return -1;
+    }
+    return 0;
+}
+#endif

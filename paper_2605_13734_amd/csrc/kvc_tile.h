@@ -402,17 +402,35 @@ __device__ __forceinline__ bool v_meta_floats(const uint32_t mw[8], float scale[
     return __builtin_amdgcn_ballot_w64(top > 65504.0f) != 0;
 }
 
-template <int BITS, int DT, bool IS_V, bool DENSE, bool SUB, bool CLAMP>
+// The lane's packed codes of row r.  LAYOUT 0: rows back to back (payload section); 1: the
+// coder's LDS layout, sub-blocks of two rows, each padded by 16 bytes; 2: the decoder's LDS
+// layout for 4-bit codes, sub-blocks of two rows without padding whose eight 16-byte pieces are
+// rotated by the sub-block's number (piece p of sub-block s sits at position (p + s) mod 8), so
+// that both the row-wise and the sub-block-wise accesses spread over the banks.
+template <int BITS, int LAYOUT> __device__ __forceinline__ u32x2 fetch_codes(uint8_t *codes, int r)
+{
+    if (LAYOUT == 2) {
+        static_assert(LAYOUT != 2 || BITS == 4, "rotated layout is for 4-bit codes");
+        const int col = lane_id() & 15, sub = r >> 1, piece = ((r & 1) << 2) + (col >> 2);
+        u32x2 w;
+        w[0] = *(const uint32_t *)(codes + sub * 128 + (((piece + sub) & 7) << 4) + ((col & 3) << 2));
+        w[1] = 0;
+        return w;
+    }
+    return load_row_codes<BITS>(code_row<BITS, LAYOUT == 1>(codes, r));
+}
+
+template <int BITS, int DT, bool IS_V, bool DENSE, int LAYOUT, bool CLAMP>
 __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float scale[8], const float zero[8],
                                                   const TensorView &x, long long head_off, long long row0, int rows,
-                                                  bool &bad)
+                                                  bool &bad, int row_base)
 {
     const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
     if (DENSE && rows >= kPassRows) {
         u32x4 *dst = (u32x4 *)(x.base + head_off + (row0 + rsub) * kDim + col * 8);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const u32x2 w = load_row_codes<BITS>(code_row<BITS, SUB>(codes, 4 * i + rsub));
+            const u32x2 w = fetch_codes<BITS, LAYOUT>(codes, row_base + 4 * i + rsub);
             const u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w, scale[i], zero[i])
                                    : dequant_row<BITS, DT, CLAMP>(w, scale, zero);
             __builtin_nontemporal_store(out, dst + i * 64);
@@ -423,7 +441,7 @@ __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float sc
     for (int i = 0; i < 8; ++i) {
         const int r = 4 * i + rsub;
         const bool ok = r < rows;                       // uniform over each quad of lanes
-        const u32x2 w = load_row_codes<BITS>(code_row<BITS, SUB>(codes, ok ? r : 0));
+        const u32x2 w = fetch_codes<BITS, LAYOUT>(codes, row_base + (ok ? r : 0));
         const u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w, scale[i], zero[i])
                                : dequant_row<BITS, DT, CLAMP>(w, scale, zero);
         if (ok) {
@@ -435,15 +453,16 @@ __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float sc
     }
 }
 
-// Dequantize the pass whose packed rows start at `codes` (row-major, or the coder's LDS layout
-// when SUB) and store its `rows` existing rows at token rows row0... of head `head_off`.
+// Dequantize the pass whose packed rows are rows row_base... of `codes` (see fetch_codes for
+// LAYOUT) and store its `rows` existing rows at token rows row0... of head `head_off`.
 // K: scale / zero per channel of the lane; V: per row of the lane.
-template <int BITS, int DT, bool IS_V, bool DENSE, bool SUB>
+template <int BITS, int DT, bool IS_V, bool DENSE, int LAYOUT>
 __device__ __forceinline__ void dequant_pass(uint8_t *codes, const float scale[8], const float zero[8], bool clamp,
-                                             const TensorView &x, long long head_off, long long row0, int rows, bool &bad)
+                                             const TensorView &x, long long head_off, long long row0, int rows, bool &bad,
+                                             int row_base = 0)
 {
-    if (clamp) dequant_pass_rows<BITS, DT, IS_V, DENSE, SUB, true>(codes, scale, zero, x, head_off, row0, rows, bad);
-    else dequant_pass_rows<BITS, DT, IS_V, DENSE, SUB, false>(codes, scale, zero, x, head_off, row0, rows, bad);
+    if (clamp) dequant_pass_rows<BITS, DT, IS_V, DENSE, LAYOUT, true>(codes, scale, zero, x, head_off, row0, rows, bad, row_base);
+    else dequant_pass_rows<BITS, DT, IS_V, DENSE, LAYOUT, false>(codes, scale, zero, x, head_off, row0, rows, bad, row_base);
 }
 
 }  // namespace kvc
