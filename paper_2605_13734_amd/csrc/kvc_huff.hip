@@ -44,7 +44,12 @@ __device__ unsigned long long g_phase_clocks[1024][2][16];      // rows spread t
 #endif
 
 
-constexpr unsigned long long kFlagAgg = 1ull << 62, kFlagPrefix = 2ull << 62, kValueMask = (1ull << 62) - 1;
+// Scan state of a workgroup: bits 63:62 = 2 once its inclusive prefix (bits 0..39) is known.
+// Before that, every wave adds its chunk's size to bits 0..39 and its share of kAggComplete to
+// the arrival count in bits 40..47; the sum of sizes is the workgroup's aggregate once the
+// count is complete.  Sizes and prefixes are in 16-byte units.
+constexpr unsigned long long kFlagPrefix = 2ull << 62, kValueMask = (1ull << 40) - 1;
+constexpr int kAggShift = 40, kAggComplete = 4;
 constexpr int kSpinLimit = 1 << 20;
 
 template <int BITS> struct ChunkGeom {
@@ -498,6 +503,11 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void encode_kernel(Co
         const uint32_t coded_bytes = (2 * kSubs + 4 * ((total + 31) / 32) + 15) & ~15u;
         coded = coded_bytes < raw_bytes;
         body_units = (coded ? coded_bytes : raw_bytes) / 16;
+        // the size goes out before the code words are written, so that successors see this
+        // workgroup's aggregate as early as possible
+        if (lane == 0)
+            __hip_atomic_fetch_add(&a.ws.state[ticket], ((unsigned long long)(kAggComplete / NW) << kAggShift) | body_units,
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         PHASE(0, 2);
         if (coded) {
             wave_sync();                                          // every lane holds its symbols
@@ -524,6 +534,9 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void encode_kernel(Co
         }
     }
     PHASE(0, 3);
+    if (!live && lane == 0)
+        __hip_atomic_fetch_add(&a.ws.state[ticket], (unsigned long long)(kAggComplete / NW) << kAggShift, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
     if (lane == 0) s_units[wave] = body_units;
     __syncthreads();
     PHASE(0, 4);
@@ -535,15 +548,14 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void encode_kernel(Co
         unsigned long long excl = 0;
         bool timeout = false;
         if (ticket > 0) {
-            if (lane == 0)
-                __hip_atomic_store(&a.ws.state[ticket], kFlagAgg | agg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             long long idx = ticket - 1;
             int spins = 0;
             for (;;) {
                 const long long j = idx - lane;
                 unsigned long long v = kFlagPrefix;
                 if (j >= 0) v = __hip_atomic_load(&a.ws.state[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const unsigned flag = (unsigned)(v >> 62);
+                // 2: inclusive prefix, 1: complete aggregate, 0: not all waves have reported yet
+                const unsigned flag = (v >> 62) == 2 ? 2u : ((unsigned)(v >> kAggShift) & 0xffu) == (unsigned)kAggComplete ? 1u : 0u;
                 if (__builtin_amdgcn_ballot_w64(flag == 0) != 0) {
                     if (++spins > kSpinLimit) { timeout = true; break; }
                     __builtin_amdgcn_s_sleep(8);
