@@ -208,11 +208,16 @@ __global__ __launch_bounds__(64) void hist_kernel(CoderArgs a)
 // Huffman code lengths of 256 symbols from weights w[] (LDS), joining the two nodes with the
 // smallest (weight, id) each time: leaves have id = symbol, the k-th joined node id 256 + k.
 // Leaves sorted by (weight, symbol) form one queue, joined nodes (created in non-decreasing
-// weight order) the other; the heads of the two queues are the two candidates.
+// weight order) the other; the heads of the two queues are the two candidates.  The joining
+// itself is sequential (lane 0): it keeps the two front weights of either queue in registers
+// and reads one position ahead, so that no step waits for LDS.  Weights stay far below 2^32
+// (a table sample is at most 16 chunks of 16 KB).
 struct BuildLds {
-    unsigned long long w[512];     // node weights: leaves 0..255, joined nodes 256..510
-    uint16_t sorted[256];          // leaves by (weight, symbol)
-    uint16_t parent[512];
+    uint32_t w[256];               // leaf weights by symbol
+    uint32_t sw[258];              // leaf weights in queue order, then two sentinels
+    uint32_t wi[256];              // weights of the joined nodes, in order of creation
+    uint16_t parent_leaf[256];     // by queue position: index of the joined node above the leaf
+    uint16_t parent_int[256];      // by joined node: index of the joined node above it
     uint8_t len[256];
     uint32_t count[16], first[16], start[16];
     uint16_t by_len[256];          // symbols by (length, symbol)
@@ -221,47 +226,68 @@ struct BuildLds {
 
 __device__ __forceinline__ void build_lengths(BuildLds &s)
 {
+    constexpr uint32_t kNone = 0xffffffffu;
     const int lane = lane_id();
     for (;;) {
-        // rank of each leaf among all leaves
-        for (int k = lane; k < 256; k += 64) {
-            const unsigned long long wk = s.w[k];
+        // position of each leaf among all leaves
+        int pos[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int k = lane + 64 * j;
+            const uint32_t wk = s.w[k];
             int rank = 0;
             for (int t = 0; t < 256; ++t) {
-                const unsigned long long wt = s.w[t];
+                const uint32_t wt = s.w[t];
                 rank += (wt < wk || (wt == wk && t < k)) ? 1 : 0;
             }
-            s.sorted[rank] = (uint16_t)k;
+            pos[j] = rank;
+            s.sw[rank] = wk;
         }
+        if (lane < 2) s.sw[256 + lane] = kNone;
+        if (lane == 0) s.longest = 0;
         wave_sync();
         if (lane == 0) {
-            int lq = 0, iq = 256, made = 256;          // queue heads; next joined-node id
+            uint32_t wl = s.sw[0], wl1 = s.sw[1];      // front of the leaf queue and the one behind it
+            uint32_t wj = kNone, wj1 = kNone;          // same for the queue of joined nodes
+            int lq = 0, jq = 0, made = 0;
             for (int k = 0; k < 255; ++k) {
-                int pick[2];
+                uint32_t sum = 0;
+#pragma unroll
                 for (int j = 0; j < 2; ++j) {
-                    const bool has_leaf = lq < 256, has_int = iq < made;
-                    bool take_leaf = has_leaf;
-                    if (has_leaf && has_int) take_leaf = s.w[s.sorted[lq]] <= s.w[iq];   // leaf ids are lower
-                    pick[j] = take_leaf ? (int)s.sorted[lq++] : iq++;
+                    if (wl <= wj) {                    // a leaf wins a tie: its id is lower
+                        sum += wl;
+                        s.parent_leaf[lq] = (uint16_t)made;
+                        ++lq;
+                        wl = wl1;
+                        wl1 = s.sw[lq + 1];
+                    } else {
+                        sum += wj;
+                        s.parent_int[jq] = (uint16_t)made;
+                        ++jq;
+                        wj = wj1;
+                        wj1 = jq + 1 < made ? s.wi[jq + 1] : kNone;
+                    }
                 }
-                s.w[made] = s.w[pick[0]] + s.w[pick[1]];
-                s.parent[pick[0]] = s.parent[pick[1]] = (uint16_t)made;
+                s.wi[made] = sum;
+                if (made == jq) wj = sum;
+                else if (made == jq + 1) wj1 = sum;
                 ++made;
             }
-            s.parent[510] = 0xffff;
-            s.longest = 0;
         }
         wave_sync();
-        for (int k = lane; k < 256; k += 64) {
-            int d = 0;
-            for (int i = k; s.parent[i] != 0xffff && d < 512; i = s.parent[i]) ++d;
-            s.len[k] = (uint8_t)d;
-            atomicMax(&s.longest, d);
+        int deepest = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int d = 1;
+            for (int i = s.parent_leaf[pos[j]]; i != 254 && d < 256; i = s.parent_int[i]) ++d;
+            s.len[lane + 64 * j] = (uint8_t)d;
+            deepest = max(deepest, d);
         }
+        atomicMax(&s.longest, deepest);
         wave_sync();
         if (s.longest <= kMaxLen) return;
         for (int k = lane; k < 256; k += 64) {
-            unsigned long long v = (s.w[k] + 1) >> 1;
+            const uint32_t v = (s.w[k] + 1) >> 1;
             s.w[k] = v < 1 ? 1 : v;
         }
         wave_sync();
@@ -320,7 +346,7 @@ __global__ __launch_bounds__(64) void build_tables_kernel(CoderArgs a)
     __shared__ BuildLds s;
     const int sec = blockIdx.x, lane = lane_id();
     const uint32_t *hist = a.ws.hist + 256 * sec;
-    for (int k = lane; k < 256; k += 64) s.w[k] = (unsigned long long)hist[k] + 1;
+    for (int k = lane; k < 256; k += 64) s.w[k] = hist[k] + 1;
     wave_sync();
     build_lengths(s);
     canonical_tables(s);
