@@ -294,9 +294,9 @@ __device__ __forceinline__ void build_lengths(BuildLds &s)
     }
 }
 
-// Canonical order tables from len[]: count / first code / start index per length, and the
-// symbols sorted by (length, symbol).  Returns false if the lengths are not a complete code.
-__device__ __forceinline__ bool canonical_tables(BuildLds &s)
+// Canonical order tables from len[]: count / first code / start index per length, and (ORDER)
+// the symbols sorted by (length, symbol).  Returns false if the lengths are not a complete code.
+template <bool ORDER> __device__ __forceinline__ bool canonical_tables(BuildLds &s)
 {
     const int lane = lane_id();
     if (lane < 16) s.count[lane] = 0;
@@ -322,13 +322,15 @@ __device__ __forceinline__ bool canonical_tables(BuildLds &s)
     wave_sync();
     ok = ok && s.longest == 1;
     if (__builtin_amdgcn_ballot_w64(!ok) != 0) return false;
-    for (int k = lane; k < 256; k += 64) {
-        const int L = s.len[k];
-        int rank = 0;
-        for (int t = 0; t < k; ++t) rank += (s.len[t] == L) ? 1 : 0;
-        s.by_len[s.start[L] + rank] = (uint16_t)k;
+    if (ORDER) {
+        for (int k = lane; k < 256; k += 64) {
+            const int L = s.len[k];
+            int rank = 0;
+            for (int t = 0; t < k; ++t) rank += (s.len[t] == L) ? 1 : 0;
+            s.by_len[s.start[L] + rank] = (uint16_t)k;
+        }
+        wave_sync();
     }
-    wave_sync();
     return true;
 }
 
@@ -340,6 +342,8 @@ __device__ __forceinline__ uint32_t code_of(const BuildLds &s, int sym)
     return s.first[L] + rank;
 }
 
+constexpr int kTableWaves = 8;      // waves that fill a decode table
+
 // grid = 2 workgroups of one wave: 0 builds the K table, 1 the V table
 __global__ __launch_bounds__(64) void build_tables_kernel(CoderArgs a)
 {
@@ -349,7 +353,7 @@ __global__ __launch_bounds__(64) void build_tables_kernel(CoderArgs a)
     for (int k = lane; k < 256; k += 64) s.w[k] = hist[k] + 1;
     wave_sync();
     build_lengths(s);
-    canonical_tables(s);
+    canonical_tables<false>(s);
     uint8_t *lens = a.payload + a.off_aux + 256 * sec;
     uint32_t *enc = a.ws.enc + 256 * sec;
     for (int k = lane; k < 256; k += 64) {
@@ -358,23 +362,31 @@ __global__ __launch_bounds__(64) void build_tables_kernel(CoderArgs a)
     }
 }
 
-// grid = 2 workgroups of one wave: decode tables from the lengths stored in the payload
-__global__ __launch_bounds__(64) void decode_prepare_kernel(CoderArgs a)
+// grid = 2 workgroups of kTableWaves waves: decode tables from the lengths stored in the payload
+__global__ __launch_bounds__(kTableWaves * 64) void decode_prepare_kernel(CoderArgs a)
 {
     __shared__ BuildLds s;
-    const int sec = blockIdx.x, lane = lane_id();
+    __shared__ int s_ok;
+    const int sec = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
     if (*a.q.status & KVC_DEV_BAD_HEADER) return;
-    const uint8_t *lens = a.payload + a.off_aux + 256 * sec;
-    for (int k = lane; k < 256; k += 64) s.len[k] = lens[k];
-    wave_sync();
+    if (wave == 0) {
+        const uint8_t *lens = a.payload + a.off_aux + 256 * sec;
+        for (int k = lane; k < 256; k += 64) s.len[k] = lens[k];
+        wave_sync();
+        const bool ok = canonical_tables<true>(s);
+        if (lane == 0) {
+            s_ok = ok ? 1 : 0;
+            if (!ok) atomicOr(a.q.status, KVC_DEV_BAD_TABLE);
+        }
+    }
+    __syncthreads();
     uint16_t *lut = a.ws.lut + 4096 * sec;
-    if (!canonical_tables(s)) {
-        if (lane == 0) atomicOr(a.q.status, KVC_DEV_BAD_TABLE);
-        for (int i = lane; i < 4096; i += 64) lut[i] = (uint16_t)(1u << 8);      // symbol 0, length 1
+    if (!s_ok) {
+        for (int i = tid; i < 4096; i += kTableWaves * 64) lut[i] = (uint16_t)(1u << 8);      // symbol 0, length 1
         return;
     }
     // entry i describes the code word that is a prefix of the 12-bit string i
-    for (int i = lane; i < 4096; i += 64) {
+    for (int i = tid; i < 4096; i += kTableWaves * 64) {
         uint16_t e = (uint16_t)(1u << 8);
         for (int L = 1; L <= kMaxLen; ++L) {
             const uint32_t c = (uint32_t)i >> (kMaxLen - L);
@@ -963,7 +975,7 @@ int launch_encode_section(int bits, int group, int dtype, const CoderArgs &a, hi
 
 int launch_decode_prepare(const CoderArgs &k, hipStream_t s)
 {
-    hipLaunchKernelGGL(decode_prepare_kernel, dim3(2), dim3(64), 0, s, k);
+    hipLaunchKernelGGL(decode_prepare_kernel, dim3(2), dim3(kTableWaves * 64), 0, s, k);
     return launched();
 }
 
