@@ -70,6 +70,43 @@ static float load_elem(const void *base, int dtype, int64_t idx)
     return dtype == REF_F16 ? ref_f16_to_f32(w) : ref_bf16_to_f32(w);
 }
 
+/* ------------------------------------------------------------------ transform T
+ *
+ * KVServe section 5.1 lists a Hadamard rotation (QuaRot) among the transformer modules that may
+ * precede the quantizer; the paper gives no formula.  Reading taken here: every head_dim-long row
+ * x of K and of V becomes y = s * H x, H the Walsh-Hadamard matrix in natural (Sylvester) order,
+ * H[i][j] = (-1)^popcount(i & j), and decompression applies s' * H to the reconstructed row.
+ * H H = dim * I, so s * s' = 1 / dim makes the pair an identity; with dim = 2^m the factors are
+ * the powers of two s = 2^-floor(m/2), s' = 2^-ceil(m/2) (1/8 and 1/16 for head_dim 128), which
+ * scale without rounding.  H x is computed by the fast transform, whose operation order is part
+ * of the definition because fp32 sums round: for h = 1, 2, 4, ..., dim/2, every pair (j, j + h)
+ * with bit h of j clear becomes (a + b, a - b), one fp32 operation each.  The scaled result is
+ * limited to the finite range of the tensor's type and rounded to it (nearest even).  A tensor
+ * stored unchanged (16 bits) is not transformed, so that this setting stays lossless.
+ */
+void ref_hadamard_row(const uint16_t *in, uint16_t *out, int dim, int dtype, int inverse)
+{
+    float x[1024];
+    int m = 0;
+    while ((1 << m) < dim) ++m;
+    for (int i = 0; i < dim; ++i) x[i] = dtype == REF_F16 ? ref_f16_to_f32(in[i]) : ref_bf16_to_f32(in[i]);
+    for (int h = 1; h < dim; h <<= 1)
+        for (int j = 0; j < dim; ++j)
+            if (!(j & h)) {
+                float a = x[j], b = x[j + h];
+                x[j] = a + b;
+                x[j + h] = a - b;
+            }
+    const float scale = 1.0f / (float)(1 << (inverse ? (m + 1) / 2 : m / 2));
+    const float top = dtype == REF_F16 ? 65504.0f : 3.3895313892515355e38f;
+    for (int i = 0; i < dim; ++i) {
+        float y = x[i] * scale;
+        if (y > top) y = top;
+        if (y < -top) y = -top;
+        out[i] = dtype == REF_F16 ? ref_f32_to_f16(y) : ref_f32_to_bf16(y);
+    }
+}
+
 static int64_t row_offset(const ref_layout *lay, int l, int h, int64_t t)
 {
     int64_t o = (int64_t)l * lay->stride_layer + (int64_t)h * lay->stride_head;
@@ -334,6 +371,8 @@ int ref_check_config(const ref_config *c)
     if (c->bits_v != 16 && (c->group_v < 1 || c->head_dim % c->group_v)) return REF_ERR_ARG;
     if (c->codec != 0 && c->codec != 1) return REF_ERR_ARG;
     if (c->codec == 1 && (c->bits_k == 16 || c->bits_v == 16)) return REF_ERR_UNSUPPORTED;
+    if (c->transform != 0 && c->transform != 1) return REF_ERR_ARG;
+    if (c->transform == 1 && ((c->head_dim & (c->head_dim - 1)) || c->head_dim > 1024)) return REF_ERR_UNSUPPORTED;
     return REF_OK;
 }
 
@@ -397,6 +436,19 @@ int ref_compress_head(const ref_config *c, int is_v, const void *src, const ref_
             memcpy(codes + t * D * 2, (const uint16_t *)src + row_offset(lay, l, h, t), (size_t)D * 2);
         return REF_OK;
     }
+    if (c->transform) {
+        /* T first: the quantizer then sees the transformed rows as its input tensor */
+        uint16_t *xt = (uint16_t *)malloc((size_t)(T * D) * 2 + 2);
+        if (!xt) return REF_ERR_ARG;
+        for (int64_t t = 0; t < T; ++t)
+            ref_hadamard_row((const uint16_t *)src + row_offset(lay, l, h, t), xt + t * D, D, c->dtype, 0);
+        ref_config plain = *c;
+        plain.transform = 0;
+        ref_layout rows = {0, 0, D, 0, 0, NULL};
+        int rc = ref_compress_head(&plain, is_v, xt, &rows, T, 0, 0, codes, meta);
+        free(xt);
+        return rc;
+    }
     uint8_t *q = (uint8_t *)malloc((size_t)(T * D) + 1);
     float *grp = (float *)malloc(sizeof(float) * (size_t)(c->group_k > D ? c->group_k : D));
     uint8_t *gq = (uint8_t *)malloc((size_t)(c->group_k > D ? c->group_k : D));
@@ -444,6 +496,19 @@ int ref_decompress_head(const ref_config *c, int is_v, const uint8_t *codes, con
         for (int64_t t = 0; t < T; ++t)
             memcpy(out + row_offset(lay, l, h, t), codes + t * D * 2, (size_t)D * 2);
         return REF_OK;
+    }
+    if (c->transform) {
+        /* reconstruct the transformed rows, then undo T row by row */
+        uint16_t *xt = (uint16_t *)malloc((size_t)(T * D) * 2 + 2);
+        if (!xt) return REF_ERR_ARG;
+        ref_config plain = *c;
+        plain.transform = 0;
+        ref_layout rows = {0, 0, D, 0, 0, NULL};
+        int rc = ref_decompress_head(&plain, is_v, codes, meta, T, 0, 0, xt, &rows);
+        for (int64_t t = 0; t < T && rc == REF_OK; ++t)
+            ref_hadamard_row(xt + t * D, out + row_offset(lay, l, h, t), D, c->dtype, 1);
+        free(xt);
+        return rc;
     }
     uint8_t *q = (uint8_t *)malloc((size_t)(T * D) + 1);
     if (!q) return REF_ERR_ARG;
@@ -572,6 +637,7 @@ static void write_header(uint8_t *p, const ref_config *c, int64_t T, const geome
     p[21] = (uint8_t)c->bits_v;
     put_u16(p + 22, (unsigned)c->group_k);
     put_u16(p + 24, (unsigned)c->group_v);
+    p[26] = (uint8_t)c->transform;
     put_u64(p + 32, (uint64_t)T);
     put_u64(p + 40, (uint64_t)total);
     put_u64(p + 48, (uint64_t)g->off_meta_k);  put_u64(p + 56, (uint64_t)g->meta_k);
@@ -597,6 +663,7 @@ int ref_inspect(const uint8_t *p, ref_config *c, int64_t *tokens, uint64_t *tota
     c->bits_v = p[21];
     c->group_k = (int32_t)get_u16(p + 22);
     c->group_v = (int32_t)get_u16(p + 24);
+    c->transform = p[26];
     if (tokens) *tokens = (int64_t)get_u64(p + 32);
     if (total_bytes) *total_bytes = get_u64(p + 40);
     if (sections) for (int i = 0; i < 10; ++i) sections[i] = get_u64(p + 48 + 8 * i);

@@ -48,6 +48,7 @@ typedef struct {
     int32_t group_k;            /* tokens per K group (one group per channel) */
     int32_t group_v;            /* channels per V group (one group per token) */
     int32_t codec;              /* 0 none, 1 huff8 */
+    int32_t transform;          /* 0 none, 1 Walsh-Hadamard over head_dim (ref_hadamard_row) */
 } ref_config;
 
 /* Element index of x[l][h][t][0] (channel stride is 1):
@@ -66,6 +67,9 @@ float    ref_f16_to_f32(uint16_t h);
 uint16_t ref_f32_to_f16(float f);
 float    ref_bf16_to_f32(uint16_t h);
 uint16_t ref_f32_to_bf16(float f);
+
+/* transform T: one head_dim-long row of 16-bit values -> the same, see kvc_ref.c */
+void     ref_hadamard_row(const uint16_t *in, uint16_t *out, int dim, int dtype, int inverse);
 
 /* quantizer on one group held as floats */
 void     ref_group_meta(const float *x, int n, int bits, uint16_t *scale_h, uint16_t *zero_h);

@@ -28,7 +28,8 @@ def build(force=False):
 class Config(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("layers", C.c_int32), ("heads", C.c_int32),
                 ("head_dim", C.c_int32), ("bits_k", C.c_int32), ("bits_v", C.c_int32),
-                ("group_k", C.c_int32), ("group_v", C.c_int32), ("codec", C.c_int32)]
+                ("group_k", C.c_int32), ("group_v", C.c_int32), ("codec", C.c_int32),
+                ("transform", C.c_int32)]
 
 
 class Layout(C.Structure):
@@ -67,8 +68,8 @@ def _p(a):
 
 
 def config(dtype=F16, layers=1, heads=1, head_dim=128, bits_k=4, bits_v=4, group_k=32, group_v=32,
-           codec=0):
-    return Config(dtype, layers, heads, head_dim, bits_k, bits_v, group_k, group_v, codec)
+           codec=0, transform=0):
+    return Config(dtype, layers, heads, head_dim, bits_k, bits_v, group_k, group_v, codec, transform)
 
 
 def contiguous_layout(heads, tokens, head_dim):
@@ -136,6 +137,14 @@ def unpack(buf, n, bits):
     q = np.empty(n, dtype=np.uint8)
     lib().ref_unpack(_p(buf), C.c_int64(n), C.c_int(bits), _p(q))
     return q
+
+
+def hadamard_row(row_u16, dtype=F16, inverse=False):
+    """ref_hadamard_row on one row of 16-bit patterns (length = a power of two)."""
+    row = np.ascontiguousarray(row_u16, dtype=np.uint16)
+    out = np.empty_like(row)
+    lib().ref_hadamard_row(_p(row), _p(out), C.c_int(row.size), C.c_int(dtype), C.c_int(1 if inverse else 0))
+    return out
 
 
 def huff_lengths(hist):
