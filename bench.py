@@ -22,16 +22,18 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 WORKLOADS = {
-    # name: (layers, heads, tokens, dtype, bits_k, bits_v, group_k, group_v, codec)
+    # name: (layers, heads, tokens, dtype, bits_k, bits_v, group_k, group_v, codec[, transform])
     "llama70b_32k_fp16_int4g32_huff8": (80, 8, 32768, "f16", 4, 4, 32, 32, 1),
     "llama70b_32k_fp16_int4g32": (80, 8, 32768, "f16", 4, 4, 32, 32, 0),
+    "llama70b_32k_fp16_hadamard_int4g32_huff8": (80, 8, 32768, "f16", 4, 4, 32, 32, 1, 1),
+    "llama70b_32k_fp16_hadamard_int4g32": (80, 8, 32768, "f16", 4, 4, 32, 32, 0, 1),
     "llama8b_8k_bf16_int4g32": (32, 8, 8192, "bf16", 4, 4, 32, 32, 0),
     "llama8b_8k_bf16_int2g64": (32, 8, 8192, "bf16", 2, 2, 64, 64, 0),
     "tiny_fp16_int4g32": (1, 8, 1024, "f16", 4, 4, 32, 32, 0),
 }
 
 
-def cpu_baseline(x_dev, layers, heads, tokens, dt, bits_k, bits_v, gk, gv, codec, sample_layers):
+def cpu_baseline(x_dev, layers, heads, tokens, dt, bits_k, bits_v, gk, gv, codec, transform, sample_layers):
     """The oracle as it stands, single-threaded, on the first `sample_layers` layers."""
     import numpy as np
     from oracle import ref
@@ -39,7 +41,7 @@ def cpu_baseline(x_dev, layers, heads, tokens, dt, bits_k, bits_v, gk, gv, codec
     xs = x_dev[:sample_layers].cpu()
     xu = kvgen.as_u16(xs)
     cfg = ref.config(dtype=dt, layers=sample_layers, heads=heads, bits_k=bits_k, bits_v=bits_v,
-                     group_k=gk, group_v=gv, codec=codec)
+                     group_k=gk, group_v=gv, codec=codec, transform=transform)
     lay = ref.contiguous_layout(heads, tokens, 128)
     t0 = time.perf_counter()
     payload = ref.compress(cfg, xu[0, 0], xu[0, 1], lay, tokens)
@@ -62,7 +64,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="llama70b_32k_fp16_int4g32_huff8", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-layers", type=int, default=2)
+    ap.add_argument("--cpu-sample-layers", type=int, default=4)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is the single-GPU hot path (one process, one MI355X); "
@@ -77,12 +79,13 @@ def main():
         return 3
     kvc.load()                                    # fails loudly if the HIP library is missing
 
-    L, H, T, dtn, bk, bv, gk, gv, codec = WORKLOADS[args.workload]
+    L, H, T, dtn, bk, bv, gk, gv, codec = WORKLOADS[args.workload][:9]
+    transform = WORKLOADS[args.workload][9] if len(WORKLOADS[args.workload]) > 9 else 0
     dtype, dt = (torch.float16, kvc.F16) if dtn == "f16" else (torch.bfloat16, kvc.BF16)
     dev = "cuda:0"
     x = kvgen.make_kv(0, L, H, 128, T, dtype, dev)
     y = torch.empty_like(x)
-    plan = kvc.Plan(dt, L, H, 128, bk, bv, gk, gv, codec, max_tokens=T)
+    plan = kvc.Plan(dt, L, H, 128, bk, bv, gk, gv, codec, max_tokens=T, transform=transform)
     buf = kvc.Buffers(plan, [T], dev)
     src, dst = [kvc.contiguous_request(x)], [kvc.contiguous_request(y)]
     stream = torch.cuda.current_stream().cuda_stream
@@ -181,7 +184,8 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "layers": L, "kv_heads": H, "head_dim": 128, "tokens": T,
                    "kv_dtype": dtn, "bits_k": bk, "bits_v": bv, "group_k": gk, "group_v": gv,
-                   "codec": "huff8" if codec else "none", "kv_bytes": V, "payload_bytes": payload_bytes},
+                   "codec": "huff8" if codec else "none", "transform": "hadamard" if transform else "none",
+                   "kv_bytes": V, "payload_bytes": payload_bytes},
         "s_enc_GBps": round(s_enc, 1), "s_dec_GBps": round(s_dec, 1), "cr": round(cr, 4),
         "break_even_bandwidth_GBps": round((1 - 1 / cr) * s_p, 1),
         "compress_ms": round(t_enc, 4), "decompress_ms": round(t_dec, 4),
@@ -192,7 +196,8 @@ def main():
         "kernels": per_kernel, "roofline": roofline,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(x, L, H, T, dt, bk, bv, gk, gv, codec, min(args.cpu_sample_layers, L))
+        out["cpu_baseline"] = cpu_baseline(x, L, H, T, dt, bk, bv, gk, gv, codec, transform,
+                                           min(args.cpu_sample_layers, L))
     print(json.dumps(out))
     return 0
 

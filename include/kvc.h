@@ -59,11 +59,20 @@ enum { KVC_CODEC_NONE = 0, KVC_CODEC_HUFF8 = 1 };
  *   group_k         : tokens per K group (K is quantized per channel): 32, 64 or 128
  *   group_v         : channels per V group (V is quantized per token): 32, 64 or 128
  *   codec           : lossless stage over the packed code bytes (needs bits < 16)
- *   transform       : stage T; only 0 (none) is built
+ *   transform       : stage T (section 5.1, the Hadamard rotation listed among the transformer
+ *                     modules): 0 none, KVC_T_HADAMARD = every head_dim-long row of K and of V
+ *                     is replaced by H x / 8 before the quantizer and decompression applies
+ *                     H x / 16 to the reconstructed row (H = Walsh-Hadamard matrix of order 128
+ *                     in natural order; fp32 butterflies with strides 1, 2, ..., 64; results
+ *                     rounded to the tensor type); a tensor stored unchanged (16 bits) is not
+ *                     transformed
  *   head_bits_k/v   : reserved for per-head bit widths (MixHQ); must be NULL
  * Every group carries two fp16 values (scale, zero): the 32 bits per group that cap
  * 2-bit / group-32 at 16/(2+1) = 5.33x (section 7.3).
  */
+#define KVC_T_NONE 0
+#define KVC_T_HADAMARD 1
+
 typedef struct {
     uint8_t bits_k, bits_v;
     uint16_t group_k, group_v;

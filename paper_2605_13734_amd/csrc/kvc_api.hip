@@ -88,6 +88,7 @@ static void make_header(const kvc_plan_t *p, long long T, const Geometry &g, Hea
     h[21] = p->strat.bits_v;
     put16(h + 22, p->strat.group_k);
     put16(h + 24, p->strat.group_v);
+    h[26] = p->strat.transform;
     put64(h + 32, (uint64_t)T);
     put64(h + 48, (uint64_t)g.off_meta_k); put64(h + 56, (uint64_t)g.meta_k);
     put64(h + 64, (uint64_t)g.off_meta_v); put64(h + 72, (uint64_t)g.meta_v);
@@ -126,7 +127,7 @@ static int check_pair(const kvc_model *m, const kvc_strategy *s)
     if (s->bits_k != 16 && !group_ok(s->group_k)) return KVC_ERR_ARG;
     if (s->bits_v != 16 && !group_ok(s->group_v)) return KVC_ERR_ARG;
     if (m->head_dim != kDim) return KVC_ERR_UNSUPPORTED;
-    if (s->transform != 0 || s->head_bits_k || s->head_bits_v) return KVC_ERR_UNSUPPORTED;
+    if (s->transform > KVC_T_HADAMARD || s->head_bits_k || s->head_bits_v) return KVC_ERR_UNSUPPORTED;
     if (s->codec && (s->bits_k == 16 || s->bits_v == 16)) return KVC_ERR_UNSUPPORTED;
     return KVC_OK;
 }
@@ -194,10 +195,11 @@ extern "C" int kvc_payload_inspect(const void *header128, kvc_model *model, kvc_
     s.bits_v = h[21];
     s.group_k = (uint16_t)get16(h + 22);
     s.group_v = (uint16_t)get16(h + 24);
+    s.transform = h[26];
     const int64_t T = (int64_t)get64(h + 32);
     int rc = check_pair(&m, &s);
     if (rc == KVC_ERR_ARG || T < 0) return KVC_ERR_FORMAT;
-    for (int i = 26; i < 32; ++i)
+    for (int i = 27; i < 32; ++i)
         if (h[i]) return KVC_ERR_FORMAT;
     // the fixed part of the section table must be the closed form of the fields above
     kvc_plan_t tmp;
@@ -288,6 +290,7 @@ static QuantArgs quant_args(const kvc_plan_t *p, const kvc_request *r, int is_v,
     a.heads = p->model.kv_heads;
     a.group = group;
     a.dense = (!r->block_table && r->stride_token == kDim) ? 1 : 0;
+    a.rotate = (p->strat.transform == KVC_T_HADAMARD && bits != 16) ? 1 : 0;
     const long long rows_per_unit = (compress && !is_v && bits != 16) ? group : kPassRows;
     a.units_per_head = (r->tokens + rows_per_unit - 1) / rows_per_unit;
     a.total_units = a.units_per_head * p->model.layers * p->model.kv_heads;

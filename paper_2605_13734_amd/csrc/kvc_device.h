@@ -171,6 +171,67 @@ template <int LANES> __device__ __forceinline__ void group_minmax(float &mn, flo
     }
 }
 
+// ---- transform (KVServe section 5.1, stage T: the Hadamard rotation among the transformer
+//      modules) ---------------------------------------------------------------------------------
+
+// The value of lane (lane ^ MASK), MASK = 1, 2, 4 or 8: within the 16 lanes that hold one row.
+template <int MASK> __device__ __forceinline__ float xor_lane_f32(float v)
+{
+    if (MASK == 1) return dpp_f32<DPP_QUAD_XOR1>(v);
+    if (MASK == 2) return dpp_f32<DPP_QUAD_XOR2>(v);
+    // ds_swizzle, bit-mask mode: and 0x1f, or 0, xor MASK (no LDS memory is touched)
+    return __uint_as_float((uint32_t)__builtin_amdgcn_ds_swizzle((int)__float_as_uint(v), (MASK << 10) | 0x1f));
+}
+
+// One row of 128 values, 8 per lane over 16 lanes (lane & 15 = col holds channels 8*col ...):
+// y = H x * scale, H the Walsh-Hadamard matrix in natural order, as the fast transform with the
+// strides 1, 2, 4 (inside the lane), 8, 16, 32, 64 (across lanes) in this order, every sum and
+// difference one fp32 operation; scale = 1/8 on the way in, 1/16 on the way back (both exact);
+// the result is limited to the finite range of the type and rounded to it.  All 16 lanes of a
+// row must be active.
+template <int DT> __device__ __forceinline__ u32x4 hadamard_row(const u32x4 &in, bool inverse)
+{
+    float x[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = elem_f32<DT>(in, e);
+#pragma unroll
+    for (int h = 1; h < 8; h <<= 1)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (!(j & h)) {
+                const float a = x[j], b = x[j + h];
+                x[j] = a + b;
+                x[j + h] = a - b;
+            }
+    const int col = lane_id() & 15;
+#pragma unroll
+    for (int m = 1; m < 16; m <<= 1) {
+        // the lane with bit m of col clear holds a and gets a + b, the other holds b and gets a - b
+        const float sign = (col & m) ? -1.0f : 1.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float other = m == 1 ? xor_lane_f32<1>(x[e]) : m == 2 ? xor_lane_f32<2>(x[e])
+                              : m == 4 ? xor_lane_f32<4>(x[e]) : xor_lane_f32<8>(x[e]);
+            x[e] = __builtin_fmaf(x[e], sign, other);          // exact product, one rounded sum
+        }
+    }
+    const float scale = inverse ? 0.0625f : 0.125f;
+    constexpr float top = DT == DT_F16 ? 65504.0f : 3.3895313892515355e38f;
+    u32x4 out;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const float a = __builtin_amdgcn_fmed3f(x[2 * w] * scale, -top, top);
+        const float b = __builtin_amdgcn_fmed3f(x[2 * w + 1] * scale, -top, top);
+        if (DT == DT_F16) {
+            out[w] = f32_to_f16_bits(rounded_f32(a)) | (f32_to_f16_bits(rounded_f32(b)) << 16);
+        } else {
+            f32x2_t v = {a, b};
+            out[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+        }
+    }
+    return out;
+}
+
 // ---- quantizer (KVServe section 5.1, stage Q: asymmetric, grouped; section 7.3: two
 //      16-bit metadata values per group) ------------------------------------------------
 

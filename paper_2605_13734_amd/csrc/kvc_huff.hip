@@ -119,6 +119,7 @@ __device__ __forceinline__ void quantize_chunk(const QuantArgs &a, const ChunkPo
         u32x4 raw[PU * 8];
 #pragma unroll
         for (int p = 0; p < PU; ++p) load_pass<DENSE>(a.x, c.head_off, row0 + p * kPassRows, a.tokens, raw + p * 8, bad);
+        if (a.rotate) rotate_rows<DT, PU * 8>(raw);
         if (!IS_V) {
             const long long nb = (a.tokens + G - 1) / G;
             KParams kp;
@@ -864,7 +865,7 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
             else load_meta_v(a.q, c, (p + 1) * kPassRows, mv);
         }
         dequant_pass<BITS, DT, IS_V, DENSE, Dec::kLayout>(lds, scale, zero, clamp, a.q.x, c.head_off, c.row0 + p * kPassRows,
-                                                          c.rows - p * kPassRows, bad, p * kPassRows);
+                                                          c.rows - p * kPassRows, bad, p * kPassRows, a.q.rotate != 0);
     }
     if (bad) atomicOr(a.q.status, KVC_DEV_BAD_BLOCK);
     PHASE(1, 3);

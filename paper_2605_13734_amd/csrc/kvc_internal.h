@@ -17,6 +17,7 @@ struct QuantArgs {
     int heads;
     int group;                  // runtime copy of the group size
     int dense;                  // rows of a head are contiguous: stride_token == head_dim, no block table
+    int rotate;                 // stage T: rows are Hadamard-transformed on the way in / back on the way out
     long long units_per_head;   // work units (one wave each) per (layer, head)
     long long total_units;
     int *status;                // device status word of the request

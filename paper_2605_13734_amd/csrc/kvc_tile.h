@@ -423,7 +423,7 @@ template <int BITS, int LAYOUT> __device__ __forceinline__ u32x2 fetch_codes(uin
 template <int BITS, int DT, bool IS_V, bool DENSE, int LAYOUT, bool CLAMP>
 __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float scale[8], const float zero[8],
                                                   const TensorView &x, long long head_off, long long row0, int rows,
-                                                  bool &bad, int row_base)
+                                                  bool &bad, int row_base, bool rotate)
 {
     const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
     if (DENSE && rows >= kPassRows) {
@@ -431,8 +431,9 @@ __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float sc
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const u32x2 w = fetch_codes<BITS, LAYOUT>(codes, row_base + 4 * i + rsub);
-            const u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w, scale[i], zero[i])
-                                   : dequant_row<BITS, DT, CLAMP>(w, scale, zero);
+            u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w, scale[i], zero[i])
+                             : dequant_row<BITS, DT, CLAMP>(w, scale, zero);
+            if (rotate) out = hadamard_row<DT>(out, true);
             __builtin_nontemporal_store(out, dst + i * 64);
         }
         return;
@@ -442,8 +443,9 @@ __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float sc
         const int r = 4 * i + rsub;
         const bool ok = r < rows;                       // uniform over each quad of lanes
         const u32x2 w = fetch_codes<BITS, LAYOUT>(codes, row_base + (ok ? r : 0));
-        const u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w, scale[i], zero[i])
-                               : dequant_row<BITS, DT, CLAMP>(w, scale, zero);
+        u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w, scale[i], zero[i])
+                         : dequant_row<BITS, DT, CLAMP>(w, scale, zero);
+        if (rotate) out = hadamard_row<DT>(out, true);      // (all 16 lanes of a row take part)
         if (ok) {
             bool b = false;
             const long long off = DENSE ? head_off + (row0 + r) * kDim : row_offset(x, head_off, row0 + r, b);
@@ -459,10 +461,17 @@ __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float sc
 template <int BITS, int DT, bool IS_V, bool DENSE, int LAYOUT>
 __device__ __forceinline__ void dequant_pass(uint8_t *codes, const float scale[8], const float zero[8], bool clamp,
                                              const TensorView &x, long long head_off, long long row0, int rows, bool &bad,
-                                             int row_base = 0)
+                                             int row_base = 0, bool rotate = false)
 {
-    if (clamp) dequant_pass_rows<BITS, DT, IS_V, DENSE, LAYOUT, true>(codes, scale, zero, x, head_off, row0, rows, bad, row_base);
-    else dequant_pass_rows<BITS, DT, IS_V, DENSE, LAYOUT, false>(codes, scale, zero, x, head_off, row0, rows, bad, row_base);
+    if (clamp) dequant_pass_rows<BITS, DT, IS_V, DENSE, LAYOUT, true>(codes, scale, zero, x, head_off, row0, rows, bad, row_base, rotate);
+    else dequant_pass_rows<BITS, DT, IS_V, DENSE, LAYOUT, false>(codes, scale, zero, x, head_off, row0, rows, bad, row_base, rotate);
+}
+
+// Stage T on the rows just loaded (see hadamard_row).
+template <int DT, int N> __device__ __forceinline__ void rotate_rows(u32x4 *raw)
+{
+#pragma unroll
+    for (int i = 0; i < N; ++i) raw[i] = hadamard_row<DT>(raw[i], false);
 }
 
 }  // namespace kvc

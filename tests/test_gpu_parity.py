@@ -31,18 +31,19 @@ def gpu_compress(plan, reqs, tokens):
     return buf
 
 
-def check_contiguous(ref, x_cpu, bits_k, bits_v, gk, gv, codec=0, T=None):
+def check_contiguous(ref, x_cpu, bits_k, bits_v, gk, gv, codec=0, T=None, transform=0):
     """x_cpu: [L, 2, H, T, D] CPU tensor. Returns the GPU payload (numpy)."""
     L, _, H, Tfull, D = x_cpu.shape
     T = Tfull if T is None else T
     dt = DT[x_cpu.dtype]
     xu = kvgen.as_u16(x_cpu)
-    cfg = ref.config(dtype=dt, layers=L, heads=H, bits_k=bits_k, bits_v=bits_v, group_k=gk, group_v=gv, codec=codec)
+    cfg = ref.config(dtype=dt, layers=L, heads=H, bits_k=bits_k, bits_v=bits_v, group_k=gk, group_v=gv, codec=codec,
+                     transform=transform)
     lay = ref.contiguous_layout(H, Tfull, D)
     want = ref.compress(cfg, xu[0, 0], xu[0, 1], lay, T)
 
     x = x_cpu.cuda()
-    plan = kvc.Plan(dt, L, H, D, bits_k, bits_v, gk, gv, codec, max_tokens=T)
+    plan = kvc.Plan(dt, L, H, D, bits_k, bits_v, gk, gv, codec, max_tokens=T, transform=transform)
     buf = gpu_compress(plan, [kvc.contiguous_request(x, T)], [T])
     assert int(buf.status[0]) == 0
     got = buf.payload_of(0)
@@ -341,3 +342,56 @@ def test_scale_rounding_ties(ref):
         check_contiguous(ref, x, bits, bits, 32, 32)
         check_contiguous(ref, x, bits, bits, 64, 128)
         assert ties >= 0
+
+
+# ---- stage T: Hadamard rotation in front of the quantizer ---------------------------------------
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+@pytest.mark.parametrize("bits,group", [(4, 32), (2, 64), (3, 128), (8, 32)])
+def test_transform_contiguous(ref, dtype, bits, group):
+    x = kvgen.make_kv(60 + bits, 2, 2, 128, 32 * 9 + 5, dtype)
+    check_contiguous(ref, x, bits, bits, group, group, transform=1)
+
+
+def test_transform_with_codec_and_ragged_tail(ref):
+    x = kvgen.make_kv(70, 2, 4, 128, 128 * 5 + 37, torch.float16)
+    check_contiguous(ref, x, 4, 4, 32, 32, codec=1, transform=1)
+    check_contiguous(ref, x, 4, 2, 64, 64, codec=1, transform=1, T=128 * 3 + 1)
+
+
+def test_transform_mixed_with_passthrough(ref):
+    """A tensor stored unchanged is not rotated; the other one is."""
+    x = kvgen.make_kv(71, 1, 2, 128, 100, torch.float16)
+    check_contiguous(ref, x, 16, 4, 32, 32, transform=1)
+    check_contiguous(ref, x, 4, 16, 32, 32, transform=1)
+
+
+def test_transform_paged(ref):
+    L, H, bt, P, T = 2, 2, 16, 24, 16 * 13 + 7
+    cfg = ref.config(dtype=1, layers=L, heads=H, bits_k=4, bits_v=4, group_k=32, group_v=32, transform=1)
+    plan = kvc.Plan(1, L, H, 128, 4, 4, 32, 32, 0, max_tokens=T, transform=1)
+    x = kvgen.make_kv(72, L, H, 128, T, torch.float16)
+    tab = kvgen.block_table(5, -(-T // bt), P)
+    pool = kvgen.to_paged(x, tab, bt, P).cuda()
+    tabd = tab.cuda()
+    buf = gpu_compress(plan, [kvc.paged_request(pool, tabd, T)], [T])
+    xu = kvgen.as_u16(x)
+    lay = ref.contiguous_layout(H, T, 128)
+    want = ref.compress(cfg, xu[0, 0], xu[0, 1], lay, T)
+    got = buf.payload_of(0)
+    assert int(buf.status[0]) == 0
+    assert np.array_equal(got, want), first_diff(got, want)
+    out = torch.zeros_like(pool)
+    buf.decompress([kvc.paged_request(out, tabd, T)], torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert int(buf.status[0]) == 0
+    y = kvgen.from_paged(out.cpu(), tab, T)
+    ru = np.zeros_like(xu)
+    assert ref.decompress(want, ru[0, 0], ru[0, 1], lay, cfg) == 0
+    assert np.array_equal(kvgen.as_u16(y), ru)
+
+
+def test_transform_saturates_instead_of_overflowing(ref):
+    x = torch.full((1, 2, 1, 64, 128), 60000.0, dtype=torch.float16)
+    x[0, 1, 0, ::2] = -60000.0
+    check_contiguous(ref, x, 4, 4, 32, 32, transform=1)

@@ -38,7 +38,7 @@ def test_plan_validation(lib):
         with pytest.raises(kvc.KvcError) as e:
             kvc.Plan(**{**ok, **kw})
         assert e.value.status == -1, kw
-    unsupported = [dict(head_dim=64), dict(transform=1), dict(bits_k=16, codec=1)]
+    unsupported = [dict(head_dim=64), dict(transform=2), dict(bits_k=16, codec=1)]
     for kw in unsupported:
         with pytest.raises(kvc.KvcError) as e:
             kvc.Plan(**{**ok, **kw})
