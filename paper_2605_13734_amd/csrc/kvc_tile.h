@@ -59,6 +59,22 @@ __device__ __forceinline__ uint32_t pk_max_f16(uint32_t a, uint32_t b)
     return d;
 }
 
+// min(-a, -b) per half: maxima are carried negated so that one packed minimum reduces a
+// (min, -max) pair
+__device__ __forceinline__ uint32_t pk_min_neg_f16(uint32_t a, uint32_t b)
+{
+    uint32_t d;
+    asm("v_pk_min_f16 %0, %1, %2 neg_lo:[1,1] neg_hi:[1,1]" : "=v"(d) : "v"(a), "v"(b));
+    return d;
+}
+// both halves = min(a.lo, a.hi)
+__device__ __forceinline__ uint32_t pk_min_halves_f16(uint32_t a)
+{
+    uint32_t d;
+    asm("v_pk_min_f16 %0, %1, %1 op_sel:[0,1] op_sel_hi:[1,0]" : "=v"(d) : "v"(a));
+    return d;
+}
+
 template <typename T> __device__ __forceinline__ T pick4(int k, T v0, T v1, T v2, T v3)
 {
     return (k & 2) ? ((k & 1) ? v3 : v2) : ((k & 1) ? v1 : v0);
@@ -181,10 +197,19 @@ template <int GV, int DT>
 __device__ __forceinline__ void v_row_minmax(const u32x4 &raw, float &mn, float &mx)
 {
     if (DT == DT_F16) {
-        const uint32_t a = pk_min_f16(pk_min_f16(raw[0], raw[1]), pk_min_f16(raw[2], raw[3]));
-        const uint32_t b = pk_max_f16(pk_max_f16(raw[0], raw[1]), pk_max_f16(raw[2], raw[3]));
-        mn = fminf(lo_f32<DT_F16>(a), hi_f32<DT_F16>(a));
-        mx = fmaxf(lo_f32<DT_F16>(b), hi_f32<DT_F16>(b));
+        // everything stays packed: (min, -max) of the lane's 8 values in one register, reduced
+        // over the group's lanes by packed minima, converted once at the end
+        const uint32_t a = pk_min_halves_f16(pk_min_f16(pk_min_f16(raw[0], raw[1]), pk_min_f16(raw[2], raw[3])));
+        const uint32_t b = pk_min_halves_f16(pk_min_f16(pk_min_neg_f16(raw[0], raw[1]), pk_min_neg_f16(raw[2], raw[3])));
+        uint32_t p = (a & 0xffffu) | (b & 0xffff0000u);
+        constexpr int LANES = GV / 8;
+        p = pk_min_f16(p, dpp_u32<DPP_QUAD_XOR1>(p));
+        p = pk_min_f16(p, dpp_u32<DPP_QUAD_XOR2>(p));
+        if (LANES >= 8) p = pk_min_f16(p, dpp_u32<DPP_HALF_MIRROR>(p));
+        if (LANES >= 16) p = pk_min_f16(p, dpp_u32<DPP_MIRROR>(p));
+        mn = lo_f32<DT_F16>(p);
+        mx = -hi_f32<DT_F16>(p);
+        return;
     } else {
         float x[8];
 #pragma unroll
