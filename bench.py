@@ -57,6 +57,61 @@ def cpu_baseline(x_dev, layers, heads, tokens, dt, bits_k, bits_v, gk, gv, codec
             "s_enc": round(nbytes / (t1 - t0) / 1e9, 5), "s_dec": round(nbytes / (t2 - t1) / 1e9, 5)}
 
 
+POLICY_STRATEGIES = [
+    # name, bits_k, bits_v, group_k, group_v, codec, transform
+    ("int8g32", 8, 8, 32, 32, 0, 0),
+    ("int4g32", 4, 4, 32, 32, 0, 0),
+    ("int4g32_huff8", 4, 4, 32, 32, 1, 0),
+    ("hadamard_int4g32", 4, 4, 32, 32, 0, 1),
+    ("k4v2g64", 4, 2, 64, 64, 0, 0),
+    ("int3g64", 3, 3, 64, 64, 0, 0),
+    ("int2g64", 2, 2, 64, 64, 0, 0),
+    ("int2g128_huff8", 2, 2, 128, 128, 1, 0),
+]
+
+
+def policy_table(x, y, dt, L, H, T, steps):
+    """Measures (cr, s_enc, s_dec) of several strategies on the same tensor and turns them into the
+    piecewise policy of section 6.1 (kvc_policy_build): which strategy to use below which bandwidth."""
+    import ctypes
+    import torch
+    from paper_2605_13734_amd import kvc
+    V = x.numel() * 2
+    stream = torch.cuda.current_stream().cuda_stream
+    profiles, rows = [], []
+    for name, bk, bv, gk, gv, codec, tr in POLICY_STRATEGIES:
+        plan = kvc.Plan(dt, L, H, 128, bk, bv, gk, gv, codec, max_tokens=T, transform=tr)
+        buf = kvc.Buffers(plan, [T], "cuda:0")
+        src, dst = [kvc.contiguous_request(x)], [kvc.contiguous_request(y)]
+        buf.compress(src, stream)
+        buf.decompress(dst, stream)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        ev[0].record()
+        for _ in range(steps):
+            buf.compress(src, stream)
+        ev[1].record()
+        for _ in range(steps):
+            buf.decompress(dst, stream)
+        ev[2].record()
+        torch.cuda.synchronize()
+        assert int(buf.status[0]) == 0
+        t_enc, t_dec = ev[0].elapsed_time(ev[1]) / steps, ev[1].elapsed_time(ev[2]) / steps
+        cr = V / int(buf.out_bytes[0])
+        prof = (cr, V / t_enc / 1e6, V / t_dec / 1e6)                       # GB/s of fp16 KV
+        profiles.append(prof)
+        rows.append({"name": name, "cr": round(cr, 4), "s_enc_GBps": round(prof[1], 1), "s_dec_GBps": round(prof[2], 1),
+                     "s_p_GBps": round(kvc.profile_throughput(*prof), 1),
+                     "break_even_bandwidth_GBps": round(kvc.benefit_threshold(*prof), 1)})
+        del buf, plan
+    rc, table = kvc.policy_build(profiles)
+    assert rc == 0
+    segs = []
+    for k, (x_from, prof) in enumerate(table):
+        segs.append({"profile": rows[prof]["name"] if prof >= 0 else "uncompressed",
+                     "bandwidth_below_GBps": None if x_from == 0 else round(1.0 / x_from, 1)})
+    return {"profiles": rows, "table": segs}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -64,6 +119,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="llama70b_32k_fp16_int4g32_huff8", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--policy", action="store_true",
+                    help="also measure a set of strategies and print the analytic policy table")
     ap.add_argument("--cpu-sample-layers", type=int, default=4)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -195,6 +252,8 @@ def main():
         "device_copy_GBps_rw": round(copy_gbps, 1), "copy_rows_reference_bytes_per_launch": ref_bytes,
         "kernels": per_kernel, "roofline": roofline,
     }
+    if args.policy:
+        out["policy"] = policy_table(x, y, dt, L, H, T, max(2, args.steps // 3))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(x, L, H, T, dt, bk, bv, gk, gv, codec, transform,
                                            min(args.cpu_sample_layers, L))

@@ -195,6 +195,43 @@ int kvc_trace(void **hip_events, int32_t capacity);
 #define KVC_SELFTEST_COUNTS 8
 int kvc_selftest(uint64_t *counts, void *stream);
 
+/*
+ * Analytic selection among measured profiles (section 6.1).  Host functions, no GPU work.
+ * A profile is the triple of section 3.1 as this library measures it: cr = V / V_p and the
+ * encode / decode throughputs in bytes of uncompressed KV per second (any consistent unit).
+ *   kvc_profile_throughput : s_p, the harmonic combination 1 / (1/s_enc + 1/s_dec)
+ *   kvc_benefit_threshold  : B*_p = (1 - 1/cr_p) s_p (Eq. 5): the profile shortens the transfer
+ *                            exactly when the effective bandwidth is below it (Theorem 1)
+ *   kvc_policy_build       : the piecewise policy of Theorem 2, the lower envelope over
+ *                            x = 1/B of cost_p(x) = 1/s_p + x/cr_p (Eq. 6) together with
+ *                            cost(x) = x for an uncompressed transfer.  Writes *count segments
+ *                            ordered by x_from (the first starts at 0); segment i is optimal for
+ *                            x in [x_from_i, x_from_(i+1)); profile -1 = do not compress.
+ *                            Profiles that are never optimal do not appear.  Returns
+ *                            KVC_ERR_CAPACITY (with *count set) if the table is too small
+ *                            (n + 1 entries always suffice), KVC_ERR_ARG for a profile with a
+ *                            non-positive or non-finite field.
+ *   kvc_policy_lookup      : O(log n) look-up for a bandwidth (same unit as the throughputs):
+ *                            the optimal profile and its two neighbours on the envelope, the
+ *                            candidate set the paper hands to its online stage.
+ * All arrays are host memory owned by the caller.
+ */
+typedef struct {
+    double cr, s_enc, s_dec;
+} kvc_profile;
+
+typedef struct {
+    double x_from;
+    int32_t profile;
+} kvc_policy_segment;
+
+double kvc_profile_throughput(const kvc_profile *p);
+double kvc_benefit_threshold(const kvc_profile *p);
+int kvc_policy_build(const kvc_profile *profiles, int32_t n, kvc_policy_segment *table, int32_t capacity,
+                     int32_t *count);
+int kvc_policy_lookup(const kvc_policy_segment *table, int32_t count, double bandwidth, int32_t *profile,
+                      int32_t *toward_more_bandwidth, int32_t *toward_less_bandwidth);
+
 const char *kvc_status_string(int status);
 
 #ifdef __cplusplus

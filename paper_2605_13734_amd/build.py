@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 OUT = os.path.join(HERE, "libkvc.so")
-SOURCES = ["kvc_api.hip", "kvc_quant.hip", "kvc_huff.hip", "kvc_selftest.hip"]
+SOURCES = ["kvc_api.hip", "kvc_quant.hip", "kvc_huff.hip", "kvc_selftest.hip", "kvc_policy.hip"]
 # packed fp32 instructions are switched off for the device pass (flag for hipcc only)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall",

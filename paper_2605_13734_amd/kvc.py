@@ -17,13 +17,22 @@ DEV_BAD_BLOCK, DEV_BAD_HEADER, DEV_BAD_CHUNK, DEV_BAD_TABLE, DEV_SCAN_TIMEOUT = 
 
 SYMBOLS = ["kvc_plan", "kvc_plan_free", "kvc_payload_size", "kvc_workspace_size", "kvc_compress",
            "kvc_decompress", "kvc_payload_inspect", "kvc_check_block_table", "kvc_status_string",
-           "kvc_trace", "kvc_selftest"]
+           "kvc_trace", "kvc_selftest", "kvc_profile_throughput", "kvc_benefit_threshold", "kvc_policy_build",
+           "kvc_policy_lookup"]
 
 
 class Strategy(C.Structure):
     _fields_ = [("bits_k", C.c_uint8), ("bits_v", C.c_uint8), ("group_k", C.c_uint16),
                 ("group_v", C.c_uint16), ("codec", C.c_uint8), ("transform", C.c_uint8),
                 ("head_bits_k", C.c_void_p), ("head_bits_v", C.c_void_p)]
+
+
+class Profile(C.Structure):
+    _fields_ = [("cr", C.c_double), ("s_enc", C.c_double), ("s_dec", C.c_double)]
+
+
+class PolicySegment(C.Structure):
+    _fields_ = [("x_from", C.c_double), ("profile", C.c_int32)]
 
 
 class Model(C.Structure):
@@ -76,6 +85,14 @@ def load():
         L.kvc_check_block_table.argtypes = [C.c_void_p, C.c_int64, C.c_int32]
         L.kvc_trace.argtypes = [C.c_void_p, C.c_int32]
         L.kvc_selftest.argtypes = [C.c_void_p, C.c_void_p]
+        L.kvc_profile_throughput.argtypes = [C.POINTER(Profile)]
+        L.kvc_profile_throughput.restype = C.c_double
+        L.kvc_benefit_threshold.argtypes = [C.POINTER(Profile)]
+        L.kvc_benefit_threshold.restype = C.c_double
+        L.kvc_policy_build.argtypes = [C.POINTER(Profile), C.c_int32, C.POINTER(PolicySegment), C.c_int32,
+                                       C.POINTER(C.c_int32)]
+        L.kvc_policy_lookup.argtypes = [C.POINTER(PolicySegment), C.c_int32, C.c_double, C.POINTER(C.c_int32),
+                                        C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.kvc_status_string.argtypes = [C.c_int]
         L.kvc_status_string.restype = C.c_char_p
         _lib = L
@@ -179,6 +196,32 @@ def payload_inspect(header_bytes):
 def trace(events, capacity):
     """kvc_trace: install (or, with None, remove) an array of hipEvent_t handles."""
     return load().kvc_trace(events, capacity)
+
+
+def profile_throughput(cr, s_enc, s_dec):
+    return load().kvc_profile_throughput(C.byref(Profile(cr, s_enc, s_dec)))
+
+
+def benefit_threshold(cr, s_enc, s_dec):
+    return load().kvc_benefit_threshold(C.byref(Profile(cr, s_enc, s_dec)))
+
+
+def policy_build(profiles):
+    """kvc_policy_build on a list of (cr, s_enc, s_dec); returns (rc, [(x_from, profile)])."""
+    n = len(profiles)
+    arr = (Profile * max(n, 1))(*[Profile(*p) for p in profiles])
+    table = (PolicySegment * (n + 1))()
+    count = C.c_int32(0)
+    rc = load().kvc_policy_build(arr, n, table, n + 1, C.byref(count))
+    return rc, [(table[i].x_from, table[i].profile) for i in range(count.value if rc == 0 else 0)]
+
+
+def policy_lookup(table, bandwidth):
+    """kvc_policy_lookup on a table returned by policy_build; returns (rc, profile, more_bw, less_bw)."""
+    arr = (PolicySegment * len(table))(*[PolicySegment(x, p) for x, p in table])
+    a, b, c = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+    rc = load().kvc_policy_lookup(arr, len(table), bandwidth, C.byref(a), C.byref(b), C.byref(c))
+    return rc, a.value, b.value, c.value
 
 
 SELFTEST_COUNTS = 8
