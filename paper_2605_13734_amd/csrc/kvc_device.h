@@ -183,19 +183,35 @@ template <int MASK> __device__ __forceinline__ float xor_lane_f32(float v)
     return __uint_as_float((uint32_t)__builtin_amdgcn_ds_swizzle((int)__float_as_uint(v), (MASK << 10) | 0x1f));
 }
 
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+
 // One row of 128 values, 8 per lane over 16 lanes (lane & 15 = col holds channels 8*col ...):
 // y = H x * scale, H the Walsh-Hadamard matrix in natural order, as the fast transform with the
 // strides 1, 2, 4 (inside the lane), 8, 16, 32, 64 (across lanes) in this order, every sum and
 // difference one fp32 operation; scale = 1/8 on the way in, 1/16 on the way back (both exact);
 // the result is limited to the finite range of the type and rounded to it.  All 16 lanes of a
 // row must be active.
+//
+// How the same bits are reached with fewer instructions: the scale, a power of two, is applied
+// in the first stage, which for fp16 input is computed straight from the packed halves by the
+// mixed-precision FMA (scaling by a power of two commutes with every later rounding).  In a
+// stage across lanes every lane computes own + c * other with c = +-1 on the operand that comes
+// from the other lane, so that the lane exchange can ride on the multiply-add; the lane that
+// should hold a - b then holds b - a, and a lane's values are negated once for every set bit
+// of col.  That sign is folded into the first stage's factor, which flips the roles of c.
 template <int DT> __device__ __forceinline__ u32x4 hadamard_row(const u32x4 &in, bool inverse)
 {
+    const int col = lane_id() & 15;
+    const float factor = (__builtin_popcount(col) & 1 ? -1.0f : 1.0f) * (inverse ? 0.0625f : 0.125f);
     float x[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) x[e] = elem_f32<DT>(in, e);
+    for (int w = 0; w < 4; ++w) {
+        const float lo = elem_f32<DT>(in, 2 * w), hi = elem_f32<DT>(in, 2 * w + 1) * factor;
+        x[2 * w] = __builtin_fmaf(lo, factor, hi);
+        x[2 * w + 1] = __builtin_fmaf(lo, factor, -hi);
+    }
 #pragma unroll
-    for (int h = 1; h < 8; h <<= 1)
+    for (int h = 2; h < 8; h <<= 1)
 #pragma unroll
         for (int j = 0; j < 8; ++j)
             if (!(j & h)) {
@@ -203,31 +219,23 @@ template <int DT> __device__ __forceinline__ u32x4 hadamard_row(const u32x4 &in,
                 x[j] = a + b;
                 x[j + h] = a - b;
             }
-    const int col = lane_id() & 15;
 #pragma unroll
     for (int m = 1; m < 16; m <<= 1) {
-        // the lane with bit m of col clear holds a and gets a + b, the other holds b and gets a - b
-        const float sign = (col & m) ? -1.0f : 1.0f;
+        const float c = (col & m) ? 1.0f : -1.0f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const float other = m == 1 ? xor_lane_f32<1>(x[e]) : m == 2 ? xor_lane_f32<2>(x[e])
                               : m == 4 ? xor_lane_f32<4>(x[e]) : xor_lane_f32<8>(x[e]);
-            x[e] = __builtin_fmaf(x[e], sign, other);          // exact product, one rounded sum
+            x[e] = __builtin_fmaf(other, c, x[e]);             // exact product, one rounded sum
         }
     }
-    const float scale = inverse ? 0.0625f : 0.125f;
     constexpr float top = DT == DT_F16 ? 65504.0f : 3.3895313892515355e38f;
     u32x4 out;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-        const float a = __builtin_amdgcn_fmed3f(x[2 * w] * scale, -top, top);
-        const float b = __builtin_amdgcn_fmed3f(x[2 * w + 1] * scale, -top, top);
-        if (DT == DT_F16) {
-            out[w] = f32_to_f16_bits(rounded_f32(a)) | (f32_to_f16_bits(rounded_f32(b)) << 16);
-        } else {
-            f32x2_t v = {a, b};
-            out[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
-        }
+        f32x2_t v = {__builtin_amdgcn_fmed3f(x[2 * w], -top, top), __builtin_amdgcn_fmed3f(x[2 * w + 1], -top, top)};
+        if (DT == DT_F16) out[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_t));
+        else out[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
     }
     return out;
 }
