@@ -360,12 +360,40 @@ int ref_huff_decode_chunk(const uint8_t *body, int64_t body_bytes, int rows, int
 
 static int bits_ok(int b) { return b == 2 || b == 3 || b == 4 || b == 8 || b == 16; }
 
+/*
+ * Mixed precision at head granularity (KVServe section 5.1: "mixed-precision at layer-wise and
+ * head-wise granularity", and MixHQ: heads that matter keep a high precision, the others drop to
+ * very few bits instead of being pruned).  The paper names the mechanism only; the reading here:
+ * an optional table per tensor gives the width of every (layer, head); groups, metadata and
+ * code order are those of the uniform case, the codes of the heads follow each other in
+ * (layer, head) order, each with its own width, and the tables travel in the payload's
+ * auxiliary section (K table, then V table, one byte per head).  Which head gets which width is
+ * the caller's business (the paper takes it from trained head masks).
+ */
+static int bits_at(const ref_config *c, int is_v, int64_t lh)
+{
+    const uint8_t *t = is_v ? c->head_bits_v : c->head_bits_k;
+    return t ? t[lh] : (is_v ? c->bits_v : c->bits_k);
+}
+
+static int table_ok(const ref_config *c, int is_v)
+{
+    const uint8_t *t = is_v ? c->head_bits_v : c->head_bits_k;
+    if (!t) return 1;
+    if ((is_v ? c->bits_v : c->bits_k) != 0) return 0;
+    for (int64_t i = 0; i < (int64_t)c->layers * c->heads; ++i)
+        if (t[i] != 2 && t[i] != 3 && t[i] != 4 && t[i] != 8) return 0;
+    return 1;
+}
+
 int ref_check_config(const ref_config *c)
 {
     if (!c) return REF_ERR_ARG;
     if (c->dtype != REF_F16 && c->dtype != REF_BF16) return REF_ERR_ARG;
     if (c->layers < 1 || c->heads < 1 || c->head_dim < 8 || c->head_dim % 8) return REF_ERR_ARG;
-    if (!bits_ok(c->bits_k) || !bits_ok(c->bits_v)) return REF_ERR_ARG;
+    if (!table_ok(c, 0) || !table_ok(c, 1)) return REF_ERR_ARG;
+    if ((c->head_bits_k || c->head_bits_v) && c->codec) return REF_ERR_UNSUPPORTED;
+    if ((!c->head_bits_k && !bits_ok(c->bits_k)) || (!c->head_bits_v && !bits_ok(c->bits_v))) return REF_ERR_ARG;
     if (c->bits_k != 16 && (c->group_k < 1 || c->group_k > CHUNK_ROWS || CHUNK_ROWS % c->group_k))
         return REF_ERR_ARG;
     if (c->bits_v != 16 && (c->group_v < 1 || c->head_dim % c->group_v)) return REF_ERR_ARG;
@@ -395,10 +423,14 @@ static void layout_of(const ref_config *c, int64_t T, geometry *g)
     int64_t LH = (int64_t)c->layers * c->heads, D = c->head_dim;
     g->meta_k = c->bits_k == 16 ? 0 : 4 * LH * ((T + c->group_k - 1) / c->group_k) * D;
     g->meta_v = c->bits_v == 16 ? 0 : 4 * LH * T * (D / c->group_v);
-    g->codes_k = LH * T * D * c->bits_k / 8;
-    g->codes_v = LH * T * D * c->bits_v / 8;
+    g->codes_k = g->codes_v = 0;
+    for (int64_t lh = 0; lh < LH; ++lh) {
+        g->codes_k += T * D * bits_at(c, 0, lh) / 8;
+        g->codes_v += T * D * bits_at(c, 1, lh) / 8;
+    }
     g->chunks_k = g->chunks_v = LH * ref_chunks_per_head(T);
     g->aux = c->codec ? 512 + 4 * (g->chunks_k + g->chunks_v + 1) : 0;
+    g->aux += (c->head_bits_k ? LH : 0) + (c->head_bits_v ? LH : 0);
     g->off_meta_k = HEADER;
     g->off_meta_v = g->off_meta_k + align16(g->meta_k);
     g->off_aux = g->off_meta_v + align16(g->meta_v);
@@ -430,7 +462,7 @@ int ref_payload_size(const ref_config *c, int64_t tokens, uint64_t *bytes, int *
 int ref_compress_head(const ref_config *c, int is_v, const void *src, const ref_layout *lay,
                       int64_t T, int l, int h, uint8_t *codes, uint16_t *meta)
 {
-    int D = c->head_dim, bits = is_v ? c->bits_v : c->bits_k;
+    int D = c->head_dim, bits = bits_at(c, is_v, (int64_t)l * c->heads + h);
     if (bits == 16) {
         for (int64_t t = 0; t < T; ++t)
             memcpy(codes + t * D * 2, (const uint16_t *)src + row_offset(lay, l, h, t), (size_t)D * 2);
@@ -444,6 +476,8 @@ int ref_compress_head(const ref_config *c, int is_v, const void *src, const ref_
             ref_hadamard_row((const uint16_t *)src + row_offset(lay, l, h, t), xt + t * D, D, c->dtype, 0);
         ref_config plain = *c;
         plain.transform = 0;
+        plain.head_bits_k = plain.head_bits_v = NULL;
+        plain.bits_k = plain.bits_v = bits;
         ref_layout rows = {0, 0, D, 0, 0, NULL};
         int rc = ref_compress_head(&plain, is_v, xt, &rows, T, 0, 0, codes, meta);
         free(xt);
@@ -490,7 +524,7 @@ int ref_compress_head(const ref_config *c, int is_v, const void *src, const ref_
 int ref_decompress_head(const ref_config *c, int is_v, const uint8_t *codes, const uint16_t *meta,
                         int64_t T, int l, int h, void *dst, const ref_layout *lay)
 {
-    int D = c->head_dim, bits = is_v ? c->bits_v : c->bits_k;
+    int D = c->head_dim, bits = bits_at(c, is_v, (int64_t)l * c->heads + h);
     uint16_t *out = (uint16_t *)dst;
     if (bits == 16) {
         for (int64_t t = 0; t < T; ++t)
@@ -503,6 +537,8 @@ int ref_decompress_head(const ref_config *c, int is_v, const uint8_t *codes, con
         if (!xt) return REF_ERR_ARG;
         ref_config plain = *c;
         plain.transform = 0;
+        plain.head_bits_k = plain.head_bits_v = NULL;
+        plain.bits_k = plain.bits_v = bits;
         ref_layout rows = {0, 0, D, 0, 0, NULL};
         int rc = ref_decompress_head(&plain, is_v, codes, meta, T, 0, 0, xt, &rows);
         for (int64_t t = 0; t < T && rc == REF_OK; ++t)
@@ -531,9 +567,18 @@ static int64_t head_code_bytes(const ref_config *c, int is_v, int64_t T)
     return T * c->head_dim * (is_v ? c->bits_v : c->bits_k) / 8;
 }
 
+/* byte offset of head lh's codes inside its section, and their size */
+static int64_t head_code_off(const ref_config *c, int is_v, int64_t T, int64_t lh, int64_t *bytes)
+{
+    int64_t off = 0;
+    for (int64_t j = 0; j < lh; ++j) off += T * c->head_dim * bits_at(c, is_v, j) / 8;
+    if (bytes) *bytes = T * c->head_dim * bits_at(c, is_v, lh) / 8;
+    return off;
+}
+
 static int64_t head_meta_pairs(const ref_config *c, int is_v, int64_t T)
 {
-    if ((is_v ? c->bits_v : c->bits_k) == 16) return 0;
+    if (!(is_v ? c->head_bits_v : c->head_bits_k) && (is_v ? c->bits_v : c->bits_k) == 16) return 0;
     return is_v ? T * (c->head_dim / c->group_v)
                 : ((T + c->group_k - 1) / c->group_k) * c->head_dim;
 }
@@ -638,6 +683,7 @@ static void write_header(uint8_t *p, const ref_config *c, int64_t T, const geome
     put_u16(p + 22, (unsigned)c->group_k);
     put_u16(p + 24, (unsigned)c->group_v);
     p[26] = (uint8_t)c->transform;
+    p[27] = (uint8_t)((c->head_bits_k ? 1 : 0) | (c->head_bits_v ? 2 : 0));
     put_u64(p + 32, (uint64_t)T);
     put_u64(p + 40, (uint64_t)total);
     put_u64(p + 48, (uint64_t)g->off_meta_k);  put_u64(p + 56, (uint64_t)g->meta_k);
@@ -664,10 +710,25 @@ int ref_inspect(const uint8_t *p, ref_config *c, int64_t *tokens, uint64_t *tota
     c->group_k = (int32_t)get_u16(p + 22);
     c->group_v = (int32_t)get_u16(p + 24);
     c->transform = p[26];
+    /* per-head tables sit at the start of the auxiliary section: the pointers are only valid
+     * when `p` is the whole payload, not just its header */
+    {
+        int64_t LH = (int64_t)c->layers * c->heads;
+        const uint8_t *aux = p + get_u64(p + 80);
+        if (p[27] & ~3) return REF_ERR_FORMAT;
+        if (p[27] & 1) { c->head_bits_k = aux; aux += LH; }
+        if (p[27] & 2) c->head_bits_v = aux;
+    }
     if (tokens) *tokens = (int64_t)get_u64(p + 32);
     if (total_bytes) *total_bytes = get_u64(p + 40);
     if (sections) for (int i = 0; i < 10; ++i) sections[i] = get_u64(p + 48 + 8 * i);
-    if (ref_check_config(c) != REF_OK || (int64_t)get_u64(p + 32) < 0) return REF_ERR_FORMAT;
+    {
+        /* the tables themselves are checked by ref_decompress, which knows the payload size */
+        ref_config fields = *c;
+        if (fields.head_bits_k) { fields.head_bits_k = NULL; fields.bits_k = fields.bits_k ? 0xff : 4; }
+        if (fields.head_bits_v) { fields.head_bits_v = NULL; fields.bits_v = fields.bits_v ? 0xff : 4; }
+        if (ref_check_config(&fields) != REF_OK || (int64_t)get_u64(p + 32) < 0) return REF_ERR_FORMAT;
+    }
     return REF_OK;
 }
 
@@ -694,12 +755,17 @@ int ref_compress(const ref_config *c, const void *k, const void *v, const ref_la
         for (int l = 0; l < c->layers; ++l)
             for (int h = 0; h < c->heads; ++h) {
                 int64_t lh = (int64_t)l * c->heads + h;
-                rc = ref_compress_head(c, is_v, is_v ? v : k, lay, T, l, h, cbase + lh * hb,
+                rc = ref_compress_head(c, is_v, is_v ? v : k, lay, T, l, h,
+                                       cbase + head_code_off(c, is_v, T, lh, NULL),
                                        (uint16_t *)(mbase + lh * hm));
                 if (rc) return rc;
             }
     }
     if (!c->codec) {
+        uint8_t *tab = payload + g.off_aux;
+        int64_t LH = (int64_t)c->layers * c->heads;
+        if (c->head_bits_k) { memcpy(tab, c->head_bits_k, (size_t)LH); tab += LH; }
+        if (c->head_bits_v) memcpy(tab, c->head_bits_v, (size_t)LH);
         write_header(payload, c, T, &g, g.codes_k, g.codes_v, g.total);
         if (out_bytes) *out_bytes = (uint64_t)g.total;
         return REF_OK;
@@ -754,8 +820,21 @@ int ref_decompress(const uint8_t *payload, uint64_t bytes, void *k, void *v,
     uint64_t total, sec[10];
     int rc = ref_inspect(payload, &c, &T, &total, sec);
     if (rc) return rc;
-    if (expect && memcmp(expect, &c, sizeof c) != 0) return REF_ERR_MISMATCH;
     if (total > bytes) return REF_ERR_FORMAT;
+    {
+        int64_t LH = (int64_t)c.layers * c.heads;
+        uint64_t tables = (uint64_t)((c.head_bits_k ? LH : 0) + (c.head_bits_v ? LH : 0));
+        if (tables && (sec[4] + tables > total || c.codec)) return REF_ERR_FORMAT;
+        if (ref_check_config(&c) != REF_OK) return REF_ERR_FORMAT;
+        if (expect) {
+            ref_config a = *expect, b = c;
+            a.head_bits_k = a.head_bits_v = b.head_bits_k = b.head_bits_v = NULL;
+            if (memcmp(&a, &b, sizeof a) != 0) return REF_ERR_MISMATCH;
+            if (!expect->head_bits_k != !c.head_bits_k || !expect->head_bits_v != !c.head_bits_v) return REF_ERR_MISMATCH;
+            if (c.head_bits_k && memcmp(expect->head_bits_k, c.head_bits_k, (size_t)LH)) return REF_ERR_MISMATCH;
+            if (c.head_bits_v && memcmp(expect->head_bits_v, c.head_bits_v, (size_t)LH)) return REF_ERR_MISMATCH;
+        }
+    }
     geometry g;
     layout_of(&c, T, &g);
     if (sec[0] != (uint64_t)g.off_meta_k || sec[1] != (uint64_t)g.meta_k ||
@@ -778,7 +857,8 @@ int ref_decompress(const uint8_t *payload, uint64_t bytes, void *k, void *v,
         for (int l = 0; l < c.layers; ++l)
             for (int h = 0; h < c.heads; ++h) {
                 int64_t lh = (int64_t)l * c.heads + h;
-                const uint8_t *codes = payload + (is_v ? g.off_codes_v : g.off_codes_k) + lh * hb;
+                const uint8_t *codes = payload + (is_v ? g.off_codes_v : g.off_codes_k) +
+                                       head_code_off(&c, is_v, T, lh, NULL);
                 if (c.codec) {
                     for (int64_t cb = 0; cb < cph; ++cb) {
                         int64_t idx = (is_v ? g.chunks_k : 0) + lh * cph + cb;

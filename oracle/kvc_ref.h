@@ -49,6 +49,9 @@ typedef struct {
     int32_t group_v;            /* channels per V group (one group per token) */
     int32_t codec;              /* 0 none, 1 huff8 */
     int32_t transform;          /* 0 none, 1 Walsh-Hadamard over head_dim (ref_hadamard_row) */
+    /* optional per-head bit widths, index l*heads + h, values 2, 3, 4 or 8; when a table is
+     * given the uniform width of that tensor (bits_k / bits_v) must be 0.  Not with codec 1. */
+    const uint8_t *head_bits_k, *head_bits_v;
 } ref_config;
 
 /* Element index of x[l][h][t][0] (channel stride is 1):

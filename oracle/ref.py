@@ -29,7 +29,7 @@ class Config(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("layers", C.c_int32), ("heads", C.c_int32),
                 ("head_dim", C.c_int32), ("bits_k", C.c_int32), ("bits_v", C.c_int32),
                 ("group_k", C.c_int32), ("group_v", C.c_int32), ("codec", C.c_int32),
-                ("transform", C.c_int32)]
+                ("transform", C.c_int32), ("head_bits_k", C.c_void_p), ("head_bits_v", C.c_void_p)]
 
 
 class Layout(C.Structure):
@@ -68,8 +68,23 @@ def _p(a):
 
 
 def config(dtype=F16, layers=1, heads=1, head_dim=128, bits_k=4, bits_v=4, group_k=32, group_v=32,
-           codec=0, transform=0):
-    return Config(dtype, layers, heads, head_dim, bits_k, bits_v, group_k, group_v, codec, transform)
+           codec=0, transform=0, head_bits_k=None, head_bits_v=None):
+    """head_bits_k / head_bits_v: optional uint8 arrays of layers*heads widths (the uniform width of
+    that tensor is then 0); the arrays are kept alive by the returned object."""
+    keep = []
+    ptrs = []
+    for t in (head_bits_k, head_bits_v):
+        if t is None:
+            ptrs.append(None)
+        else:
+            a = np.ascontiguousarray(t, dtype=np.uint8).reshape(-1)
+            assert a.size == layers * heads
+            keep.append(a)
+            ptrs.append(a.ctypes.data)
+    cfg = Config(dtype, layers, heads, head_dim, 0 if head_bits_k is not None else bits_k,
+                 0 if head_bits_v is not None else bits_v, group_k, group_v, codec, transform, ptrs[0], ptrs[1])
+    cfg._keep = keep
+    return cfg
 
 
 def contiguous_layout(heads, tokens, head_dim):
