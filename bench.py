@@ -27,13 +27,17 @@ WORKLOADS = {
     "llama70b_32k_fp16_int4g32": (80, 8, 32768, "f16", 4, 4, 32, 32, 0),
     "llama70b_32k_fp16_hadamard_int4g32_huff8": (80, 8, 32768, "f16", 4, 4, 32, 32, 1, 1),
     "llama70b_32k_fp16_hadamard_int4g32": (80, 8, 32768, "f16", 4, 4, 32, 32, 0, 1),
+    # per-head widths: a seeded random half of the heads at 8 bits, the other half at 2 (the paper's
+    # MixHQ takes the split from trained head masks, which are not available here)
+    "llama70b_32k_fp16_mixhq_8_2_g32": (80, 8, 32768, "f16", 4, 4, 32, 32, 0, 0, (8, 2)),
     "llama8b_8k_bf16_int4g32": (32, 8, 8192, "bf16", 4, 4, 32, 32, 0),
     "llama8b_8k_bf16_int2g64": (32, 8, 8192, "bf16", 2, 2, 64, 64, 0),
     "tiny_fp16_int4g32": (1, 8, 1024, "f16", 4, 4, 32, 32, 0),
 }
 
 
-def cpu_baseline(x_dev, layers, heads, tokens, dt, bits_k, bits_v, gk, gv, codec, transform, sample_layers):
+def cpu_baseline(x_dev, layers, heads, tokens, dt, bits_k, bits_v, gk, gv, codec, transform, sample_layers,
+                 head_bits=None):
     """The oracle as it stands, single-threaded, on the first `sample_layers` layers."""
     import numpy as np
     from oracle import ref
@@ -41,7 +45,9 @@ def cpu_baseline(x_dev, layers, heads, tokens, dt, bits_k, bits_v, gk, gv, codec
     xs = x_dev[:sample_layers].cpu()
     xu = kvgen.as_u16(xs)
     cfg = ref.config(dtype=dt, layers=sample_layers, heads=heads, bits_k=bits_k, bits_v=bits_v,
-                     group_k=gk, group_v=gv, codec=codec, transform=transform)
+                     group_k=gk, group_v=gv, codec=codec, transform=transform,
+                     head_bits_k=head_bits[0][:sample_layers * heads] if head_bits else None,
+                     head_bits_v=head_bits[1][:sample_layers * heads] if head_bits else None)
     lay = ref.contiguous_layout(heads, tokens, 128)
     t0 = time.perf_counter()
     payload = ref.compress(cfg, xu[0, 0], xu[0, 1], lay, tokens)
@@ -138,11 +144,18 @@ def main():
 
     L, H, T, dtn, bk, bv, gk, gv, codec = WORKLOADS[args.workload][:9]
     transform = WORKLOADS[args.workload][9] if len(WORKLOADS[args.workload]) > 9 else 0
+    mix = WORKLOADS[args.workload][10] if len(WORKLOADS[args.workload]) > 10 else None
+    head_bits = None
+    if mix:
+        import numpy as np
+        rng = np.random.default_rng(0)
+        head_bits = [np.where(rng.permutation(L * H) < L * H // 2, mix[0], mix[1]).astype(np.uint8) for _ in range(2)]
     dtype, dt = (torch.float16, kvc.F16) if dtn == "f16" else (torch.bfloat16, kvc.BF16)
     dev = "cuda:0"
     x = kvgen.make_kv(0, L, H, 128, T, dtype, dev)
     y = torch.empty_like(x)
-    plan = kvc.Plan(dt, L, H, 128, bk, bv, gk, gv, codec, max_tokens=T, transform=transform)
+    plan = kvc.Plan(dt, L, H, 128, bk, bv, gk, gv, codec, max_tokens=T, transform=transform,
+                    head_bits_k=head_bits[0] if mix else None, head_bits_v=head_bits[1] if mix else None)
     buf = kvc.Buffers(plan, [T], dev)
     src, dst = [kvc.contiguous_request(x)], [kvc.contiguous_request(y)]
     stream = torch.cuda.current_stream().cuda_stream
@@ -256,7 +269,7 @@ def main():
         out["policy"] = policy_table(x, y, dt, L, H, T, max(2, args.steps // 3))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(x, L, H, T, dt, bk, bv, gk, gv, codec, transform,
-                                           min(args.cpu_sample_layers, L))
+                                           min(args.cpu_sample_layers, L), head_bits)
     print(json.dumps(out))
     return 0
 

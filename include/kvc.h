@@ -66,7 +66,16 @@ enum { KVC_CODEC_NONE = 0, KVC_CODEC_HUFF8 = 1 };
  *                     in natural order; fp32 butterflies with strides 1, 2, ..., 64; results
  *                     rounded to the tensor type); a tensor stored unchanged (16 bits) is not
  *                     transformed
- *   head_bits_k/v   : reserved for per-head bit widths (MixHQ); must be NULL
+ *   head_bits_k/v   : optional per-head bit widths (section 5.1: mixed precision at head
+ *                     granularity; the mechanism behind MixHQ, which keeps the heads that matter
+ *                     at a high precision and gives the others very few bits).  HOST arrays of
+ *                     layers * kv_heads bytes, index layer * kv_heads + head, values 2, 3, 4 or
+ *                     8; NULL = one width for the whole tensor.  A tensor with a table has
+ *                     bits_k (bits_v) = 0.  kvc_plan copies the tables.  The codes of the heads
+ *                     follow each other in (layer, head) order, each with its own width; the
+ *                     tables travel in the payload's auxiliary section (K table, then V table).
+ *                     Which head gets which width is the caller's choice.  Not with a codec.
+ *                     A plan with tables needs a workspace (kvc_workspace_size).
  * Every group carries two fp16 values (scale, zero): the 32 bits per group that cap
  * 2-bit / group-32 at 16/(2+1) = 5.33x (section 7.3).
  */

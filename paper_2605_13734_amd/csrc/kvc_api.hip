@@ -17,7 +17,45 @@ struct kvc_plan_s {
     int32_t max_batch;
     size_t ws_request;          // workspace bytes per request
     size_t ws_state_off;        // offset of the scan state inside a request's workspace
+    // per-head bit widths (section 5.1: head-wise mixed precision; the MixHQ mechanism)
+    int has_table[2];           // K, V
+    uint8_t *blob;              // host image of the device tables, see table_layout
+    size_t blob_bytes;          // multiple of 256; the workspace starts with a copy of it
+    int width_count[2][4];      // heads per width 2, 3, 4, 8
 };
+
+static const int kWidths[4] = {2, 3, 4, 8};
+
+// Device tables of a plan with per-head widths, in this order (LH = layers * kv_heads):
+//   aux image : the bytes of the payload's auxiliary section (K table, V table, zero padding
+//               to 16 bytes)
+//   per tensor: long long bits_before[LH], then int head_list[LH] (heads grouped by width, in
+//               the order 2, 3, 4, 8; head order kept inside a group)
+struct TableLayout {
+    size_t aux_image, bits_before[2], head_list[2], total;
+};
+static TableLayout table_layout(long long LH, int tables)
+{
+    TableLayout t;
+    size_t at = 0;
+    t.aux_image = at;
+    at += (size_t)((tables * LH + 15) & ~15ll);
+    at = (at + 255) & ~(size_t)255;
+    for (int i = 0; i < 2; ++i) {
+        t.bits_before[i] = at;
+        at += (size_t)LH * 8;
+        t.head_list[i] = at;
+        at += (((size_t)LH * 4) + 7) & ~(size_t)7;
+    }
+    t.total = (at + 255) & ~(size_t)255;
+    return t;
+}
+
+static int width_at(const kvc_plan_t *p, int is_v, long long lh)
+{
+    const uint8_t *t = is_v ? p->strat.head_bits_v : p->strat.head_bits_k;
+    return t ? t[lh] : (is_v ? p->strat.bits_v : p->strat.bits_k);
+}
 
 // Optional measurement hook (kvc_trace): events recorded between the stages of a call.
 static hipEvent_t *g_trace = nullptr;
@@ -50,12 +88,22 @@ static void geometry(const kvc_plan_t *p, long long T, Geometry *g)
 {
     const long long LH = (long long)p->model.layers * p->model.kv_heads, D = p->model.head_dim;
     const int bk = p->strat.bits_k, bv = p->strat.bits_v;
-    g->meta_k = bk == 16 ? 0 : 4 * LH * ((T + p->strat.group_k - 1) / p->strat.group_k) * D;
-    g->meta_v = bv == 16 ? 0 : 4 * LH * T * (D / p->strat.group_v);
-    g->codes_k = LH * T * D * bk / 8;
-    g->codes_v = LH * T * D * bv / 8;
+    g->meta_k = (bk == 16 && !p->has_table[0]) ? 0 : 4 * LH * ((T + p->strat.group_k - 1) / p->strat.group_k) * D;
+    g->meta_v = (bv == 16 && !p->has_table[1]) ? 0 : 4 * LH * T * (D / p->strat.group_v);
+    long long sum_k = LH * bk, sum_v = LH * bv;          // widths summed over the heads
+    if (p->has_table[0]) {
+        sum_k = 0;
+        for (long long i = 0; p->strat.head_bits_k && i < LH; ++i) sum_k += p->strat.head_bits_k[i];
+    }
+    if (p->has_table[1]) {
+        sum_v = 0;
+        for (long long i = 0; p->strat.head_bits_v && i < LH; ++i) sum_v += p->strat.head_bits_v[i];
+    }
+    g->codes_k = sum_k * T * D / 8;
+    g->codes_v = sum_v * T * D / 8;
     g->chunks_k = g->chunks_v = LH * chunks_per_head(T);
     g->aux = p->strat.codec ? 512 + 4 * (g->chunks_k + g->chunks_v + 1) : 0;
+    g->aux += (p->has_table[0] + p->has_table[1]) * LH;
     g->off_meta_k = kHeader;
     g->off_meta_v = g->off_meta_k + a16(g->meta_k);
     g->off_aux = g->off_meta_v + a16(g->meta_v);
@@ -84,11 +132,12 @@ static void make_header(const kvc_plan_t *p, long long T, const Geometry &g, Hea
     put32(h + 8, (uint32_t)p->model.layers);
     put32(h + 12, (uint32_t)p->model.kv_heads);
     put32(h + 16, (uint32_t)p->model.head_dim);
-    h[20] = p->strat.bits_k;
-    h[21] = p->strat.bits_v;
+    h[20] = p->has_table[0] ? 0 : p->strat.bits_k;
+    h[21] = p->has_table[1] ? 0 : p->strat.bits_v;
     put16(h + 22, p->strat.group_k);
     put16(h + 24, p->strat.group_v);
     h[26] = p->strat.transform;
+    h[27] = (uint8_t)(p->has_table[0] | (p->has_table[1] << 1));
     put64(h + 32, (uint64_t)T);
     put64(h + 48, (uint64_t)g.off_meta_k); put64(h + 56, (uint64_t)g.meta_k);
     put64(h + 64, (uint64_t)g.off_meta_v); put64(h + 72, (uint64_t)g.meta_v);
@@ -122,12 +171,21 @@ static int check_pair(const kvc_model *m, const kvc_strategy *s)
     if (!m || !s) return KVC_ERR_ARG;
     if (m->dtype != KVC_F16 && m->dtype != KVC_BF16) return KVC_ERR_ARG;
     if (m->layers < 1 || m->kv_heads < 1 || m->head_dim < 1) return KVC_ERR_ARG;
-    if (!bits_ok(s->bits_k) || !bits_ok(s->bits_v)) return KVC_ERR_ARG;
+    if ((!s->head_bits_k && !bits_ok(s->bits_k)) || (!s->head_bits_v && !bits_ok(s->bits_v))) return KVC_ERR_ARG;
     if (s->codec != KVC_CODEC_NONE && s->codec != KVC_CODEC_HUFF8) return KVC_ERR_ARG;
-    if (s->bits_k != 16 && !group_ok(s->group_k)) return KVC_ERR_ARG;
-    if (s->bits_v != 16 && !group_ok(s->group_v)) return KVC_ERR_ARG;
+    if ((s->head_bits_k || s->bits_k != 16) && !group_ok(s->group_k)) return KVC_ERR_ARG;
+    if ((s->head_bits_v || s->bits_v != 16) && !group_ok(s->group_v)) return KVC_ERR_ARG;
+    const long long LH = (long long)m->layers * m->kv_heads;
+    for (int is_v = 0; is_v < 2; ++is_v) {
+        const uint8_t *t = is_v ? s->head_bits_v : s->head_bits_k;
+        if (!t) continue;
+        if ((is_v ? s->bits_v : s->bits_k) != 0) return KVC_ERR_ARG;        // the table replaces the uniform width
+        for (long long i = 0; i < LH; ++i)
+            if (t[i] != 2 && t[i] != 3 && t[i] != 4 && t[i] != 8) return KVC_ERR_ARG;
+    }
     if (m->head_dim != kDim) return KVC_ERR_UNSUPPORTED;
-    if (s->transform > KVC_T_HADAMARD || s->head_bits_k || s->head_bits_v) return KVC_ERR_UNSUPPORTED;
+    if (s->transform > KVC_T_HADAMARD) return KVC_ERR_UNSUPPORTED;
+    if (s->codec && (s->head_bits_k || s->head_bits_v)) return KVC_ERR_UNSUPPORTED;
     if (s->codec && (s->bits_k == 16 || s->bits_v == 16)) return KVC_ERR_UNSUPPORTED;
     return KVC_OK;
 }
@@ -148,6 +206,32 @@ extern "C" int kvc_plan(const kvc_model *model, const kvc_strategy *strategy, in
     if (p->strat.bits_v == 16) p->strat.group_v = 32;
     p->max_tokens = max_tokens;
     p->max_batch = max_batch;
+    p->has_table[0] = strategy->head_bits_k ? 1 : 0;
+    p->has_table[1] = strategy->head_bits_v ? 1 : 0;
+    p->strat.head_bits_k = p->strat.head_bits_v = nullptr;
+    if (p->has_table[0] || p->has_table[1]) {
+        // the plan owns copies of the tables, inside the image of the device tables
+        const long long LH = (long long)model->layers * model->kv_heads;
+        const TableLayout t = table_layout(LH, p->has_table[0] + p->has_table[1]);
+        p->blob = (uint8_t *)calloc(1, t.total);
+        if (!p->blob) { free(p); return KVC_ERR_ARG; }
+        p->blob_bytes = t.total;
+        uint8_t *aux = p->blob + t.aux_image;
+        if (p->has_table[0]) { memcpy(aux, strategy->head_bits_k, (size_t)LH); p->strat.head_bits_k = aux; aux += LH; }
+        if (p->has_table[1]) { memcpy(aux, strategy->head_bits_v, (size_t)LH); p->strat.head_bits_v = aux; }
+        for (int is_v = 0; is_v < 2; ++is_v) {
+            if (!p->has_table[is_v]) continue;
+            long long *before = (long long *)(p->blob + t.bits_before[is_v]);
+            int *list = (int *)(p->blob + t.head_list[is_v]);
+            long long sum = 0, at = 0;
+            for (long long i = 0; i < LH; ++i) { before[i] = sum; sum += width_at(p, is_v, i); }
+            for (int w = 0; w < 4; ++w) {
+                p->width_count[is_v][w] = 0;
+                for (long long i = 0; i < LH; ++i)
+                    if (width_at(p, is_v, i) == kWidths[w]) { list[at++] = (int)i; ++p->width_count[is_v][w]; }
+            }
+        }
+    }
     if (strategy->codec) {
         // histograms, encode tables, decode tables, ticket, then the scan state
         // one scan-state word per chunk of K and of V
@@ -159,7 +243,11 @@ extern "C" int kvc_plan(const kvc_model *model, const kvc_strategy *strategy, in
     return KVC_OK;
 }
 
-extern "C" void kvc_plan_free(kvc_plan_t *plan) { free(plan); }
+extern "C" void kvc_plan_free(kvc_plan_t *plan)
+{
+    if (plan) free(plan->blob);
+    free(plan);
+}
 
 extern "C" int kvc_payload_size(const kvc_plan_t *plan, int64_t tokens, uint64_t *bytes, int *is_exact)
 {
@@ -173,7 +261,7 @@ extern "C" int kvc_payload_size(const kvc_plan_t *plan, int64_t tokens, uint64_t
 
 extern "C" size_t kvc_workspace_size(const kvc_plan_t *plan)
 {
-    return plan ? plan->ws_request * (size_t)plan->max_batch : 0;
+    return plan ? plan->blob_bytes + plan->ws_request * (size_t)plan->max_batch : 0;
 }
 
 extern "C" int kvc_payload_inspect(const void *header128, kvc_model *model, kvc_strategy *strategy,
@@ -197,15 +285,25 @@ extern "C" int kvc_payload_inspect(const void *header128, kvc_model *model, kvc_
     s.group_v = (uint16_t)get16(h + 24);
     s.transform = h[26];
     const int64_t T = (int64_t)get64(h + 32);
-    int rc = check_pair(&m, &s);
+    // a tensor with a per-head width table has width 0 in the header; the table itself is in the
+    // auxiliary section, which this function does not see
+    const int flags = h[27];
+    if (flags & ~3) return KVC_ERR_FORMAT;
+    kvc_strategy probe = s;
+    if (flags & 1) { if (s.bits_k) return KVC_ERR_FORMAT; probe.bits_k = 4; }
+    if (flags & 2) { if (s.bits_v) return KVC_ERR_FORMAT; probe.bits_v = 4; }
+    int rc = check_pair(&m, &probe);
     if (rc == KVC_ERR_ARG || T < 0) return KVC_ERR_FORMAT;
-    for (int i = 27; i < 32; ++i)
+    if (flags && s.codec) return KVC_ERR_FORMAT;
+    for (int i = 28; i < 32; ++i)
         if (h[i]) return KVC_ERR_FORMAT;
     // the fixed part of the section table must be the closed form of the fields above
     kvc_plan_t tmp;
     memset(&tmp, 0, sizeof tmp);
     tmp.model = m;
     tmp.strat = s;
+    tmp.has_table[0] = flags & 1;
+    tmp.has_table[1] = (flags >> 1) & 1;
     Geometry g;
     geometry(&tmp, T, &g);
     const uint64_t want[7] = {(uint64_t)g.off_meta_k, (uint64_t)g.meta_k, (uint64_t)g.off_meta_v,
@@ -214,7 +312,16 @@ extern "C" int kvc_payload_inspect(const void *header128, kvc_model *model, kvc_
     for (int i = 0; i < 7; ++i)
         if (get64(h + 48 + 8 * i) != want[i]) return KVC_ERR_FORMAT;
     const uint64_t total = get64(h + 40), ck = get64(h + 104), ov = get64(h + 112), cv = get64(h + 120);
-    if (!s.codec) {
+    if (flags) {
+        // code sizes follow from the width tables, which are not in the header: only their
+        // consistency and the bounds that hold for any table (2 to 8 bits per element) are checked
+        const uint64_t unit = (uint64_t)m.layers * m.kv_heads * (uint64_t)T * 16;      // bytes per bit of width
+        const uint64_t lo_k = (flags & 1) ? 2 * unit : (uint64_t)s.bits_k * unit, hi_k = (flags & 1) ? 8 * unit : lo_k;
+        const uint64_t lo_v = (flags & 2) ? 2 * unit : (uint64_t)s.bits_v * unit, hi_v = (flags & 2) ? 8 * unit : lo_v;
+        if (ck < lo_k || ck > hi_k || cv < lo_v || cv > hi_v || ov != (uint64_t)g.off_codes_k + (uint64_t)a16((long long)ck) ||
+            total != ov + (uint64_t)a16((long long)cv))
+            return KVC_ERR_FORMAT;
+    } else if (!s.codec) {
         if (total != (uint64_t)g.total || ck != (uint64_t)g.codes_k || ov != (uint64_t)g.off_codes_v ||
             cv != (uint64_t)g.codes_v)
             return KVC_ERR_FORMAT;
@@ -298,6 +405,41 @@ static QuantArgs quant_args(const kvc_plan_t *p, const kvc_request *r, int is_v,
     return a;
 }
 
+// One tensor without the coder: one launch, or one per width present in the head table.
+static int launch_tensor(const kvc_plan_t *p, int is_v, bool compress, QuantArgs a, const uint8_t *dev_tables, hipStream_t s)
+{
+    const int dt = p->model.dtype;
+    const int group = is_v ? p->strat.group_v : p->strat.group_k;
+    if (!p->has_table[is_v]) {
+        const int bits = is_v ? p->strat.bits_v : p->strat.bits_k;
+        return compress ? launch_compress_tensor(is_v, bits, group, dt, a, s) : launch_decompress_tensor(is_v, bits, group, dt, a, s);
+    }
+    const long long LH = (long long)p->model.layers * p->model.kv_heads;
+    const TableLayout t = table_layout(LH, p->has_table[0] + p->has_table[1]);
+    a.bits_before = (const long long *)(dev_tables + t.bits_before[is_v]);
+    const int *list = (const int *)(dev_tables + t.head_list[is_v]);
+    for (int w = 0; w < 4; ++w) {
+        const int n = p->width_count[is_v][w];
+        if (n > 0) {
+            a.head_list = list;
+            a.total_units = a.units_per_head * n;
+            const int rc = compress ? launch_compress_tensor(is_v, kWidths[w], group, dt, a, s)
+                                    : launch_decompress_tensor(is_v, kWidths[w], group, dt, a, s);
+            if (rc) return rc;
+        }
+        list += n;
+    }
+    return KVC_OK;
+}
+
+// The plan's device tables at the start of the workspace (every call brings them again: the
+// workspace belongs to the caller between calls).
+static int upload_tables(const kvc_plan_t *p, void *workspace, hipStream_t s)
+{
+    if (!p->blob_bytes) return KVC_OK;
+    return hipMemcpyAsync(workspace, p->blob, p->blob_bytes, hipMemcpyHostToDevice, s) == hipSuccess ? KVC_OK : KVC_ERR_DEVICE;
+}
+
 static CoderArgs coder_args(const kvc_plan_t *p, const QuantArgs &q, int is_v, uint8_t *payload,
                             const Geometry &g, uint8_t *ws, long long capacity, uint64_t *out_bytes)
 {
@@ -331,7 +473,7 @@ static int check_batch(const kvc_plan_t *p, const kvc_request *reqs, int32_t n, 
 {
     if (!p || !reqs || n < 1 || !payload || !off || !aligned16(payload)) return KVC_ERR_ARG;
     if (n > p->max_batch) return KVC_ERR_CAPACITY;
-    if (p->ws_request && (!workspace || !aligned16(workspace))) return KVC_ERR_ARG;
+    if ((p->ws_request || p->blob_bytes) && (!workspace || !aligned16(workspace))) return KVC_ERR_ARG;
     for (int i = 0; i < n; ++i) {
         int rc = check_request(p, &reqs[i]);
         if (rc) return rc;
@@ -357,6 +499,7 @@ extern "C" int kvc_compress(const kvc_plan_t *plan, const kvc_request *reqs, int
     const kvc_strategy &st = plan->strat;
     const int dt = plan->model.dtype;
     KVC_TRY(launch_fill_u32((uint32_t *)dev_status, 0, n, s));
+    KVC_TRY(upload_tables(plan, workspace, s));
     for (int i = 0; i < n; ++i) {
         const kvc_request *r = &reqs[i];
         Geometry g;
@@ -368,21 +511,25 @@ extern "C" int kvc_compress(const kvc_plan_t *plan, const kvc_request *reqs, int
         // alignment padding after the V metadata and after the coder tables is zero
         if (a16(g.meta_v) != g.meta_v)
             KVC_TRY(launch_fill_u32((uint32_t *)(pl + g.off_meta_v + g.meta_v), 0, (a16(g.meta_v) - g.meta_v) / 4, s));
-        if (a16(g.aux) != g.aux)
+        if (plan->blob_bytes) {
+            // the width tables and their padding: a device copy of the image at the start of the workspace
+            if (hipMemcpyAsync(pl + g.off_aux, workspace, (size_t)a16(g.aux), hipMemcpyDeviceToDevice, s) != hipSuccess)
+                return KVC_ERR_DEVICE;
+        } else if (a16(g.aux) != g.aux)
             KVC_TRY(launch_fill_u32((uint32_t *)(pl + g.off_aux + g.aux), 0, (a16(g.aux) - g.aux) / 4, s));
         QuantArgs qk = quant_args(plan, r, 0, pl, g, dev_status + i, true);
         QuantArgs qv = quant_args(plan, r, 1, pl, g, dev_status + i, true);
         if (!st.codec) {
             mark(s);
             mark(s);
-            KVC_TRY(launch_compress_tensor(0, st.bits_k, st.group_k, dt, qk, s));
+            KVC_TRY(launch_tensor(plan, 0, true, qk, (const uint8_t *)workspace, s));
             mark(s);
-            KVC_TRY(launch_compress_tensor(1, st.bits_v, st.group_v, dt, qv, s));
+            KVC_TRY(launch_tensor(plan, 1, true, qv, (const uint8_t *)workspace, s));
             mark(s);
             KVC_TRY(launch_fill_u32((uint32_t *)(out_bytes + i), (uint32_t)g.total, 1, s));
             KVC_TRY(launch_fill_u32((uint32_t *)(out_bytes + i) + 1, (uint32_t)((uint64_t)g.total >> 32), 1, s));
         } else {
-            uint8_t *ws = (uint8_t *)workspace + (size_t)i * plan->ws_request;
+            uint8_t *ws = (uint8_t *)workspace + plan->blob_bytes + (size_t)i * plan->ws_request;
             const long long cap = (long long)(payload_off[i + 1] - payload_off[i]);
             CoderArgs ck = coder_args(plan, qk, 0, pl, g, ws, cap, out_bytes + i);
             CoderArgs cv = coder_args(plan, qv, 1, pl, g, ws, cap, out_bytes + i);
@@ -423,6 +570,7 @@ extern "C" int kvc_decompress(const kvc_plan_t *plan, const void *payload, const
     const kvc_strategy &st = plan->strat;
     const int dt = plan->model.dtype;
     KVC_TRY(launch_fill_u32((uint32_t *)dev_status, 0, n, s));
+    KVC_TRY(upload_tables(plan, workspace, s));
     for (int i = 0; i < n; ++i) {
         const kvc_request *r = &dst[i];
         Geometry g;
@@ -436,17 +584,19 @@ extern "C" int kvc_decompress(const kvc_plan_t *plan, const void *payload, const
         // words 10/11 (total), 26..31 (code sizes) depend on the data when the coder is on
         const uint32_t mask = st.codec ? 0x03fff3ffu : 0xffffffffu;
         KVC_TRY(launch_check_header(pl, hb, mask, dev_status + i, s));
+        if (plan->blob_bytes)       // the payload's width tables must be the plan's
+            KVC_TRY(launch_check_bytes(pl + g.off_aux, (const uint8_t *)workspace, g.aux, dev_status + i, s));
         QuantArgs qk = quant_args(plan, r, 0, pl, g, dev_status + i, false);
         QuantArgs qv = quant_args(plan, r, 1, pl, g, dev_status + i, false);
         if (!st.codec) {
             mark(s);
             mark(s);
-            KVC_TRY(launch_decompress_tensor(0, st.bits_k, st.group_k, dt, qk, s));
+            KVC_TRY(launch_tensor(plan, 0, false, qk, (const uint8_t *)workspace, s));
             mark(s);
-            KVC_TRY(launch_decompress_tensor(1, st.bits_v, st.group_v, dt, qv, s));
+            KVC_TRY(launch_tensor(plan, 1, false, qv, (const uint8_t *)workspace, s));
             mark(s);
         } else {
-            uint8_t *ws = (uint8_t *)workspace + (size_t)i * plan->ws_request;
+            uint8_t *ws = (uint8_t *)workspace + plan->blob_bytes + (size_t)i * plan->ws_request;
             CoderArgs ck = coder_args(plan, qk, 0, pl, g, ws, cap, nullptr);
             CoderArgs cv = coder_args(plan, qv, 1, pl, g, ws, cap, nullptr);
             mark(s);

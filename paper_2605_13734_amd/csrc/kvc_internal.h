@@ -18,6 +18,11 @@ struct QuantArgs {
     int group;                  // runtime copy of the group size
     int dense;                  // rows of a head are contiguous: stride_token == head_dim, no block table
     int rotate;                 // stage T: rows are Hadamard-transformed on the way in / back on the way out
+    // per-head bit widths (null = one width for all heads): the heads this launch covers, and for
+    // every head the sum of the widths of the heads before it (its codes start at that many times
+    // tokens * 16 bytes into the section)
+    const int *head_list;
+    const long long *bits_before;
     long long units_per_head;   // work units (one wave each) per (layer, head)
     long long total_units;
     int *status;                // device status word of the request
@@ -39,6 +44,7 @@ int launch_write_header(uint8_t *dst, const HeaderBytes &h, hipStream_t s);
 int launch_check_header(const uint8_t *hdr, const HeaderBytes &expect, uint32_t mask, int *status,
                         hipStream_t s);
 int launch_fill_u32(uint32_t *dst, uint32_t value, long long n, hipStream_t s);
+int launch_check_bytes(const uint8_t *a, const uint8_t *b, long long n, int *status, hipStream_t s);
 
 // ---- lossless stage (codec 1) -----------------------------------------------------------
 

@@ -21,11 +21,19 @@ __device__ __forceinline__ bool unit_pos(const QuantArgs &a, UnitPos &u)
 {
     long long unit = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (unit >= a.total_units) return false;
-    u.lh = unit / a.units_per_head;
-    u.blk = unit - u.lh * a.units_per_head;
+    const long long slot = unit / a.units_per_head;
+    u.lh = a.head_list ? a.head_list[slot] : slot;
+    u.blk = unit - slot * a.units_per_head;
     long long l = u.lh / a.heads, h = u.lh - l * a.heads;
     u.head_off = l * a.x.stride_layer + h * a.x.stride_head;
     return true;
+}
+
+// first code byte of head lh (width BITS) in its section
+template <int BITS> __device__ __forceinline__ uint8_t *head_codes(const QuantArgs &a, long long lh)
+{
+    const long long widths = a.bits_before ? a.bits_before[lh] : lh * BITS;
+    return a.codes + widths * a.tokens * 16;
 }
 
 __device__ __forceinline__ void report(int *status, bool bad)
@@ -51,7 +59,7 @@ __global__ __launch_bounds__(256) void compress_k_kernel(QuantArgs a)
     KParams kp;
     uint8_t *meta_block = a.meta + (u.lh * a.units_per_head + u.blk) * (kDim * 4);
     k_group_params<BITS, DT, P * 8, 16>(raw, (uint8_t *)(xch_all + (threadIdx.x >> 6) * kXchFloats), meta_block, kp);
-    uint8_t *codes = a.codes + (u.lh * a.tokens + row0) * (16 * BITS);
+    uint8_t *codes = head_codes<BITS>(a, u.lh) + row0 * (16 * BITS);
     const long long left = a.tokens - row0;
     k_emit<BITS, DT, P, false>(raw, kp, codes, left < G ? (int)left : G);
     report(a.status, bad);
@@ -70,7 +78,7 @@ __global__ __launch_bounds__(256) void decompress_k_kernel(QuantArgs a)
     const u32x4 m0 = m[0], m1 = m[1];
     float scale[8], zero[8];
     const bool clamp = k_meta_floats<BITS, DT>(m0, m1, scale, zero);
-    uint8_t *codes = a.codes + (u.lh * a.tokens + row0) * (16 * BITS);
+    uint8_t *codes = head_codes<BITS>(a, u.lh) + row0 * (16 * BITS);
     const long long left = a.tokens - row0;
     bool bad = false;
     dequant_pass<BITS, DT, false, DENSE, false>(codes, scale, zero, clamp, a.x, u.head_off, row0,
@@ -93,7 +101,7 @@ __global__ __launch_bounds__(256) void compress_v_kernel(QuantArgs a)
     if (a.rotate) rotate_rows<DT, 8>(raw);
     VParams vp;
     v_pass_params<BITS, GV, DT>(raw, vp);
-    uint8_t *codes = a.codes + (u.lh * a.tokens + row0) * (16 * BITS);
+    uint8_t *codes = head_codes<BITS>(a, u.lh) + row0 * (16 * BITS);
     uint32_t *meta = (uint32_t *)a.meta + (u.lh * a.tokens + row0) * NG;
     const long long left = a.tokens - row0;
     v_emit<BITS, GV, DT, false>(raw, vp, codes, left < kPassRows ? (int)left : kPassRows, meta);
@@ -117,7 +125,7 @@ __global__ __launch_bounds__(256) void decompress_v_kernel(QuantArgs a)
     for (int i = 0; i < 8; ++i) mw[i] = meta[(4 * i + rsub < rows ? 4 * i + rsub : 0) * ng];
     float scale[8], zero[8];
     const bool clamp = v_meta_floats<BITS, DT>(mw, scale, zero);
-    uint8_t *codes = a.codes + (u.lh * a.tokens + row0) * (16 * BITS);
+    uint8_t *codes = head_codes<BITS>(a, u.lh) + row0 * (16 * BITS);
     bool bad = false;
     dequant_pass<BITS, DT, true, DENSE, false>(codes, scale, zero, clamp, a.x, u.head_off, row0, rows, bad, 0, a.rotate != 0);
     report(a.status, bad);
@@ -161,6 +169,13 @@ __global__ void check_header_kernel(const uint32_t *hdr, HeaderBytes expect, uin
     const int i = threadIdx.x;
     bool diff = i < 32 && ((mask >> i) & 1u) && hdr[i] != expect.w[i];
     if (diff) atomicOr(status, KVC_DEV_BAD_HEADER);
+}
+
+// two byte strings of the same length must be equal (the width tables of payload and plan)
+__global__ void check_bytes_kernel(const uint8_t *a, const uint8_t *b, long long n, int *status)
+{
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n && a[i] != b[i]) atomicOr(status, KVC_DEV_BAD_HEADER);
 }
 
 __global__ void fill_u32_kernel(uint32_t *dst, uint32_t value, long long n)
@@ -256,6 +271,13 @@ int launch_write_header(uint8_t *dst, const HeaderBytes &h, hipStream_t s)
 int launch_check_header(const uint8_t *hdr, const HeaderBytes &expect, uint32_t mask, int *status, hipStream_t s)
 {
     hipLaunchKernelGGL(check_header_kernel, dim3(1), dim3(64), 0, s, (const uint32_t *)hdr, expect, mask, status);
+    return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_DEVICE;
+}
+
+int launch_check_bytes(const uint8_t *a, const uint8_t *b, long long n, int *status, hipStream_t s)
+{
+    if (n <= 0) return KVC_OK;
+    hipLaunchKernelGGL(check_bytes_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a, b, n, status);
     return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_DEVICE;
 }
 

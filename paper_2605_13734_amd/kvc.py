@@ -107,9 +107,21 @@ class Plan:
     """kvc_plan / kvc_plan_free, kvc_payload_size, kvc_workspace_size."""
 
     def __init__(self, dtype, layers, kv_heads, head_dim=128, bits_k=4, bits_v=4, group_k=32,
-                 group_v=32, codec=0, max_tokens=0, max_batch=1, transform=0):
+                 group_v=32, codec=0, max_tokens=0, max_batch=1, transform=0, head_bits_k=None, head_bits_v=None):
+        """head_bits_k / head_bits_v: optional sequences of layers * kv_heads widths (the uniform
+        width of that tensor is then passed as 0)."""
         self.model = Model(dtype, layers, kv_heads, head_dim)
-        self.strategy = Strategy(bits_k, bits_v, group_k, group_v, codec, transform, None, None)
+        tabs = []
+        for t in (head_bits_k, head_bits_v):
+            if t is None:
+                tabs.append(None)
+            else:
+                tabs.append((C.c_uint8 * (layers * kv_heads))(*[int(b) for b in t]))
+        self._tables = tabs
+        self.strategy = Strategy(0 if tabs[0] is not None else bits_k, 0 if tabs[1] is not None else bits_v,
+                                 group_k, group_v, codec, transform,
+                                 C.cast(tabs[0], C.c_void_p) if tabs[0] is not None else None,
+                                 C.cast(tabs[1], C.c_void_p) if tabs[1] is not None else None)
         self.max_tokens, self.max_batch = max_tokens, max_batch
         self._h = C.c_void_p()
         rc = load().kvc_plan(C.byref(self.model), C.byref(self.strategy), max_tokens, max_batch,

@@ -120,3 +120,21 @@ def test_host_errors_before_launch(lib):
     with pytest.raises(kvc.KvcError) as e:
         kvc.compress(plan, [r4], 0x10000, [0, 1 << 20], 0x100, 0x200)
     assert e.value.status == -2                                   # block size not a power of two
+
+
+def test_inspect_accepts_payloads_with_width_tables(ref):
+    """kvc_payload_inspect on oracle payloads whose tensors carry per-head width tables."""
+    import torch
+    from paper_2605_13734_amd import kvgen
+    L, H, T = 2, 3, 50
+    x = kvgen.as_u16(kvgen.make_kv(1, L, H, 128, T, torch.float16))
+    lay = ref.contiguous_layout(H, T, 128)
+    tk = np.array([2, 3, 4, 8, 2, 8], np.uint8)
+    for kw in (dict(head_bits_k=tk, bits_v=4), dict(bits_k=2, head_bits_v=tk), dict(head_bits_k=tk, head_bits_v=tk[::-1])):
+        p = ref.compress(ref.config(layers=L, heads=H, **kw), x[0, 0], x[0, 1], lay, T)
+        rc, model, strat, tokens, total, sec = kvc.payload_inspect(p[:128])
+        assert rc == 0 and tokens == T and total == p.size
+        assert (strat.bits_k == 0) == ("head_bits_k" in kw) and (strat.bits_v == 0) == ("head_bits_v" in kw)
+        bad = p[:128].copy()
+        bad[104] ^= 0x10                                   # K code bytes no longer match the offsets
+        assert kvc.payload_inspect(bad)[0] != 0
