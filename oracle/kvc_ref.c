@@ -107,6 +107,31 @@ void ref_hadamard_row(const uint16_t *in, uint16_t *out, int dim, int dtype, int
     }
 }
 
+/*
+ * The other transform of section 5.1 built here is the delta against an anchor token (the paper
+ * names it and refers to CacheGen for it).  Reading: the tokens of a head are cut into runs of
+ * `anchor_period` consecutive tokens; the first token of a run is its anchor and travels unchanged
+ * (16 bits) beside the codes; every row is replaced by its difference from the anchor row of its
+ * run before the quantizer (an anchor row by zeros), and decompression adds the anchor back to the
+ * reconstructed difference (an anchor row is its stored copy).  A difference or sum is the exact
+ * value rounded once to the tensor type, limited to the type's finite range.  fp32 arithmetic
+ * followed by the rounding to 16 bits gives exactly that: the wider format has more than twice
+ * the digits of the narrow one, so the first rounding cannot change the second.
+ */
+void ref_delta_row(const uint16_t *x, const uint16_t *anchor, uint16_t *out, int dim, int dtype,
+                   int inverse)
+{
+    const float top = dtype == REF_F16 ? 65504.0f : 3.3895313892515355e38f;
+    for (int d = 0; d < dim; ++d) {
+        float a = dtype == REF_F16 ? ref_f16_to_f32(x[d]) : ref_bf16_to_f32(x[d]);
+        float b = dtype == REF_F16 ? ref_f16_to_f32(anchor[d]) : ref_bf16_to_f32(anchor[d]);
+        float y = inverse ? a + b : a - b;
+        if (y > top) y = top;
+        if (y < -top) y = -top;
+        out[d] = dtype == REF_F16 ? ref_f32_to_f16(y) : ref_f32_to_bf16(y);
+    }
+}
+
 static int64_t row_offset(const ref_layout *lay, int l, int h, int64_t t)
 {
     int64_t o = (int64_t)l * lay->stride_layer + (int64_t)h * lay->stride_head;
@@ -399,7 +424,11 @@ int ref_check_config(const ref_config *c)
     if (c->bits_v != 16 && (c->group_v < 1 || c->head_dim % c->group_v)) return REF_ERR_ARG;
     if (c->codec != 0 && c->codec != 1) return REF_ERR_ARG;
     if (c->codec == 1 && (c->bits_k == 16 || c->bits_v == 16)) return REF_ERR_UNSUPPORTED;
-    if (c->transform != 0 && c->transform != 1) return REF_ERR_ARG;
+    if (c->transform < 0 || c->transform > 2) return REF_ERR_ARG;
+    if (c->transform == 2) {
+        int a = c->anchor_period;
+        if (a < 8 || a > 128 || (a & (a - 1))) return REF_ERR_ARG;
+    } else if (c->anchor_period != 0) return REF_ERR_ARG;
     if (c->transform == 1 && ((c->head_dim & (c->head_dim - 1)) || c->head_dim > 1024)) return REF_ERR_UNSUPPORTED;
     return REF_OK;
 }
@@ -410,11 +439,22 @@ typedef struct {
     int64_t meta_k, meta_v, aux, codes_k, codes_v;       /* byte sizes (codes: raw size) */
     int64_t off_meta_k, off_meta_v, off_aux, off_codes_k, off_codes_v, total;
     int64_t chunks_k, chunks_v;
+    int64_t anchors_k, anchors_v, off_anchors_k, off_anchors_v;   /* inside the auxiliary section */
 } geometry;
 
+/* anchor rows one head of a tensor carries (delta transform; a tensor stored unchanged has none) */
+static int64_t anchor_rows(const ref_config *c, int is_v, int64_t T)
+{
+    if (c->transform != 2) return 0;
+    if (!(is_v ? c->head_bits_v : c->head_bits_k) && (is_v ? c->bits_v : c->bits_k) == 16) return 0;
+    return (T + c->anchor_period - 1) / c->anchor_period;
+}
+
 /*
- * Payload = header | K meta | V meta | coder tables and directory | K codes | V codes,
- * every part starting on a 16-byte boundary.  Metadata is two fp16 values per group
+ * Payload = header | K meta | V meta | auxiliary section | K codes | V codes, every part
+ * starting on a 16-byte boundary.  The auxiliary section holds the coder's tables and directory
+ * or the per-head width tables, then (delta transform, from the next 16-byte boundary) the anchor
+ * rows of K and of V, [layer][head][run][channel], 16 bits each.  Metadata is two fp16 values per group
  * (the 32 bits per group behind the paper's 5.33x figure for 2 bits and groups of 32,
  * section 7.3); codes are bits/8 bytes per element.
  */
@@ -431,10 +471,15 @@ static void layout_of(const ref_config *c, int64_t T, geometry *g)
     g->chunks_k = g->chunks_v = LH * ref_chunks_per_head(T);
     g->aux = c->codec ? 512 + 4 * (g->chunks_k + g->chunks_v + 1) : 0;
     g->aux += (c->head_bits_k ? LH : 0) + (c->head_bits_v ? LH : 0);
+    g->anchors_k = 2 * LH * anchor_rows(c, 0, T) * D;
+    g->anchors_v = 2 * LH * anchor_rows(c, 1, T) * D;
+    if (c->transform == 2) g->aux = align16(g->aux) + g->anchors_k + g->anchors_v;
     g->off_meta_k = HEADER;
     g->off_meta_v = g->off_meta_k + align16(g->meta_k);
     g->off_aux = g->off_meta_v + align16(g->meta_v);
     g->off_codes_k = g->off_aux + align16(g->aux);
+    g->off_anchors_k = g->off_codes_k - g->anchors_v - g->anchors_k;
+    g->off_anchors_v = g->off_codes_k - g->anchors_v;
     g->off_codes_v = g->off_codes_k + align16(g->codes_k);
     g->total = g->off_codes_v + align16(g->codes_v);
 }
@@ -472,10 +517,14 @@ int ref_compress_head(const ref_config *c, int is_v, const void *src, const ref_
         /* T first: the quantizer then sees the transformed rows as its input tensor */
         uint16_t *xt = (uint16_t *)malloc((size_t)(T * D) * 2 + 2);
         if (!xt) return REF_ERR_ARG;
-        for (int64_t t = 0; t < T; ++t)
-            ref_hadamard_row((const uint16_t *)src + row_offset(lay, l, h, t), xt + t * D, D, c->dtype, 0);
+        for (int64_t t = 0; t < T; ++t) {
+            const uint16_t *row = (const uint16_t *)src + row_offset(lay, l, h, t);
+            if (c->transform == 1) ref_hadamard_row(row, xt + t * D, D, c->dtype, 0);
+            else ref_delta_row(row, (const uint16_t *)src + row_offset(lay, l, h, t - t % c->anchor_period),
+                               xt + t * D, D, c->dtype, 0);
+        }
         ref_config plain = *c;
-        plain.transform = 0;
+        plain.transform = plain.anchor_period = 0;
         plain.head_bits_k = plain.head_bits_v = NULL;
         plain.bits_k = plain.bits_v = bits;
         ref_layout rows = {0, 0, D, 0, 0, NULL};
@@ -522,7 +571,8 @@ int ref_compress_head(const ref_config *c, int is_v, const void *src, const ref_
 }
 
 int ref_decompress_head(const ref_config *c, int is_v, const uint8_t *codes, const uint16_t *meta,
-                        int64_t T, int l, int h, void *dst, const ref_layout *lay)
+                        const uint16_t *anchors, int64_t T, int l, int h, void *dst,
+                        const ref_layout *lay)
 {
     int D = c->head_dim, bits = bits_at(c, is_v, (int64_t)l * c->heads + h);
     uint16_t *out = (uint16_t *)dst;
@@ -535,14 +585,22 @@ int ref_decompress_head(const ref_config *c, int is_v, const uint8_t *codes, con
         /* reconstruct the transformed rows, then undo T row by row */
         uint16_t *xt = (uint16_t *)malloc((size_t)(T * D) * 2 + 2);
         if (!xt) return REF_ERR_ARG;
+        if (c->transform == 2 && !anchors && T > 0) { free(xt); return REF_ERR_ARG; }
         ref_config plain = *c;
-        plain.transform = 0;
+        plain.transform = plain.anchor_period = 0;
         plain.head_bits_k = plain.head_bits_v = NULL;
         plain.bits_k = plain.bits_v = bits;
         ref_layout rows = {0, 0, D, 0, 0, NULL};
-        int rc = ref_decompress_head(&plain, is_v, codes, meta, T, 0, 0, xt, &rows);
-        for (int64_t t = 0; t < T && rc == REF_OK; ++t)
-            ref_hadamard_row(xt + t * D, out + row_offset(lay, l, h, t), D, c->dtype, 1);
+        int rc = ref_decompress_head(&plain, is_v, codes, meta, NULL, T, 0, 0, xt, &rows);
+        for (int64_t t = 0; t < T && rc == REF_OK; ++t) {
+            uint16_t *row = out + row_offset(lay, l, h, t);
+            if (c->transform == 1) ref_hadamard_row(xt + t * D, row, D, c->dtype, 1);
+            else {
+                const uint16_t *anchor = anchors + (t / c->anchor_period) * D;
+                if (t % c->anchor_period == 0) memcpy(row, anchor, (size_t)D * 2);
+                else ref_delta_row(xt + t * D, anchor, row, D, c->dtype, 1);
+            }
+        }
         free(xt);
         return rc;
     }
@@ -664,7 +722,8 @@ static uint64_t get_u64(const uint8_t *p) { uint64_t v = 0; for (int i = 0; i < 
  * Header, 128 bytes, little endian:
  *   0 "KVC1" | 4 u16 version=1 | 6 u8 dtype | 7 u8 codec | 8 i32 layers | 12 i32 heads |
  *   16 i32 head_dim | 20 u8 bits_k | 21 u8 bits_v | 22 u16 group_k | 24 u16 group_v |
- *   26..31 zero | 32 i64 tokens | 40 u64 total bytes |
+ *   26 u8 transform | 27 u8 width-table flags | 28 u16 anchor period | 30..31 zero |
+ *   32 i64 tokens | 40 u64 total bytes |
  *   48.. five (offset u64, bytes u64) pairs: K meta, V meta, coder aux, K codes, V codes
  */
 static void write_header(uint8_t *p, const ref_config *c, int64_t T, const geometry *g,
@@ -684,6 +743,7 @@ static void write_header(uint8_t *p, const ref_config *c, int64_t T, const geome
     put_u16(p + 24, (unsigned)c->group_v);
     p[26] = (uint8_t)c->transform;
     p[27] = (uint8_t)((c->head_bits_k ? 1 : 0) | (c->head_bits_v ? 2 : 0));
+    put_u16(p + 28, (unsigned)c->anchor_period);
     put_u64(p + 32, (uint64_t)T);
     put_u64(p + 40, (uint64_t)total);
     put_u64(p + 48, (uint64_t)g->off_meta_k);  put_u64(p + 56, (uint64_t)g->meta_k);
@@ -710,6 +770,8 @@ int ref_inspect(const uint8_t *p, ref_config *c, int64_t *tokens, uint64_t *tota
     c->group_k = (int32_t)get_u16(p + 22);
     c->group_v = (int32_t)get_u16(p + 24);
     c->transform = p[26];
+    c->anchor_period = (int32_t)get_u16(p + 28);
+    if (p[30] | p[31]) return REF_ERR_FORMAT;
     /* per-head tables sit at the start of the auxiliary section: the pointers are only valid
      * when `p` is the whole payload, not just its header */
     {
@@ -742,6 +804,17 @@ int ref_compress(const ref_config *c, const void *k, const void *v, const ref_la
     layout_of(c, T, &g);
     if (capacity < (uint64_t)g.total) return REF_ERR_CAPACITY;
     memset(payload, 0, (size_t)g.total);
+
+    /* delta transform: the anchor rows travel as they are */
+    for (int is_v = 0; is_v < 2; ++is_v) {
+        int64_t n = anchor_rows(c, is_v, T);
+        uint16_t *dst = (uint16_t *)(payload + (is_v ? g.off_anchors_v : g.off_anchors_k));
+        for (int l = 0; l < c->layers; ++l)
+            for (int h = 0; h < c->heads; ++h)
+                for (int64_t r = 0; r < n; ++r, dst += c->head_dim)
+                    memcpy(dst, (const uint16_t *)(is_v ? v : k) + row_offset(lay, l, h, r * c->anchor_period),
+                           (size_t)c->head_dim * 2);
+    }
 
     /* Q: quantize and pack both tensors, head by head */
     uint8_t *codes[2];
@@ -873,8 +946,10 @@ int ref_decompress(const uint8_t *payload, uint64_t bytes, void *k, void *v,
                     }
                     codes = head;
                 }
-                rc = ref_decompress_head(&c, is_v, codes, (const uint16_t *)(mbase + lh * hm), T,
-                                         l, h, is_v ? v : k, lay);
+                const uint16_t *anchors = (const uint16_t *)(payload + (is_v ? g.off_anchors_v : g.off_anchors_k)) +
+                                          lh * anchor_rows(&c, is_v, T) * c.head_dim;
+                rc = ref_decompress_head(&c, is_v, codes, (const uint16_t *)(mbase + lh * hm), anchors,
+                                         T, l, h, is_v ? v : k, lay);
                 if (rc) { free(head); return rc; }
             }
         free(head);

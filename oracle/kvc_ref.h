@@ -21,7 +21,9 @@
  * max -> top code; constant group exact; offset invariance (asymmetry); identity at
  * 16 bits; exhaustive pack/unpack; hand-written packed byte strings; K/V transpose
  * duality; paged == contiguous; Kraft equality, length limit, entropy bound and
- * round trip for the coder; number-format conversions against numpy.
+ * round trip for the coder; number-format conversions against numpy; the transforms against
+ * their float64 definitions (matrix product; exact difference rounded once) and against
+ * transform-free payloads of tensors transformed beforehand.
  * Parity unpinned by the paper itself: the exact operation order of the quantizer
  * (two rounded fp32 operations), the tie rule, the payload byte layout and the
  * choice of entropy coder.  They are pinned only by the invariants above.
@@ -48,7 +50,9 @@ typedef struct {
     int32_t group_k;            /* tokens per K group (one group per channel) */
     int32_t group_v;            /* channels per V group (one group per token) */
     int32_t codec;              /* 0 none, 1 huff8 */
-    int32_t transform;          /* 0 none, 1 Walsh-Hadamard over head_dim (ref_hadamard_row) */
+    int32_t transform;          /* 0 none, 1 Walsh-Hadamard over head_dim (ref_hadamard_row),
+                                   2 delta against an anchor token (ref_delta_row) */
+    int32_t anchor_period;      /* transform 2: tokens per run, a power of two in 8..128; else 0 */
     /* optional per-head bit widths, index l*heads + h, values 2, 3, 4 or 8; when a table is
      * given the uniform width of that tensor (bits_k / bits_v) must be 0.  Not with codec 1. */
     const uint8_t *head_bits_k, *head_bits_v;
@@ -73,6 +77,8 @@ uint16_t ref_f32_to_bf16(float f);
 
 /* transform T: one head_dim-long row of 16-bit values -> the same, see kvc_ref.c */
 void     ref_hadamard_row(const uint16_t *in, uint16_t *out, int dim, int dtype, int inverse);
+void     ref_delta_row(const uint16_t *x, const uint16_t *anchor, uint16_t *out, int dim, int dtype,
+                       int inverse);
 
 /* quantizer on one group held as floats */
 void     ref_group_meta(const float *x, int n, int bits, uint16_t *scale_h, uint16_t *zero_h);
@@ -103,8 +109,11 @@ int     ref_payload_size(const ref_config *c, int64_t tokens, uint64_t *bytes, i
  *        each pair = scale (fp16 bits) then zero (fp16 bits)                             */
 int ref_compress_head(const ref_config *c, int is_v, const void *src, const ref_layout *lay,
                       int64_t tokens, int l, int h, uint8_t *codes, uint16_t *meta);
+/* anchors (delta transform only, else NULL): this head's anchor rows,
+ * [ceil(tokens/anchor_period)][head_dim] */
 int ref_decompress_head(const ref_config *c, int is_v, const uint8_t *codes, const uint16_t *meta,
-                        int64_t tokens, int l, int h, void *dst, const ref_layout *lay);
+                        const uint16_t *anchors, int64_t tokens, int l, int h, void *dst,
+                        const ref_layout *lay);
 
 /* code-length tables of the two sections (codec 1), from the deterministic sample */
 int ref_huff_tables(const ref_config *c, const void *k, const void *v, const ref_layout *lay,

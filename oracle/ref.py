@@ -29,7 +29,8 @@ class Config(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("layers", C.c_int32), ("heads", C.c_int32),
                 ("head_dim", C.c_int32), ("bits_k", C.c_int32), ("bits_v", C.c_int32),
                 ("group_k", C.c_int32), ("group_v", C.c_int32), ("codec", C.c_int32),
-                ("transform", C.c_int32), ("head_bits_k", C.c_void_p), ("head_bits_v", C.c_void_p)]
+                ("transform", C.c_int32), ("anchor_period", C.c_int32),
+                ("head_bits_k", C.c_void_p), ("head_bits_v", C.c_void_p)]
 
 
 class Layout(C.Structure):
@@ -68,8 +69,8 @@ def _p(a):
 
 
 def config(dtype=F16, layers=1, heads=1, head_dim=128, bits_k=4, bits_v=4, group_k=32, group_v=32,
-           codec=0, transform=0, head_bits_k=None, head_bits_v=None):
-    """head_bits_k / head_bits_v: optional uint8 arrays of layers*heads widths (the uniform width of
+           codec=0, transform=0, head_bits_k=None, head_bits_v=None, anchor_period=0):
+    """transform 2 (delta against an anchor token) needs anchor_period.  head_bits_k / head_bits_v: optional uint8 arrays of layers*heads widths (the uniform width of
     that tensor is then 0); the arrays are kept alive by the returned object."""
     keep = []
     ptrs = []
@@ -82,7 +83,8 @@ def config(dtype=F16, layers=1, heads=1, head_dim=128, bits_k=4, bits_v=4, group
             keep.append(a)
             ptrs.append(a.ctypes.data)
     cfg = Config(dtype, layers, heads, head_dim, 0 if head_bits_k is not None else bits_k,
-                 0 if head_bits_v is not None else bits_v, group_k, group_v, codec, transform, ptrs[0], ptrs[1])
+                 0 if head_bits_v is not None else bits_v, group_k, group_v, codec, transform, anchor_period,
+                 ptrs[0], ptrs[1])
     cfg._keep = keep
     return cfg
 
@@ -162,6 +164,17 @@ def hadamard_row(row_u16, dtype=F16, inverse=False):
     return out
 
 
+def delta_row(row_u16, anchor_u16, dtype=F16, inverse=False):
+    """ref_delta_row: row - anchor (or row + anchor), rounded to the type, on 16-bit patterns."""
+    row = np.ascontiguousarray(row_u16, dtype=np.uint16)
+    anchor = np.ascontiguousarray(anchor_u16, dtype=np.uint16)
+    assert row.size == anchor.size
+    out = np.empty_like(row)
+    lib().ref_delta_row(_p(row), _p(anchor), _p(out), C.c_int(row.size), C.c_int(dtype),
+                        C.c_int(1 if inverse else 0))
+    return out
+
+
 def huff_lengths(hist):
     hist = np.ascontiguousarray(hist, dtype=np.uint32)
     assert hist.size == 256
@@ -227,11 +240,14 @@ def compress_head(cfg, is_v, src, lay, tokens, l, h):
     return codes, meta
 
 
-def decompress_head(cfg, is_v, codes, meta, tokens, l, h, dst, lay):
+def decompress_head(cfg, is_v, codes, meta, tokens, l, h, dst, lay, anchors=None):
+    """anchors: this head's anchor rows (uint16, [runs][head_dim]) when cfg.transform == 2."""
     codes = np.ascontiguousarray(codes, dtype=np.uint8)
     meta = np.ascontiguousarray(meta, dtype=np.uint16)
+    if anchors is not None:
+        anchors = np.ascontiguousarray(anchors, dtype=np.uint16)
     rc = lib().ref_decompress_head(C.byref(cfg), C.c_int(is_v), _p(codes), _p(meta),
-                                   C.c_int64(tokens), C.c_int(l), C.c_int(h), _p(dst), C.byref(lay))
+                                   _p(anchors) if anchors is not None else None, C.c_int64(tokens), C.c_int(l), C.c_int(h), _p(dst), C.byref(lay))
     if rc:
         raise ValueError("ref_decompress_head: %d" % rc)
 
