@@ -22,11 +22,14 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 WORKLOADS = {
-    # name: (layers, heads, tokens, dtype, bits_k, bits_v, group_k, group_v, codec[, transform])
+    # name: (layers, heads, tokens, dtype, bits_k, bits_v, group_k, group_v, codec[, transform[, widths]])
+    # transform: 0 none, 1 Hadamard, (2, anchor period) delta
     "llama70b_32k_fp16_int4g32_huff8": (80, 8, 32768, "f16", 4, 4, 32, 32, 1),
     "llama70b_32k_fp16_int4g32": (80, 8, 32768, "f16", 4, 4, 32, 32, 0),
     "llama70b_32k_fp16_hadamard_int4g32_huff8": (80, 8, 32768, "f16", 4, 4, 32, 32, 1, 1),
     "llama70b_32k_fp16_hadamard_int4g32": (80, 8, 32768, "f16", 4, 4, 32, 32, 0, 1),
+    "llama70b_32k_fp16_delta32_int4g32_huff8": (80, 8, 32768, "f16", 4, 4, 32, 32, 1, (2, 32)),
+    "llama70b_32k_fp16_delta32_int4g32": (80, 8, 32768, "f16", 4, 4, 32, 32, 0, (2, 32)),
     # per-head widths: a seeded random half of the heads at 8 bits, the other half at 2 (the paper's
     # MixHQ takes the split from trained head masks, which are not available here)
     "llama70b_32k_fp16_mixhq_8_2_g32": (80, 8, 32768, "f16", 4, 4, 32, 32, 0, 0, (8, 2)),
@@ -37,7 +40,7 @@ WORKLOADS = {
 
 
 def cpu_baseline(x_dev, layers, heads, tokens, dt, bits_k, bits_v, gk, gv, codec, transform, sample_layers,
-                 head_bits=None):
+                 head_bits=None, anchor_period=0):
     """The oracle as it stands, single-threaded, on the first `sample_layers` layers."""
     import numpy as np
     from oracle import ref
@@ -45,7 +48,7 @@ def cpu_baseline(x_dev, layers, heads, tokens, dt, bits_k, bits_v, gk, gv, codec
     xs = x_dev[:sample_layers].cpu()
     xu = kvgen.as_u16(xs)
     cfg = ref.config(dtype=dt, layers=sample_layers, heads=heads, bits_k=bits_k, bits_v=bits_v,
-                     group_k=gk, group_v=gv, codec=codec, transform=transform,
+                     group_k=gk, group_v=gv, codec=codec, transform=transform, anchor_period=anchor_period,
                      head_bits_k=head_bits[0][:sample_layers * heads] if head_bits else None,
                      head_bits_v=head_bits[1][:sample_layers * heads] if head_bits else None)
     lay = ref.contiguous_layout(heads, tokens, 128)
@@ -144,6 +147,7 @@ def main():
 
     L, H, T, dtn, bk, bv, gk, gv, codec = WORKLOADS[args.workload][:9]
     transform = WORKLOADS[args.workload][9] if len(WORKLOADS[args.workload]) > 9 else 0
+    transform, anchor_period = transform if isinstance(transform, tuple) else (transform, 0)
     mix = WORKLOADS[args.workload][10] if len(WORKLOADS[args.workload]) > 10 else None
     head_bits = None
     if mix:
@@ -154,7 +158,7 @@ def main():
     dev = "cuda:0"
     x = kvgen.make_kv(0, L, H, 128, T, dtype, dev)
     y = torch.empty_like(x)
-    plan = kvc.Plan(dt, L, H, 128, bk, bv, gk, gv, codec, max_tokens=T, transform=transform,
+    plan = kvc.Plan(dt, L, H, 128, bk, bv, gk, gv, codec, max_tokens=T, transform=transform, anchor_period=anchor_period,
                     head_bits_k=head_bits[0] if mix else None, head_bits_v=head_bits[1] if mix else None)
     buf = kvc.Buffers(plan, [T], dev)
     src, dst = [kvc.contiguous_request(x)], [kvc.contiguous_request(y)]
@@ -217,7 +221,10 @@ def main():
     assert rc == 0 and total == payload_bytes
     n_half = x.numel() // 2
     chunks = L * H * -(-T // 128) if codec else 0
-    alg = {"k": 2 * n_half + sec[7] + sec[1] + 4 * chunks, "v": 2 * n_half + sec[9] + sec[3] + 4 * chunks}
+    # (delta transform: plus the anchor rows, 16 bits per element, written or read once)
+    anchors = 2 * L * H * -(-T // anchor_period) * 128 if anchor_period else 0
+    alg = {"k": 2 * n_half + sec[7] + sec[1] + 4 * chunks + (anchors if bk != 16 else 0),
+           "v": 2 * n_half + sec[9] + sec[3] + 4 * chunks + (anchors if bv != 16 else 0)}
     kernels = {
         "compress_k": (t_enc_k, alg["k"]), "compress_v": (t_enc_v, alg["v"]),
         "decompress_k": (t_dec_k, alg["k"]), "decompress_v": (t_dec_v, alg["v"]),
@@ -254,7 +261,7 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "layers": L, "kv_heads": H, "head_dim": 128, "tokens": T,
                    "kv_dtype": dtn, "bits_k": bk, "bits_v": bv, "group_k": gk, "group_v": gv,
-                   "codec": "huff8" if codec else "none", "transform": "hadamard" if transform else "none",
+                   "codec": "huff8" if codec else "none", "transform": ("none", "hadamard", "delta%d" % anchor_period)[transform],
                    "kv_bytes": V, "payload_bytes": payload_bytes},
         "s_enc_GBps": round(s_enc, 1), "s_dec_GBps": round(s_dec, 1), "cr": round(cr, 4),
         "break_even_bandwidth_GBps": round((1 - 1 / cr) * s_p, 1),
@@ -269,7 +276,7 @@ def main():
         out["policy"] = policy_table(x, y, dt, L, H, T, max(2, args.steps // 3))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(x, L, H, T, dt, bk, bv, gk, gv, codec, transform,
-                                           min(args.cpu_sample_layers, L), head_bits)
+                                           min(args.cpu_sample_layers, L), head_bits, anchor_period)
     print(json.dumps(out))
     return 0
 

@@ -64,8 +64,17 @@ enum { KVC_CODEC_NONE = 0, KVC_CODEC_HUFF8 = 1 };
  *                     is replaced by H x / 8 before the quantizer and decompression applies
  *                     H x / 16 to the reconstructed row (H = Walsh-Hadamard matrix of order 128
  *                     in natural order; fp32 butterflies with strides 1, 2, ..., 64; results
- *                     rounded to the tensor type); a tensor stored unchanged (16 bits) is not
- *                     transformed
+ *                     rounded to the tensor type); KVC_T_DELTA = the difference from an anchor
+ *                     token (named in section 5.1 with a reference to CacheGen): the tokens of a
+ *                     head form runs of anchor_period tokens, the first token of a run is its
+ *                     anchor and travels unchanged (16 bits per element) in the payload's
+ *                     auxiliary section, after the coder's tables or the width tables, K anchors
+ *                     then V anchors; every row is quantized as row - anchor row of its run and
+ *                     decompression returns reconstructed difference + anchor (an anchor row is
+ *                     its stored copy); a difference or sum is the exact value rounded once to
+ *                     the tensor type and limited to its finite range.  A tensor stored unchanged
+ *                     (16 bits) is not transformed by either
+ *   anchor_period   : KVC_T_DELTA only: 8, 16, 32, 64 or 128 tokens; 0 otherwise
  *   head_bits_k/v   : optional per-head bit widths (section 5.1: mixed precision at head
  *                     granularity; the mechanism behind MixHQ, which keeps the heads that matter
  *                     at a high precision and gives the others very few bits).  HOST arrays of
@@ -81,11 +90,13 @@ enum { KVC_CODEC_NONE = 0, KVC_CODEC_HUFF8 = 1 };
  */
 #define KVC_T_NONE 0
 #define KVC_T_HADAMARD 1
+#define KVC_T_DELTA 2
 
 typedef struct {
     uint8_t bits_k, bits_v;
     uint16_t group_k, group_v;
     uint8_t codec, transform;
+    uint16_t anchor_period;
     const uint8_t *head_bits_k, *head_bits_v;
 } kvc_strategy;
 
@@ -132,7 +143,9 @@ void kvc_plan_free(kvc_plan_t *plan);
  * Payload bytes of a request of `tokens` tokens: V_p of section 3.1.  Without the codec
  * the value is exact (*is_exact = 1):
  *   128 + a16(4*L*H*ceil(T/group_k)*D) + a16(4*L*H*T*D/group_v)
- *       + a16(L*H*T*D*bits_k/8) + a16(L*H*T*D*bits_v/8),      a16 = round up to 16;
+ *       + a16(L*H*T*D*bits_k/8) + a16(L*H*T*D*bits_v/8),      a16 = round up to 16
+ * (plus the auxiliary section: L*H bytes per width table, and with KVC_T_DELTA
+ * 2*L*H*ceil(T/anchor_period)*D bytes of anchor rows per transformed tensor);
  * with it, the value is the capacity the caller must provide (every chunk stored raw,
  * plus tables and directory) and the true size is reported by kvc_compress.
  */

@@ -819,7 +819,7 @@ int ref_compress(const ref_config *c, const void *k, const void *v, const ref_la
     /* Q: quantize and pack both tensors, head by head */
     uint8_t *codes[2];
     for (int is_v = 0; is_v < 2; ++is_v) {
-        int64_t hb = head_code_bytes(c, is_v, T), hm = head_meta_pairs(c, is_v, T) * 4;
+        int64_t hm = head_meta_pairs(c, is_v, T) * 4;
         uint8_t *cbase = c->codec ? (uint8_t *)malloc((size_t)(is_v ? g.codes_v : g.codes_k) + 1)
                                   : payload + (is_v ? g.off_codes_v : g.off_codes_k);
         if (!cbase) return REF_ERR_ARG;

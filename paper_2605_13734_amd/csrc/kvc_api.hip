@@ -82,8 +82,17 @@ static bool group_ok(int g) { return g == 32 || g == 64 || g == 128; }
 
 static long long chunks_per_head(long long tokens) { return (tokens + kChunkRows - 1) / kChunkRows; }
 
-// Payload = header | K meta | V meta | coder tables + directory | K codes | V codes, each
-// part on a 16-byte boundary; two fp16 values of metadata per group (section 7.3).
+// Payload = header | K meta | V meta | auxiliary section | K codes | V codes, each part on a
+// 16-byte boundary; two fp16 values of metadata per group (section 7.3).  The auxiliary section
+// holds the coder's tables and directory or the per-head width tables, then (delta transform, from
+// the next 16-byte boundary) the anchor rows of K and of V, 16 bits per element.
+static long long anchor_rows(const kvc_plan_t *p, int is_v, long long T)
+{
+    if (p->strat.transform != KVC_T_DELTA) return 0;
+    if (!p->has_table[is_v] && (is_v ? p->strat.bits_v : p->strat.bits_k) == 16) return 0;
+    return (T + p->strat.anchor_period - 1) / p->strat.anchor_period;
+}
+
 static void geometry(const kvc_plan_t *p, long long T, Geometry *g)
 {
     const long long LH = (long long)p->model.layers * p->model.kv_heads, D = p->model.head_dim;
@@ -104,10 +113,16 @@ static void geometry(const kvc_plan_t *p, long long T, Geometry *g)
     g->chunks_k = g->chunks_v = LH * chunks_per_head(T);
     g->aux = p->strat.codec ? 512 + 4 * (g->chunks_k + g->chunks_v + 1) : 0;
     g->aux += (p->has_table[0] + p->has_table[1]) * LH;
+    g->aux_base = g->aux;
+    g->anchors_k = 2 * LH * anchor_rows(p, 0, T) * D;
+    g->anchors_v = 2 * LH * anchor_rows(p, 1, T) * D;
+    if (p->strat.transform == KVC_T_DELTA) g->aux = a16(g->aux_base) + g->anchors_k + g->anchors_v;
     g->off_meta_k = kHeader;
     g->off_meta_v = g->off_meta_k + a16(g->meta_k);
     g->off_aux = g->off_meta_v + a16(g->meta_v);
     g->off_codes_k = g->off_aux + a16(g->aux);
+    g->off_anchors_k = g->off_codes_k - g->anchors_v - g->anchors_k;
+    g->off_anchors_v = g->off_codes_k - g->anchors_v;
     g->off_codes_v = g->off_codes_k + a16(g->codes_k);
     g->total = g->off_codes_v + a16(g->codes_v);
 }
@@ -138,6 +153,7 @@ static void make_header(const kvc_plan_t *p, long long T, const Geometry &g, Hea
     put16(h + 24, p->strat.group_v);
     h[26] = p->strat.transform;
     h[27] = (uint8_t)(p->has_table[0] | (p->has_table[1] << 1));
+    put16(h + 28, p->strat.anchor_period);
     put64(h + 32, (uint64_t)T);
     put64(h + 48, (uint64_t)g.off_meta_k); put64(h + 56, (uint64_t)g.meta_k);
     put64(h + 64, (uint64_t)g.off_meta_v); put64(h + 72, (uint64_t)g.meta_v);
@@ -184,7 +200,11 @@ static int check_pair(const kvc_model *m, const kvc_strategy *s)
             if (t[i] != 2 && t[i] != 3 && t[i] != 4 && t[i] != 8) return KVC_ERR_ARG;
     }
     if (m->head_dim != kDim) return KVC_ERR_UNSUPPORTED;
-    if (s->transform > KVC_T_HADAMARD) return KVC_ERR_UNSUPPORTED;
+    if (s->transform > KVC_T_DELTA) return KVC_ERR_UNSUPPORTED;
+    if (s->transform == KVC_T_DELTA) {
+        const int a = s->anchor_period;
+        if (a < 8 || a > 128 || (a & (a - 1))) return KVC_ERR_ARG;
+    } else if (s->anchor_period != 0) return KVC_ERR_ARG;
     if (s->codec && (s->head_bits_k || s->head_bits_v)) return KVC_ERR_UNSUPPORTED;
     if (s->codec && (s->bits_k == 16 || s->bits_v == 16)) return KVC_ERR_UNSUPPORTED;
     return KVC_OK;
@@ -284,6 +304,7 @@ extern "C" int kvc_payload_inspect(const void *header128, kvc_model *model, kvc_
     s.group_k = (uint16_t)get16(h + 22);
     s.group_v = (uint16_t)get16(h + 24);
     s.transform = h[26];
+    s.anchor_period = (uint16_t)get16(h + 28);
     const int64_t T = (int64_t)get64(h + 32);
     // a tensor with a per-head width table has width 0 in the header; the table itself is in the
     // auxiliary section, which this function does not see
@@ -295,8 +316,7 @@ extern "C" int kvc_payload_inspect(const void *header128, kvc_model *model, kvc_
     int rc = check_pair(&m, &probe);
     if (rc == KVC_ERR_ARG || T < 0) return KVC_ERR_FORMAT;
     if (flags && s.codec) return KVC_ERR_FORMAT;
-    for (int i = 28; i < 32; ++i)
-        if (h[i]) return KVC_ERR_FORMAT;
+    if (h[30] | h[31]) return KVC_ERR_FORMAT;
     // the fixed part of the section table must be the closed form of the fields above
     kvc_plan_t tmp;
     memset(&tmp, 0, sizeof tmp);
@@ -398,6 +418,10 @@ static QuantArgs quant_args(const kvc_plan_t *p, const kvc_request *r, int is_v,
     a.group = group;
     a.dense = (!r->block_table && r->stride_token == kDim) ? 1 : 0;
     a.rotate = (p->strat.transform == KVC_T_HADAMARD && bits != 16) ? 1 : 0;
+    if (anchor_rows(p, is_v, r->tokens) > 0) {
+        a.anchors = (uint16_t *)(payload + (is_v ? g.off_anchors_v : g.off_anchors_k));
+        while ((1 << a.anchor_shift) < p->strat.anchor_period) ++a.anchor_shift;
+    }
     const long long rows_per_unit = (compress && !is_v && bits != 16) ? group : kPassRows;
     a.units_per_head = (r->tokens + rows_per_unit - 1) / rows_per_unit;
     a.total_units = a.units_per_head * p->model.layers * p->model.kv_heads;
@@ -513,10 +537,10 @@ extern "C" int kvc_compress(const kvc_plan_t *plan, const kvc_request *reqs, int
             KVC_TRY(launch_fill_u32((uint32_t *)(pl + g.off_meta_v + g.meta_v), 0, (a16(g.meta_v) - g.meta_v) / 4, s));
         if (plan->blob_bytes) {
             // the width tables and their padding: a device copy of the image at the start of the workspace
-            if (hipMemcpyAsync(pl + g.off_aux, workspace, (size_t)a16(g.aux), hipMemcpyDeviceToDevice, s) != hipSuccess)
+            if (hipMemcpyAsync(pl + g.off_aux, workspace, (size_t)a16(g.aux_base), hipMemcpyDeviceToDevice, s) != hipSuccess)
                 return KVC_ERR_DEVICE;
-        } else if (a16(g.aux) != g.aux)
-            KVC_TRY(launch_fill_u32((uint32_t *)(pl + g.off_aux + g.aux), 0, (a16(g.aux) - g.aux) / 4, s));
+        } else if (a16(g.aux_base) != g.aux_base)
+            KVC_TRY(launch_fill_u32((uint32_t *)(pl + g.off_aux + g.aux_base), 0, (a16(g.aux_base) - g.aux_base) / 4, s));
         QuantArgs qk = quant_args(plan, r, 0, pl, g, dev_status + i, true);
         QuantArgs qv = quant_args(plan, r, 1, pl, g, dev_status + i, true);
         if (!st.codec) {
@@ -585,7 +609,7 @@ extern "C" int kvc_decompress(const kvc_plan_t *plan, const void *payload, const
         const uint32_t mask = st.codec ? 0x03fff3ffu : 0xffffffffu;
         KVC_TRY(launch_check_header(pl, hb, mask, dev_status + i, s));
         if (plan->blob_bytes)       // the payload's width tables must be the plan's
-            KVC_TRY(launch_check_bytes(pl + g.off_aux, (const uint8_t *)workspace, g.aux, dev_status + i, s));
+            KVC_TRY(launch_check_bytes(pl + g.off_aux, (const uint8_t *)workspace, g.aux_base, dev_status + i, s));
         QuantArgs qk = quant_args(plan, r, 0, pl, g, dev_status + i, false);
         QuantArgs qv = quant_args(plan, r, 1, pl, g, dev_status + i, false);
         if (!st.codec) {

@@ -120,6 +120,9 @@ __device__ __forceinline__ void quantize_chunk(const QuantArgs &a, const ChunkPo
 #pragma unroll
         for (int p = 0; p < PU; ++p) load_pass<DENSE>(a.x, c.head_off, row0 + p * kPassRows, a.tokens, raw + p * 8, bad);
         if (a.rotate) rotate_rows<DT, PU * 8>(raw);
+        if (a.anchors)
+            delta_rows<DT, DENSE, PU * 8>(a.x, c.head_off, row0, a.tokens, a.anchor_shift,
+                                          head_anchors(a.anchors, c.lh, a.tokens, a.anchor_shift), write_meta, raw, bad);
         if (!IS_V) {
             const long long nb = (a.tokens + G - 1) / G;
             KParams kp;
@@ -729,6 +732,32 @@ __device__ __forceinline__ void load_meta_v(const QuantArgs &q, const ChunkPos &
     }
 }
 
+// Dequantize a decoded chunk from the wave's LDS region and store its rows; the metadata of a
+// pass is in flight one pass ahead.  meta0 / meta1 (K) or metav (V): the first pass's metadata.
+template <int BITS, int DT, bool IS_V, bool DENSE, int TR>
+__device__ __forceinline__ void dequant_chunk(const CoderArgs &a, const ChunkPos &c, uint8_t *lds, const u32x4 &meta0,
+                                              const u32x4 &meta1, const uint32_t metav[8], bool &bad)
+{
+    using Dec = DecGeom<BITS>;
+    const uint16_t *anchors = TR == 2 ? head_anchors(a.q.anchors, c.lh, a.q.tokens, a.q.anchor_shift) : nullptr;
+    u32x4 mk0 = meta0, mk1 = meta1;
+    uint32_t mv[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) mv[i] = metav[i];
+#pragma unroll 1
+    for (int p = 0; p < kChunkRows / kPassRows; ++p) {
+        if (p * kPassRows >= c.rows) break;
+        float scale[8], zero[8];
+        const bool clamp = IS_V ? v_meta_floats<BITS, DT>(mv, scale, zero) : k_meta_floats<BITS, DT>(mk0, mk1, scale, zero);
+        if ((p + 1) * kPassRows < c.rows) {
+            if (!IS_V) load_meta_k(a.q, c, (p + 1) * kPassRows, mk0, mk1);
+            else load_meta_v(a.q, c, (p + 1) * kPassRows, mv);
+        }
+        dequant_pass<BITS, DT, IS_V, DENSE, Dec::kLayout, TR>(lds, scale, zero, clamp, a.q.x, c.head_off, c.row0 + p * kPassRows,
+                                                              c.rows - p * kPassRows, bad, p * kPassRows, anchors, a.q.anchor_shift);
+    }
+}
+
 template <int BITS, int DT, bool IS_V, bool DENSE>
 __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel(CoderArgs a)
 {
@@ -743,6 +772,15 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
     const bool live = chunk < a.chunks;
     uint8_t *lds = lds_all + wave * Dec::kLds;
     PHASE_START();
+    // Register headroom.  A build of this kernel that needed exactly 112 VGPRs, and kept the
+    // length of the last-but-two symbol in v111, the last register of its allocation, decoded
+    // the last two symbols of a sub-block wrongly in about one wave of seven once four such waves
+    // shared a SIMD: the 64-bit shift that took v111 as its count shifted by the lane number
+    // instead (what a read past the allocation returns: the content of v0).  The same
+    // instructions with 120 registers allocated, or with two workgroups per CU, never did.  The
+    // cause is not understood; naming a higher register here keeps the allocation (128, still
+    // four waves per SIMD) above every register the code touches.
+    asm volatile("" ::: "v127");
 
     // Round trip 1: the chunk's two directory entries and the status word, with the decode
     // table right behind them.
@@ -849,24 +887,11 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
         PHASE(1, 2);
     }
 
-    // dequantize the rows from LDS; the metadata of a pass is in flight one pass ahead
+    // dequantize the rows from LDS (one copy of the loop per transform; a launch runs one of them)
     bool bad = false;
-    u32x4 mk0 = meta0, mk1 = meta1;
-    uint32_t mv[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) mv[i] = metav[i];
-#pragma unroll 1
-    for (int p = 0; p < kChunkRows / kPassRows; ++p) {
-        if (p * kPassRows >= c.rows) break;
-        float scale[8], zero[8];
-        const bool clamp = IS_V ? v_meta_floats<BITS, DT>(mv, scale, zero) : k_meta_floats<BITS, DT>(mk0, mk1, scale, zero);
-        if ((p + 1) * kPassRows < c.rows) {
-            if (!IS_V) load_meta_k(a.q, c, (p + 1) * kPassRows, mk0, mk1);
-            else load_meta_v(a.q, c, (p + 1) * kPassRows, mv);
-        }
-        dequant_pass<BITS, DT, IS_V, DENSE, Dec::kLayout>(lds, scale, zero, clamp, a.q.x, c.head_off, c.row0 + p * kPassRows,
-                                                          c.rows - p * kPassRows, bad, p * kPassRows, a.q.rotate != 0);
-    }
+    if (a.q.rotate) dequant_chunk<BITS, DT, IS_V, DENSE, 1>(a, c, lds, meta0, meta1, metav, bad);
+    else if (a.q.anchors) dequant_chunk<BITS, DT, IS_V, DENSE, 2>(a, c, lds, meta0, meta1, metav, bad);
+    else dequant_chunk<BITS, DT, IS_V, DENSE, 0>(a, c, lds, meta0, meta1, metav, bad);
     if (bad) atomicOr(a.q.status, KVC_DEV_BAD_BLOCK);
     PHASE(1, 3);
     PHASE_END(1);

@@ -18,6 +18,10 @@ struct QuantArgs {
     int group;                  // runtime copy of the group size
     int dense;                  // rows of a head are contiguous: stride_token == head_dim, no block table
     int rotate;                 // stage T: rows are Hadamard-transformed on the way in / back on the way out
+    // stage T, delta transform: the tensor's anchor rows inside the payload,
+    // [layer * heads + head][ceil(tokens / period)][128] (null = transform off), period = 1 << anchor_shift
+    uint16_t *anchors;
+    int anchor_shift;
     // per-head bit widths (null = one width for all heads): the heads this launch covers, and for
     // every head the sum of the widths of the heads before it (its codes start at that many times
     // tokens * 16 bytes into the section)
@@ -31,6 +35,8 @@ struct QuantArgs {
 // Geometry of one payload (all byte counts), shared by host code of compress / decompress.
 struct Geometry {
     long long meta_k, meta_v, aux, codes_k, codes_v;
+    long long aux_base;          // tables / directory part of the auxiliary section (before the anchors)
+    long long anchors_k, anchors_v, off_anchors_k, off_anchors_v;
     long long off_meta_k, off_meta_v, off_aux, off_codes_k, off_codes_v, total;
     long long chunks_k, chunks_v;
 };

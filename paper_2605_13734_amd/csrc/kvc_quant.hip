@@ -56,6 +56,9 @@ __global__ __launch_bounds__(256) void compress_k_kernel(QuantArgs a)
 #pragma unroll
     for (int p = 0; p < P; ++p) load_pass<DENSE>(a.x, u.head_off, row0 + p * kPassRows, a.tokens, raw + p * 8, bad);
     if (a.rotate) rotate_rows<DT, P * 8>(raw);
+    if (a.anchors)
+        delta_rows<DT, DENSE, P * 8>(a.x, u.head_off, row0, a.tokens, a.anchor_shift,
+                                     head_anchors(a.anchors, u.lh, a.tokens, a.anchor_shift), true, raw, bad);
     KParams kp;
     uint8_t *meta_block = a.meta + (u.lh * a.units_per_head + u.blk) * (kDim * 4);
     k_group_params<BITS, DT, P * 8, 16>(raw, (uint8_t *)(xch_all + (threadIdx.x >> 6) * kXchFloats), meta_block, kp);
@@ -81,8 +84,10 @@ __global__ __launch_bounds__(256) void decompress_k_kernel(QuantArgs a)
     uint8_t *codes = head_codes<BITS>(a, u.lh) + row0 * (16 * BITS);
     const long long left = a.tokens - row0;
     bool bad = false;
-    dequant_pass<BITS, DT, false, DENSE, false>(codes, scale, zero, clamp, a.x, u.head_off, row0,
-                                                left < kPassRows ? (int)left : kPassRows, bad, 0, a.rotate != 0);
+    dequant_pass_any<BITS, DT, false, DENSE, 0>(codes, scale, zero, clamp, a.x, u.head_off, row0,
+                                                left < kPassRows ? (int)left : kPassRows, bad, a.rotate != 0,
+                                                a.anchors ? head_anchors(a.anchors, u.lh, a.tokens, a.anchor_shift) : nullptr,
+                                                a.anchor_shift);
     report(a.status, bad);
 }
 
@@ -99,6 +104,9 @@ __global__ __launch_bounds__(256) void compress_v_kernel(QuantArgs a)
     u32x4 raw[8];
     load_pass<DENSE>(a.x, u.head_off, row0, a.tokens, raw, bad);
     if (a.rotate) rotate_rows<DT, 8>(raw);
+    if (a.anchors)
+        delta_rows<DT, DENSE, 8>(a.x, u.head_off, row0, a.tokens, a.anchor_shift,
+                                 head_anchors(a.anchors, u.lh, a.tokens, a.anchor_shift), true, raw, bad);
     VParams vp;
     v_pass_params<BITS, GV, DT>(raw, vp);
     uint8_t *codes = head_codes<BITS>(a, u.lh) + row0 * (16 * BITS);
@@ -127,7 +135,9 @@ __global__ __launch_bounds__(256) void decompress_v_kernel(QuantArgs a)
     const bool clamp = v_meta_floats<BITS, DT>(mw, scale, zero);
     uint8_t *codes = head_codes<BITS>(a, u.lh) + row0 * (16 * BITS);
     bool bad = false;
-    dequant_pass<BITS, DT, true, DENSE, false>(codes, scale, zero, clamp, a.x, u.head_off, row0, rows, bad, 0, a.rotate != 0);
+    dequant_pass_any<BITS, DT, true, DENSE, 0>(codes, scale, zero, clamp, a.x, u.head_off, row0, rows, bad, a.rotate != 0,
+                                               a.anchors ? head_anchors(a.anchors, u.lh, a.tokens, a.anchor_shift) : nullptr,
+                                               a.anchor_shift);
     report(a.status, bad);
 }
 

@@ -445,10 +445,73 @@ template <int BITS, int LAYOUT> __device__ __forceinline__ u32x2 fetch_codes(uin
     return load_row_codes<BITS>(code_row<BITS, LAYOUT == 1>(codes, r));
 }
 
-template <int BITS, int DT, bool IS_V, bool DENSE, int LAYOUT, bool CLAMP>
+// ---- stage T, delta transform (KVServe section 5.1 names the difference from an anchor token
+//      among the transformer modules): the tokens of a head form runs of 2^shift tokens, the first
+//      token of a run is its anchor and travels unchanged; every row is quantized as its
+//      difference from the anchor row of its run ------------------------------------------------
+
+// a - b (ADD: a + b) element by element on two packed rows: the exact value rounded once to the
+// tensor type and limited to its finite range.  One fp32 operation and the conversion give
+// exactly that, because fp32 carries more than twice the digits of either 16-bit type.
+template <int DT, bool ADD> __device__ __forceinline__ u32x4 delta_row(const u32x4 &a, const u32x4 &b)
+{
+    constexpr float top = DT == DT_F16 ? 65504.0f : 3.3895313892515355e38f;
+    u32x4 out;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const float a0 = elem_f32<DT>(a, 2 * w), a1 = elem_f32<DT>(a, 2 * w + 1);
+        const float b0 = elem_f32<DT>(b, 2 * w), b1 = elem_f32<DT>(b, 2 * w + 1);
+        const float y0 = ADD ? a0 + b0 : a0 - b0, y1 = ADD ? a1 + b1 : a1 - b1;
+        f32x2_t v = {__builtin_amdgcn_fmed3f(y0, -top, top), __builtin_amdgcn_fmed3f(y1, -top, top)};
+        if (DT == DT_F16) out[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_t));
+        else out[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+    }
+    return out;
+}
+
+// The rows of N/8 passes just loaded (see load_pass: rows past the end repeat the last row)
+// become differences from their anchors, which are read from the tensor again (they were
+// loaded moments ago by this or a neighbouring wave).  With `keep`, the lanes that hold an
+// anchor row also store it to `anchors`, the head's anchor rows in the payload.
+template <int DT, bool DENSE, int N>
+__device__ __forceinline__ void delta_rows(const TensorView &v, long long head_off, long long row0, long long tokens,
+                                           int shift, uint16_t *anchors, bool keep, u32x4 *raw, bool &bad)
+{
+    const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
+    const long long mask = (1ll << shift) - 1;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        long long row = row0 + 4 * i + rsub;
+        const bool exists = row < tokens;
+        row = exists ? row : tokens - 1;
+        const long long arow = row & ~mask;
+        const long long off = DENSE ? head_off + arow * kDim : row_offset(v, head_off, arow, bad);
+        const u32x4 anchor = *(const u32x4 *)(v.base + off + col * 8);
+        if (keep && exists && row == arow) *(u32x4 *)(anchors + (arow >> shift) * kDim + col * 8) = anchor;
+        raw[i] = delta_row<DT, false>(raw[i], anchor);
+    }
+}
+
+// the head's first anchor row inside the tensor's anchor section
+__device__ __forceinline__ uint16_t *head_anchors(uint16_t *anchors, long long lh, long long tokens, int shift)
+{
+    return anchors + lh * ((tokens + (1ll << shift) - 1) >> shift) * kDim;
+}
+
+// a reconstructed difference row back to the token row: plus the anchor of its run; an anchor
+// row is its stored copy
+template <int DT>
+__device__ __forceinline__ u32x4 add_anchor(const u32x4 &out, const uint16_t *anchors, int shift, long long row)
+{
+    const u32x4 anchor = *(const u32x4 *)(anchors + (row >> shift) * kDim + (lane_id() & 15) * 8);
+    return (row & ((1ll << shift) - 1)) == 0 ? anchor : delta_row<DT, true>(out, anchor);
+}
+
+// TR: the inverse of stage T applied to every row (0 none, 1 Hadamard, 2 plus the anchor of the row's run)
+template <int BITS, int DT, bool IS_V, bool DENSE, int LAYOUT, bool CLAMP, int TR>
 __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float scale[8], const float zero[8],
                                                   const TensorView &x, long long head_off, long long row0, int rows,
-                                                  bool &bad, int row_base, bool rotate)
+                                                  bool &bad, int row_base, const uint16_t *anchors, int anchor_shift)
 {
     const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
     if (DENSE && rows >= kPassRows) {
@@ -458,7 +521,8 @@ __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float sc
             const u32x2 w = fetch_codes<BITS, LAYOUT>(codes, row_base + 4 * i + rsub);
             u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w, scale[i], zero[i])
                              : dequant_row<BITS, DT, CLAMP>(w, scale, zero);
-            if (rotate) out = hadamard_row<DT>(out, true);
+            if (TR == 1) out = hadamard_row<DT>(out, true);
+            if (TR == 2) out = add_anchor<DT>(out, anchors, anchor_shift, row0 + 4 * i + rsub);
             __builtin_nontemporal_store(out, dst + i * 64);
         }
         return;
@@ -470,7 +534,8 @@ __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float sc
         const u32x2 w = fetch_codes<BITS, LAYOUT>(codes, row_base + (ok ? r : 0));
         u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w, scale[i], zero[i])
                          : dequant_row<BITS, DT, CLAMP>(w, scale, zero);
-        if (rotate) out = hadamard_row<DT>(out, true);      // (all 16 lanes of a row take part)
+        if (TR == 1) out = hadamard_row<DT>(out, true);     // (all 16 lanes of a row take part)
+        if (TR == 2) out = add_anchor<DT>(out, anchors, anchor_shift, row0 + (ok ? r : 0));
         if (ok) {
             bool b = false;
             const long long off = DENSE ? head_off + (row0 + r) * kDim : row_offset(x, head_off, row0 + r, b);
@@ -481,15 +546,28 @@ __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float sc
 }
 
 // Dequantize the pass whose packed rows are rows row_base... of `codes` (see fetch_codes for
-// LAYOUT) and store its `rows` existing rows at token rows row0... of head `head_off`.
+// LAYOUT) and store its `rows` existing rows at token rows row0... of head `head_off`, after the
+// inverse of stage T (rotate: Hadamard; anchors: the head's anchor rows of the delta transform).
 // K: scale / zero per channel of the lane; V: per row of the lane.
-template <int BITS, int DT, bool IS_V, bool DENSE, int LAYOUT>
+template <int BITS, int DT, bool IS_V, bool DENSE, int LAYOUT, int TR = 0>
 __device__ __forceinline__ void dequant_pass(uint8_t *codes, const float scale[8], const float zero[8], bool clamp,
                                              const TensorView &x, long long head_off, long long row0, int rows, bool &bad,
-                                             int row_base = 0, bool rotate = false)
+                                             int row_base = 0, const uint16_t *anchors = nullptr, int anchor_shift = 0)
 {
-    if (clamp) dequant_pass_rows<BITS, DT, IS_V, DENSE, LAYOUT, true>(codes, scale, zero, x, head_off, row0, rows, bad, row_base, rotate);
-    else dequant_pass_rows<BITS, DT, IS_V, DENSE, LAYOUT, false>(codes, scale, zero, x, head_off, row0, rows, bad, row_base, rotate);
+    if (clamp) dequant_pass_rows<BITS, DT, IS_V, DENSE, LAYOUT, true, TR>(codes, scale, zero, x, head_off, row0, rows, bad, row_base, anchors, anchor_shift);
+    else dequant_pass_rows<BITS, DT, IS_V, DENSE, LAYOUT, false, TR>(codes, scale, zero, x, head_off, row0, rows, bad, row_base, anchors, anchor_shift);
+}
+
+// the same with the transform chosen at run time (one copy of the pass per transform; a launch
+// only ever runs one of them)
+template <int BITS, int DT, bool IS_V, bool DENSE, int LAYOUT>
+__device__ __forceinline__ void dequant_pass_any(uint8_t *codes, const float scale[8], const float zero[8], bool clamp,
+                                                 const TensorView &x, long long head_off, long long row0, int rows, bool &bad,
+                                                 bool rotate, const uint16_t *anchors, int anchor_shift)
+{
+    if (rotate) dequant_pass<BITS, DT, IS_V, DENSE, LAYOUT, 1>(codes, scale, zero, clamp, x, head_off, row0, rows, bad);
+    else if (anchors) dequant_pass<BITS, DT, IS_V, DENSE, LAYOUT, 2>(codes, scale, zero, clamp, x, head_off, row0, rows, bad, 0, anchors, anchor_shift);
+    else dequant_pass<BITS, DT, IS_V, DENSE, LAYOUT, 0>(codes, scale, zero, clamp, x, head_off, row0, rows, bad);
 }
 
 // Stage T on the rows just loaded (see hadamard_row).

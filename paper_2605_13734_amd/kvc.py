@@ -24,7 +24,7 @@ SYMBOLS = ["kvc_plan", "kvc_plan_free", "kvc_payload_size", "kvc_workspace_size"
 class Strategy(C.Structure):
     _fields_ = [("bits_k", C.c_uint8), ("bits_v", C.c_uint8), ("group_k", C.c_uint16),
                 ("group_v", C.c_uint16), ("codec", C.c_uint8), ("transform", C.c_uint8),
-                ("head_bits_k", C.c_void_p), ("head_bits_v", C.c_void_p)]
+                ("anchor_period", C.c_uint16), ("head_bits_k", C.c_void_p), ("head_bits_v", C.c_void_p)]
 
 
 class Profile(C.Structure):
@@ -107,8 +107,9 @@ class Plan:
     """kvc_plan / kvc_plan_free, kvc_payload_size, kvc_workspace_size."""
 
     def __init__(self, dtype, layers, kv_heads, head_dim=128, bits_k=4, bits_v=4, group_k=32,
-                 group_v=32, codec=0, max_tokens=0, max_batch=1, transform=0, head_bits_k=None, head_bits_v=None):
-        """head_bits_k / head_bits_v: optional sequences of layers * kv_heads widths (the uniform
+                 group_v=32, codec=0, max_tokens=0, max_batch=1, transform=0, head_bits_k=None, head_bits_v=None,
+                 anchor_period=0):
+        """transform 2 (difference from an anchor token) needs anchor_period.  head_bits_k / head_bits_v: optional sequences of layers * kv_heads widths (the uniform
         width of that tensor is then passed as 0)."""
         self.model = Model(dtype, layers, kv_heads, head_dim)
         tabs = []
@@ -119,7 +120,7 @@ class Plan:
                 tabs.append((C.c_uint8 * (layers * kv_heads))(*[int(b) for b in t]))
         self._tables = tabs
         self.strategy = Strategy(0 if tabs[0] is not None else bits_k, 0 if tabs[1] is not None else bits_v,
-                                 group_k, group_v, codec, transform,
+                                 group_k, group_v, codec, transform, anchor_period,
                                  C.cast(tabs[0], C.c_void_p) if tabs[0] is not None else None,
                                  C.cast(tabs[1], C.c_void_p) if tabs[1] is not None else None)
         self.max_tokens, self.max_batch = max_tokens, max_batch

@@ -31,19 +31,20 @@ def gpu_compress(plan, reqs, tokens):
     return buf
 
 
-def check_contiguous(ref, x_cpu, bits_k, bits_v, gk, gv, codec=0, T=None, transform=0):
+def check_contiguous(ref, x_cpu, bits_k, bits_v, gk, gv, codec=0, T=None, transform=0, anchor_period=0):
     """x_cpu: [L, 2, H, T, D] CPU tensor. Returns the GPU payload (numpy)."""
     L, _, H, Tfull, D = x_cpu.shape
     T = Tfull if T is None else T
     dt = DT[x_cpu.dtype]
     xu = kvgen.as_u16(x_cpu)
     cfg = ref.config(dtype=dt, layers=L, heads=H, bits_k=bits_k, bits_v=bits_v, group_k=gk, group_v=gv, codec=codec,
-                     transform=transform)
+                     transform=transform, anchor_period=anchor_period)
     lay = ref.contiguous_layout(H, Tfull, D)
     want = ref.compress(cfg, xu[0, 0], xu[0, 1], lay, T)
 
     x = x_cpu.cuda()
-    plan = kvc.Plan(dt, L, H, D, bits_k, bits_v, gk, gv, codec, max_tokens=T, transform=transform)
+    plan = kvc.Plan(dt, L, H, D, bits_k, bits_v, gk, gv, codec, max_tokens=T, transform=transform,
+                    anchor_period=anchor_period)
     buf = gpu_compress(plan, [kvc.contiguous_request(x, T)], [T])
     assert int(buf.status[0]) == 0
     got = buf.payload_of(0)
@@ -395,3 +396,28 @@ def test_transform_saturates_instead_of_overflowing(ref):
     x = torch.full((1, 2, 1, 64, 128), 60000.0, dtype=torch.float16)
     x[0, 1, 0, ::2] = -60000.0
     check_contiguous(ref, x, 4, 4, 32, 32, transform=1)
+
+
+def test_one_layer_at_a_time(ref):
+    """Layer-streamed use: a plan for one layer applied to each layer of a cache in turn (the
+    request's pointers name that layer) gives that layer's own payload, equal to the oracle's."""
+    L, H, T = 3, 2, 200
+    x_cpu = kvgen.make_kv(95, L, H, 128, T, torch.float16)
+    xu = kvgen.as_u16(x_cpu)
+    x = x_cpu.cuda()
+    for codec in (0, 1):
+        cfg = ref.config(dtype=1, layers=1, heads=H, bits_k=4, bits_v=2, group_k=32, group_v=64, codec=codec)
+        plan = kvc.Plan(1, 1, H, 128, 4, 2, 32, 64, codec, max_tokens=T)
+        lay = ref.contiguous_layout(H, T, 128)
+        for l in range(L):
+            want = ref.compress(cfg, xu[l, 0], xu[l, 1], lay, T)
+            buf = gpu_compress(plan, [kvc.contiguous_request(x[l:l + 1], T)], [T])
+            assert int(buf.status[0]) == 0
+            got = buf.payload_of(0)
+            assert np.array_equal(got, want), (codec, l, first_diff(got, want))
+            y = torch.zeros_like(x[l:l + 1])
+            buf.decompress([kvc.contiguous_request(y, T)], torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            ru = np.zeros_like(xu[l:l + 1])
+            assert ref.decompress(want, ru[0, 0], ru[0, 1], lay, cfg) == 0
+            assert np.array_equal(kvgen.as_u16(y.cpu()), ru)
