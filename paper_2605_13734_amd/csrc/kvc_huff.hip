@@ -495,8 +495,17 @@ template <int W> __device__ __forceinline__ void encode_two(const uint32_t *sym,
 // back over earlier tickets until it meets one that knows its inclusive prefix, and publishes
 // its own.  Ticket order guarantees that every predecessor is already running, so the wait
 // always ends; it is bounded by kSpinLimit all the same.
+// Waves per SIMD the register allocation must leave room for: four workgroups of the 2- to 4-bit
+// group-32 encoders fit a compute unit's LDS, and for fp16 rows in the dense layout they fit its
+// registers too without spilling (the other variants would spill, so they keep what they need).
+template <int BITS, int G, int DT, bool DENSE> constexpr int enc_min_waves()
+{
+    return (BITS <= 4 && G == 32 && DT == DT_F16 && DENSE) ? 4 : 1;
+}
+
 template <int BITS, int G, int DT, bool IS_V, bool DENSE>
-__global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) void encode_kernel(CoderArgs a)
+__global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) __attribute__((amdgpu_waves_per_eu(enc_min_waves<BITS, G, DT, DENSE>())))
+void encode_kernel(CoderArgs a)
 {
     using Geo = ChunkGeom<BITS>;
     constexpr int W = Geo::kWords, NW = Geo::kWaves;
