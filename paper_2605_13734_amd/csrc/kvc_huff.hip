@@ -781,14 +781,13 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
     const bool live = chunk < a.chunks;
     uint8_t *lds = lds_all + wave * Dec::kLds;
     PHASE_START();
-    // Register headroom.  A build of this kernel that needed exactly 112 VGPRs, and kept the
-    // length of the last-but-two symbol in v111, the last register of its allocation, decoded
-    // the last two symbols of a sub-block wrongly in about one wave of seven once four such waves
-    // shared a SIMD: the 64-bit shift that took v111 as its count shifted by the lane number
-    // instead (what a read past the allocation returns: the content of v0).  The same
-    // instructions with 120 registers allocated, or with two workgroups per CU, never did.  The
-    // cause is not understood; naming a higher register here keeps the allocation (128, still
-    // four waves per SIMD) above every register the code touches.
+    // Register headroom.  On this GPU a 64-bit shift whose count sits in the last VGPR of the
+    // wave's allocation shifts by the lane number instead, now and then, once three or four such
+    // waves share a SIMD (LLVM knows and avoids the fault for gfx90a only).  A build of this
+    // kernel that needed exactly 112 registers kept a code length in v111 for `window <<= len`
+    // and decoded the last two symbols of a sub-block wrongly in one wave of seven at full size.
+    // Naming a higher register keeps the allocation (128: still four waves per SIMD) above every
+    // register the code touches; the build checks the assembly of all kernels for the pattern.
     asm volatile("" ::: "v127");
 
     // Round trip 1: the chunk's two directory entries and the status word, with the decode

@@ -1,7 +1,9 @@
 """GPU checks at sizes where every kernel runs well past its first batch of workgroups (run with
 -m gpu).  The first 4 workgroups per CU start together on an idle chip; later ones start one at a
 time beside workgroups that are in other phases of their work, and a mistake that needs that mix
-does not show in small cases.  For every code width, both tensor types and both strategy kinds:
+does not show in small cases (the one that prompted this file: a 64-bit shift with its count in the
+last allocated VGPR, which this GPU executes wrongly at three or four waves per SIMD, never showed in
+the first 1024 workgroups).  For every code width, both tensor types and both strategy kinds:
 
 * the lossless stage is exactly that: reconstructions with and without it are the same bits
   (a property that holds at any size), on three decompressions of the same payload;

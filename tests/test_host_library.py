@@ -170,3 +170,26 @@ def test_delta_transform_sizes_and_inspect(lib, ref):
             bad = p.copy()
             bad[pos] = val
             assert kvc.payload_inspect(bad)[0] != 0, (pos, val)
+
+
+def test_build_check_finds_a_shift_count_in_the_last_vgpr(tmp_path):
+    """The build's assembly check: a 64-bit shift whose count is the last allocated VGPR is reported,
+    the same instruction with a register allocated after the count, or a 32-bit shift, is not."""
+    from paper_2605_13734_amd import build
+    def asm(next_free, body):
+        return ("\t.text\nkern:                                   ; @kern\n%s\ts_endpgm\n.Lfunc_end0:\n"
+                "\t.amdhsa_kernel kern\n\t\t.amdhsa_group_segment_fixed_size 0\n\t\t.amdhsa_next_free_vgpr %d\n"
+                "\t.end_amdhsa_kernel\n" % (body, next_free))
+    cases = [(112, "\tv_lshlrev_b64 v[58:59], v111, v[26:27]\n", 1),
+             (112, "\tv_lshrrev_b64 v[2:3], v111, v[4:5]\n\tv_ashrrev_i64 v[2:3], v111, v[4:5]\n", 2),
+             (120, "\tv_lshlrev_b64 v[58:59], v111, v[26:27]\n", 0),       # v112.. are allocated
+             (112, "\tv_lshlrev_b64 v[58:59], v109, v[26:27]\n", 0),       # not the last register
+             (112, "\tv_lshlrev_b64 v[58:59], 9, v[110:111]\n", 0),        # constant count
+             (112, "\tv_lshlrev_b32_e32 v5, v111, v4\n", 0),               # 32-bit shift
+             (110, "\tv_lshlrev_b64 v[2:3], v103, v[4:5]\n", 0)]           # 8n+7, but registers follow it
+    for i, (nf, body, want) in enumerate(cases):
+        p = tmp_path / ("k%d.s" % i)
+        p.write_text(asm(nf, body))
+        hits = build.shift_count_in_last_vgpr(str(p))
+        assert len(hits) == want, (i, hits)
+        assert all(h[0] == "kern" for h in hits)
