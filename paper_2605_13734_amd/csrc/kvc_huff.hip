@@ -743,12 +743,15 @@ __device__ __forceinline__ void load_meta_v(const QuantArgs &q, const ChunkPos &
 
 // Dequantize a decoded chunk from the wave's LDS region and store its rows; the metadata of a
 // pass is in flight one pass ahead.  meta0 / meta1 (K) or metav (V): the first pass's metadata.
+// first_anchor (delta transform with runs of 32 tokens or more): the first pass's anchor row.
 template <int BITS, int DT, bool IS_V, bool DENSE, int TR>
 __device__ __forceinline__ void dequant_chunk(const CoderArgs &a, const ChunkPos &c, uint8_t *lds, const u32x4 &meta0,
-                                              const u32x4 &meta1, const uint32_t metav[8], bool &bad)
+                                              const u32x4 &meta1, const uint32_t metav[8], const u32x4 &first_anchor, bool &bad)
 {
     using Dec = DecGeom<BITS>;
     const uint16_t *anchors = TR == 2 ? head_anchors(a.q.anchors, c.lh, a.q.tokens, a.q.anchor_shift) : nullptr;
+    const bool one_anchor = TR == 2 && a.q.anchor_shift >= 5;
+    u32x4 anchor = first_anchor, anchor_next = first_anchor;
     u32x4 mk0 = meta0, mk1 = meta1;
     uint32_t mv[8];
 #pragma unroll
@@ -761,9 +764,12 @@ __device__ __forceinline__ void dequant_chunk(const CoderArgs &a, const ChunkPos
         if ((p + 1) * kPassRows < c.rows) {
             if (!IS_V) load_meta_k(a.q, c, (p + 1) * kPassRows, mk0, mk1);
             else load_meta_v(a.q, c, (p + 1) * kPassRows, mv);
+            if (one_anchor) anchor_next = load_anchor(anchors, a.q.anchor_shift, c.row0 + (p + 1) * kPassRows);
         }
         dequant_pass<BITS, DT, IS_V, DENSE, Dec::kLayout, TR>(lds, scale, zero, clamp, a.q.x, c.head_off, c.row0 + p * kPassRows,
-                                                              c.rows - p * kPassRows, bad, p * kPassRows, anchors, a.q.anchor_shift);
+                                                              c.rows - p * kPassRows, bad, p * kPassRows, anchors, a.q.anchor_shift,
+                                                              one_anchor ? &anchor : nullptr);
+        anchor = anchor_next;
     }
 }
 
@@ -821,6 +827,7 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
     u32x4 bodyv[NB];
     u32x4 meta0 = {0, 0, 0, 0}, meta1 = {0, 0, 0, 0};
     uint32_t metav[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    u32x4 anchor0 = {0, 0, 0, 0};                      // delta transform: the first pass's anchor row
     if (ok) {
         const uint8_t *body = a.payload + a.off_bodies + d0 * 16;
 #pragma unroll
@@ -830,6 +837,8 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
         }
         if (!IS_V) load_meta_k(a.q, c, 0, meta0, meta1);
         else load_meta_v(a.q, c, 0, metav);
+        if (a.q.anchors && a.q.anchor_shift >= 5)
+            anchor0 = load_anchor(head_anchors(a.q.anchors, c.lh, a.q.tokens, a.q.anchor_shift), a.q.anchor_shift, c.row0);
     }
 #pragma unroll
     for (int i = 0; i < LUTN; ++i) ((u32x4 *)lut)[tid + i * NW * 64] = lutv[i];
@@ -897,9 +906,9 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
 
     // dequantize the rows from LDS (one copy of the loop per transform; a launch runs one of them)
     bool bad = false;
-    if (a.q.rotate) dequant_chunk<BITS, DT, IS_V, DENSE, 1>(a, c, lds, meta0, meta1, metav, bad);
-    else if (a.q.anchors) dequant_chunk<BITS, DT, IS_V, DENSE, 2>(a, c, lds, meta0, meta1, metav, bad);
-    else dequant_chunk<BITS, DT, IS_V, DENSE, 0>(a, c, lds, meta0, meta1, metav, bad);
+    if (a.q.rotate) dequant_chunk<BITS, DT, IS_V, DENSE, 1>(a, c, lds, meta0, meta1, metav, anchor0, bad);
+    else if (a.q.anchors) dequant_chunk<BITS, DT, IS_V, DENSE, 2>(a, c, lds, meta0, meta1, metav, anchor0, bad);
+    else dequant_chunk<BITS, DT, IS_V, DENSE, 0>(a, c, lds, meta0, meta1, metav, anchor0, bad);
     if (bad) atomicOr(a.q.status, KVC_DEV_BAD_BLOCK);
     PHASE(1, 3);
     PHASE_END(1);

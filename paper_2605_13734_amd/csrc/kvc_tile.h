@@ -451,20 +451,30 @@ template <int BITS, int LAYOUT> __device__ __forceinline__ u32x2 fetch_codes(uin
 //      difference from the anchor row of its run ------------------------------------------------
 
 // a - b (ADD: a + b) element by element on two packed rows: the exact value rounded once to the
-// tensor type and limited to its finite range.  One fp32 operation and the conversion give
-// exactly that, because fp32 carries more than twice the digits of either 16-bit type.
+// tensor type and limited to its finite range.  fp16: the packed half-precision add is that
+// rounding, and the packed minimum / maximum against +-65504 turn an overflow into the limit
+// (inputs are finite, so no NaN can arise).  bf16: one fp32 operation and the conversion give the
+// same, because fp32 carries more than twice the digits of the 16-bit type.
 template <int DT, bool ADD> __device__ __forceinline__ u32x4 delta_row(const u32x4 &a, const u32x4 &b)
 {
-    constexpr float top = DT == DT_F16 ? 65504.0f : 3.3895313892515355e38f;
     u32x4 out;
+    if (DT == DT_F16) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const f16x2_t x = __builtin_bit_cast(f16x2_t, (uint32_t)a[w]), y = __builtin_bit_cast(f16x2_t, (uint32_t)b[w]);
+            const f16x2_t r = ADD ? x + y : x - y;
+            out[w] = pk_max_f16(pk_min_f16(__builtin_bit_cast(uint32_t, r), 0x7bff7bffu), 0xfbfffbffu);
+        }
+        return out;
+    }
+    constexpr float top = 3.3895313892515355e38f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
         const float a0 = elem_f32<DT>(a, 2 * w), a1 = elem_f32<DT>(a, 2 * w + 1);
         const float b0 = elem_f32<DT>(b, 2 * w), b1 = elem_f32<DT>(b, 2 * w + 1);
         const float y0 = ADD ? a0 + b0 : a0 - b0, y1 = ADD ? a1 + b1 : a1 - b1;
         f32x2_t v = {__builtin_amdgcn_fmed3f(y0, -top, top), __builtin_amdgcn_fmed3f(y1, -top, top)};
-        if (DT == DT_F16) out[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_t));
-        else out[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+        out[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
     }
     return out;
 }
@@ -479,6 +489,22 @@ __device__ __forceinline__ void delta_rows(const TensorView &v, long long head_o
 {
     const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
     const long long mask = (1ll << shift) - 1;
+    if (shift >= 5) {
+        // a run covers whole passes (pass starts are multiples of 32): one anchor per pass
+#pragma unroll
+        for (int p = 0; p < N / 8; ++p) {
+            long long first = row0 + p * kPassRows;
+            const bool exists = first < tokens;
+            first = exists ? first : tokens - 1;
+            const long long arow = first & ~mask;
+            const long long off = DENSE ? head_off + arow * kDim : row_offset(v, head_off, arow, bad);
+            const u32x4 anchor = *(const u32x4 *)(v.base + off + col * 8);
+            if (keep && exists && first == arow && rsub == 0) *(u32x4 *)(anchors + (arow >> shift) * kDim + col * 8) = anchor;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) raw[p * 8 + i] = delta_row<DT, false>(raw[p * 8 + i], anchor);
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < N; ++i) {
         long long row = row0 + 4 * i + rsub;
@@ -501,19 +527,29 @@ __device__ __forceinline__ uint16_t *head_anchors(uint16_t *anchors, long long l
 // a reconstructed difference row back to the token row: plus the anchor of its run; an anchor
 // row is its stored copy
 template <int DT>
-__device__ __forceinline__ u32x4 add_anchor(const u32x4 &out, const uint16_t *anchors, int shift, long long row)
+__device__ __forceinline__ u32x4 add_anchor(const u32x4 &out, const u32x4 &anchor, int shift, long long row)
 {
-    const u32x4 anchor = *(const u32x4 *)(anchors + (row >> shift) * kDim + (lane_id() & 15) * 8);
     return (row & ((1ll << shift) - 1)) == 0 ? anchor : delta_row<DT, true>(out, anchor);
+}
+
+__device__ __forceinline__ u32x4 load_anchor(const uint16_t *anchors, int shift, long long row)
+{
+    return *(const u32x4 *)(anchors + (row >> shift) * kDim + (lane_id() & 15) * 8);
 }
 
 // TR: the inverse of stage T applied to every row (0 none, 1 Hadamard, 2 plus the anchor of the row's run)
 template <int BITS, int DT, bool IS_V, bool DENSE, int LAYOUT, bool CLAMP, int TR>
 __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float scale[8], const float zero[8],
                                                   const TensorView &x, long long head_off, long long row0, int rows,
-                                                  bool &bad, int row_base, const uint16_t *anchors, int anchor_shift)
+                                                  bool &bad, int row_base, const uint16_t *anchors, int anchor_shift,
+                                                  const u32x4 *loaded_anchor)
 {
     const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
+    // delta transform: a run of 32 tokens or more covers the whole pass (row0 is a multiple of 32);
+    // the caller may have that one anchor in flight already
+    const bool one_anchor = TR == 2 && anchor_shift >= 5;
+    u32x4 pass_anchor = {0, 0, 0, 0};
+    if (one_anchor) pass_anchor = loaded_anchor ? *loaded_anchor : load_anchor(anchors, anchor_shift, row0);
     if (DENSE && rows >= kPassRows) {
         u32x4 *dst = (u32x4 *)(x.base + head_off + (row0 + rsub) * kDim + col * 8);
 #pragma unroll
@@ -522,7 +558,10 @@ __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float sc
             u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w, scale[i], zero[i])
                              : dequant_row<BITS, DT, CLAMP>(w, scale, zero);
             if (TR == 1) out = hadamard_row<DT>(out, true);
-            if (TR == 2) out = add_anchor<DT>(out, anchors, anchor_shift, row0 + 4 * i + rsub);
+            if (TR == 2) {
+                const long long row = row0 + 4 * i + rsub;
+                out = add_anchor<DT>(out, one_anchor ? pass_anchor : load_anchor(anchors, anchor_shift, row), anchor_shift, row);
+            }
             __builtin_nontemporal_store(out, dst + i * 64);
         }
         return;
@@ -535,7 +574,10 @@ __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float sc
         u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w, scale[i], zero[i])
                          : dequant_row<BITS, DT, CLAMP>(w, scale, zero);
         if (TR == 1) out = hadamard_row<DT>(out, true);     // (all 16 lanes of a row take part)
-        if (TR == 2) out = add_anchor<DT>(out, anchors, anchor_shift, row0 + (ok ? r : 0));
+        if (TR == 2) {
+            const long long row = row0 + (ok ? r : 0);
+            out = add_anchor<DT>(out, one_anchor ? pass_anchor : load_anchor(anchors, anchor_shift, row), anchor_shift, row);
+        }
         if (ok) {
             bool b = false;
             const long long off = DENSE ? head_off + (row0 + r) * kDim : row_offset(x, head_off, row0 + r, b);
@@ -552,10 +594,11 @@ __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float sc
 template <int BITS, int DT, bool IS_V, bool DENSE, int LAYOUT, int TR = 0>
 __device__ __forceinline__ void dequant_pass(uint8_t *codes, const float scale[8], const float zero[8], bool clamp,
                                              const TensorView &x, long long head_off, long long row0, int rows, bool &bad,
-                                             int row_base = 0, const uint16_t *anchors = nullptr, int anchor_shift = 0)
+                                             int row_base = 0, const uint16_t *anchors = nullptr, int anchor_shift = 0,
+                                             const u32x4 *loaded_anchor = nullptr)
 {
-    if (clamp) dequant_pass_rows<BITS, DT, IS_V, DENSE, LAYOUT, true, TR>(codes, scale, zero, x, head_off, row0, rows, bad, row_base, anchors, anchor_shift);
-    else dequant_pass_rows<BITS, DT, IS_V, DENSE, LAYOUT, false, TR>(codes, scale, zero, x, head_off, row0, rows, bad, row_base, anchors, anchor_shift);
+    if (clamp) dequant_pass_rows<BITS, DT, IS_V, DENSE, LAYOUT, true, TR>(codes, scale, zero, x, head_off, row0, rows, bad, row_base, anchors, anchor_shift, loaded_anchor);
+    else dequant_pass_rows<BITS, DT, IS_V, DENSE, LAYOUT, false, TR>(codes, scale, zero, x, head_off, row0, rows, bad, row_base, anchors, anchor_shift, loaded_anchor);
 }
 
 // the same with the transform chosen at run time (one copy of the pass per transform; a launch
