@@ -411,11 +411,16 @@ static int table_ok(const ref_config *c, int is_v)
     return 1;
 }
 
+/* limits that keep every byte count of a payload far below 2^63 */
+#define MAX_HEADS ((int64_t)1 << 20)
+#define MAX_TOKENS ((int64_t)1 << 32)
+
 int ref_check_config(const ref_config *c)
 {
     if (!c) return REF_ERR_ARG;
     if (c->dtype != REF_F16 && c->dtype != REF_BF16) return REF_ERR_ARG;
     if (c->layers < 1 || c->heads < 1 || c->head_dim < 8 || c->head_dim % 8) return REF_ERR_ARG;
+    if ((int64_t)c->layers * c->heads > MAX_HEADS || c->head_dim > 1024) return REF_ERR_ARG;
     if (!table_ok(c, 0) || !table_ok(c, 1)) return REF_ERR_ARG;
     if ((c->head_bits_k || c->head_bits_v) && c->codec) return REF_ERR_UNSUPPORTED;
     if ((!c->head_bits_k && !bits_ok(c->bits_k)) || (!c->head_bits_v && !bits_ok(c->bits_v))) return REF_ERR_ARG;
@@ -489,7 +494,7 @@ int ref_payload_size(const ref_config *c, int64_t tokens, uint64_t *bytes, int *
 {
     int rc = ref_check_config(c);
     if (rc) return rc;
-    if (tokens < 0 || !bytes) return REF_ERR_ARG;
+    if (tokens < 0 || tokens > MAX_TOKENS || !bytes) return REF_ERR_ARG;
     geometry g;
     layout_of(c, tokens, &g);
     *bytes = (uint64_t)g.total;
@@ -789,7 +794,9 @@ int ref_inspect(const uint8_t *p, ref_config *c, int64_t *tokens, uint64_t *tota
         ref_config fields = *c;
         if (fields.head_bits_k) { fields.head_bits_k = NULL; fields.bits_k = fields.bits_k ? 0xff : 4; }
         if (fields.head_bits_v) { fields.head_bits_v = NULL; fields.bits_v = fields.bits_v ? 0xff : 4; }
-        if (ref_check_config(&fields) != REF_OK || (int64_t)get_u64(p + 32) < 0) return REF_ERR_FORMAT;
+        if (ref_check_config(&fields) != REF_OK || (int64_t)get_u64(p + 32) < 0 ||
+            (int64_t)get_u64(p + 32) > MAX_TOKENS)
+            return REF_ERR_FORMAT;
     }
     return REF_OK;
 }
@@ -799,7 +806,7 @@ int ref_compress(const ref_config *c, const void *k, const void *v, const ref_la
 {
     int rc = ref_check_config(c);
     if (rc) return rc;
-    if (T < 0 || !payload || !lay || (T > 0 && (!k || !v))) return REF_ERR_ARG;
+    if (T < 0 || T > MAX_TOKENS || !payload || !lay || (T > 0 && (!k || !v))) return REF_ERR_ARG;
     geometry g;
     layout_of(c, T, &g);
     if (capacity < (uint64_t)g.total) return REF_ERR_CAPACITY;

@@ -25,6 +25,8 @@ struct kvc_plan_s {
 };
 
 static const int kWidths[4] = {2, 3, 4, 8};
+// limits that keep every byte count of a payload below 2^63
+static const long long kMaxHeads = 1ll << 20, kMaxTokens = 1ll << 32;
 
 // Device tables of a plan with per-head widths, in this order (LH = layers * kv_heads):
 //   aux image : the bytes of the payload's auxiliary section (K table, V table, zero padding
@@ -187,6 +189,7 @@ static int check_pair(const kvc_model *m, const kvc_strategy *s)
     if (!m || !s) return KVC_ERR_ARG;
     if (m->dtype != KVC_F16 && m->dtype != KVC_BF16) return KVC_ERR_ARG;
     if (m->layers < 1 || m->kv_heads < 1 || m->head_dim < 1) return KVC_ERR_ARG;
+    if ((long long)m->layers * m->kv_heads > kMaxHeads) return KVC_ERR_ARG;      // sizes stay far below 2^63
     if ((!s->head_bits_k && !bits_ok(s->bits_k)) || (!s->head_bits_v && !bits_ok(s->bits_v))) return KVC_ERR_ARG;
     if (s->codec != KVC_CODEC_NONE && s->codec != KVC_CODEC_HUFF8) return KVC_ERR_ARG;
     if ((s->head_bits_k || s->bits_k != 16) && !group_ok(s->group_k)) return KVC_ERR_ARG;
@@ -217,7 +220,7 @@ extern "C" int kvc_plan(const kvc_model *model, const kvc_strategy *strategy, in
     *out = nullptr;
     int rc = check_pair(model, strategy);
     if (rc) return rc;
-    if (max_tokens < 0 || max_batch < 1) return KVC_ERR_ARG;
+    if (max_tokens < 0 || max_tokens > kMaxTokens || max_batch < 1) return KVC_ERR_ARG;
     kvc_plan_t *p = (kvc_plan_t *)calloc(1, sizeof(kvc_plan_t));
     if (!p) return KVC_ERR_ARG;
     p->model = *model;
@@ -271,7 +274,7 @@ extern "C" void kvc_plan_free(kvc_plan_t *plan)
 
 extern "C" int kvc_payload_size(const kvc_plan_t *plan, int64_t tokens, uint64_t *bytes, int *is_exact)
 {
-    if (!plan || !bytes || tokens < 0) return KVC_ERR_ARG;
+    if (!plan || !bytes || tokens < 0 || tokens > kMaxTokens) return KVC_ERR_ARG;
     Geometry g;
     geometry(plan, tokens, &g);
     *bytes = (uint64_t)g.total;
@@ -314,7 +317,7 @@ extern "C" int kvc_payload_inspect(const void *header128, kvc_model *model, kvc_
     if (flags & 1) { if (s.bits_k) return KVC_ERR_FORMAT; probe.bits_k = 4; }
     if (flags & 2) { if (s.bits_v) return KVC_ERR_FORMAT; probe.bits_v = 4; }
     int rc = check_pair(&m, &probe);
-    if (rc == KVC_ERR_ARG || T < 0) return KVC_ERR_FORMAT;
+    if (rc == KVC_ERR_ARG || T < 0 || T > kMaxTokens) return KVC_ERR_FORMAT;
     if (flags && s.codec) return KVC_ERR_FORMAT;
     if (h[30] | h[31]) return KVC_ERR_FORMAT;
     // the fixed part of the section table must be the closed form of the fields above

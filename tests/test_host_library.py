@@ -193,3 +193,35 @@ def test_build_check_finds_a_shift_count_in_the_last_vgpr(tmp_path):
         hits = build.shift_count_in_last_vgpr(str(p))
         assert len(hits) == want, (i, hits)
         assert all(h[0] == "kern" for h in hits)
+
+
+def test_inspect_never_accepts_a_damaged_header(lib, ref):
+    """Every single-byte change of a valid header is either rejected by kvc_payload_inspect or
+    leaves a header that the oracle also accepts with the same sections; without the lossless stage
+    only the type and the transform can change that way (they do not enter the sizes)."""
+    import torch
+    from paper_2605_13734_amd import kvgen
+    L, H, T = 2, 2, 150
+    x = kvgen.as_u16(kvgen.make_kv(3, L, H, 128, T, torch.float16))
+    lay = ref.contiguous_layout(H, T, 128)
+    rng = np.random.default_rng(5)
+    for kw in (dict(), dict(codec=1), dict(transform=1), dict(transform=2, anchor_period=16), dict(bits_k=16, bits_v=2, group_v=64)):
+        p = ref.compress(ref.config(layers=L, heads=H, **kw), x[0, 0], x[0, 1], lay, T)
+        assert kvc.payload_inspect(p)[0] == 0
+        accepted = set()
+        for pos in range(128):
+            for val in {int(p[pos]) ^ 1, int(p[pos]) ^ 0x80, int(rng.integers(0, 256))} - {int(p[pos])}:
+                bad = p.copy()
+                bad[pos] = val
+                rc, m, s, tokens, total, sec = kvc.payload_inspect(bad)
+                if rc == 0:
+                    accepted.add(pos)
+                    orc, ocfg, otok, ototal, osec = ref.inspect(bad)
+                    assert orc == 0 and otok == tokens and ototal == total and osec == sec, (kw, pos, val)
+        # with the lossless stage the data-dependent sizes are only bounded, so a few more changes pass
+        free = {6, 26} | ({22, 23} if kw.get("bits_k") == 16 else set())      # the group of a tensor stored unchanged is unused
+        assert accepted <= free or kw.get("codec"), (kw, accepted)
+    # a token count whose sizes wrap around 2^64 to those of a small one
+    bad = p.copy()
+    bad[39] = 4
+    assert kvc.payload_inspect(bad)[0] == -4 and ref.inspect(bad)[0] == -4
