@@ -67,11 +67,13 @@ def cpu_baseline(x_dev, layers, heads, tokens, dt, bits_k, bits_v, gk, gv, codec
 
 
 POLICY_STRATEGIES = [
-    # name, bits_k, bits_v, group_k, group_v, codec, transform
+    # name, bits_k, bits_v, group_k, group_v, codec, transform (0 none, 1 Hadamard, (2, anchor period) delta)
     ("int8g32", 8, 8, 32, 32, 0, 0),
     ("int4g32", 4, 4, 32, 32, 0, 0),
     ("int4g32_huff8", 4, 4, 32, 32, 1, 0),
     ("hadamard_int4g32", 4, 4, 32, 32, 0, 1),
+    ("delta32_int4g32", 4, 4, 32, 32, 0, (2, 32)),
+    ("delta128_int2g64", 2, 2, 64, 64, 0, (2, 128)),
     ("k4v2g64", 4, 2, 64, 64, 0, 0),
     ("int3g64", 3, 3, 64, 64, 0, 0),
     ("int2g64", 2, 2, 64, 64, 0, 0),
@@ -89,7 +91,8 @@ def policy_table(x, y, dt, L, H, T, steps):
     stream = torch.cuda.current_stream().cuda_stream
     profiles, rows = [], []
     for name, bk, bv, gk, gv, codec, tr in POLICY_STRATEGIES:
-        plan = kvc.Plan(dt, L, H, 128, bk, bv, gk, gv, codec, max_tokens=T, transform=tr)
+        tr, period = tr if isinstance(tr, tuple) else (tr, 0)
+        plan = kvc.Plan(dt, L, H, 128, bk, bv, gk, gv, codec, max_tokens=T, transform=tr, anchor_period=period)
         buf = kvc.Buffers(plan, [T], "cuda:0")
         src, dst = [kvc.contiguous_request(x)], [kvc.contiguous_request(y)]
         buf.compress(src, stream)

@@ -18,6 +18,7 @@
  *    launched; errors only the device can see (bad block-table entry, corrupt payload)
  *    are written to the caller's status words and never cause out-of-bounds accesses;
  *  - head_dim must be 128 (the kernels map 16 lanes x 8 channels onto one token row);
+ *  - layers * kv_heads <= 2^20 and tokens <= 2^32, so that no byte count comes near 2^63;
  *  - inputs must be finite; +0 and -0 are both reconstructed as +0.
  */
 #ifndef KVC_H
