@@ -743,14 +743,14 @@ __device__ __forceinline__ void load_meta_v(const QuantArgs &q, const ChunkPos &
 
 // Dequantize a decoded chunk from the wave's LDS region and store its rows; the metadata of a
 // pass is in flight one pass ahead.  meta0 / meta1 (K) or metav (V): the first pass's metadata.
-// first_anchor (delta transform with runs of 32 tokens or more): the first pass's anchor row.
+// first_anchor (delta transform): the first pass's anchor row.
 template <int BITS, int DT, bool IS_V, bool DENSE, int TR>
 __device__ __forceinline__ void dequant_chunk(const CoderArgs &a, const ChunkPos &c, uint8_t *lds, const u32x4 &meta0,
                                               const u32x4 &meta1, const uint32_t metav[8], const u32x4 &first_anchor, bool &bad)
 {
     using Dec = DecGeom<BITS>;
     const uint16_t *anchors = TR == 2 ? head_anchors(a.q.anchors, c.lh, a.q.tokens, a.q.anchor_shift) : nullptr;
-    const bool one_anchor = TR == 2 && a.q.anchor_shift >= 5;
+    constexpr bool one_anchor = TR == 2;
     u32x4 anchor = first_anchor, anchor_next = first_anchor;
     u32x4 mk0 = meta0, mk1 = meta1;
     uint32_t mv[8];
@@ -837,7 +837,7 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
         }
         if (!IS_V) load_meta_k(a.q, c, 0, meta0, meta1);
         else load_meta_v(a.q, c, 0, metav);
-        if (a.q.anchors && a.q.anchor_shift >= 5)
+        if (a.q.anchors)
             anchor0 = load_anchor(head_anchors(a.q.anchors, c.lh, a.q.tokens, a.q.anchor_shift), a.q.anchor_shift, c.row0);
     }
 #pragma unroll

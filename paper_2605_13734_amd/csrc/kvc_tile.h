@@ -482,39 +482,26 @@ template <int DT, bool ADD> __device__ __forceinline__ u32x4 delta_row(const u32
 // The rows of N/8 passes just loaded (see load_pass: rows past the end repeat the last row)
 // become differences from their anchors, which are read from the tensor again (they were
 // loaded moments ago by this or a neighbouring wave).  With `keep`, the lanes that hold an
-// anchor row also store it to `anchors`, the head's anchor rows in the payload.
+// anchor row also store it to `anchors`, the head's anchor rows in the payload.  Runs are 32
+// tokens or longer (shift >= 5).
 template <int DT, bool DENSE, int N>
 __device__ __forceinline__ void delta_rows(const TensorView &v, long long head_off, long long row0, long long tokens,
                                            int shift, uint16_t *anchors, bool keep, u32x4 *raw, bool &bad)
 {
     const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
     const long long mask = (1ll << shift) - 1;
-    if (shift >= 5) {
-        // a run covers whole passes (pass starts are multiples of 32): one anchor per pass
+    // a run (32 tokens or more) covers whole passes, whose first rows are multiples of 32: one anchor per pass
 #pragma unroll
-        for (int p = 0; p < N / 8; ++p) {
-            long long first = row0 + p * kPassRows;
-            const bool exists = first < tokens;
-            first = exists ? first : tokens - 1;
-            const long long arow = first & ~mask;
-            const long long off = DENSE ? head_off + arow * kDim : row_offset(v, head_off, arow, bad);
-            const u32x4 anchor = *(const u32x4 *)(v.base + off + col * 8);
-            if (keep && exists && first == arow && rsub == 0) *(u32x4 *)(anchors + (arow >> shift) * kDim + col * 8) = anchor;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) raw[p * 8 + i] = delta_row<DT, false>(raw[p * 8 + i], anchor);
-        }
-        return;
-    }
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-        long long row = row0 + 4 * i + rsub;
-        const bool exists = row < tokens;
-        row = exists ? row : tokens - 1;
-        const long long arow = row & ~mask;
+    for (int p = 0; p < N / 8; ++p) {
+        long long first = row0 + p * kPassRows;
+        const bool exists = first < tokens;
+        first = exists ? first : tokens - 1;
+        const long long arow = first & ~mask;
         const long long off = DENSE ? head_off + arow * kDim : row_offset(v, head_off, arow, bad);
         const u32x4 anchor = *(const u32x4 *)(v.base + off + col * 8);
-        if (keep && exists && row == arow) *(u32x4 *)(anchors + (arow >> shift) * kDim + col * 8) = anchor;
-        raw[i] = delta_row<DT, false>(raw[i], anchor);
+        if (keep && exists && first == arow && rsub == 0) *(u32x4 *)(anchors + (arow >> shift) * kDim + col * 8) = anchor;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) raw[p * 8 + i] = delta_row<DT, false>(raw[p * 8 + i], anchor);
     }
 }
 
@@ -545,11 +532,10 @@ __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float sc
                                                   const u32x4 *loaded_anchor)
 {
     const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
-    // delta transform: a run of 32 tokens or more covers the whole pass (row0 is a multiple of 32);
+    // delta transform: a run (32 tokens or more) covers the whole pass (row0 is a multiple of 32);
     // the caller may have that one anchor in flight already
-    const bool one_anchor = TR == 2 && anchor_shift >= 5;
     u32x4 pass_anchor = {0, 0, 0, 0};
-    if (one_anchor) pass_anchor = loaded_anchor ? *loaded_anchor : load_anchor(anchors, anchor_shift, row0);
+    if (TR == 2) pass_anchor = loaded_anchor ? *loaded_anchor : load_anchor(anchors, anchor_shift, row0);
     if (DENSE && rows >= kPassRows) {
         u32x4 *dst = (u32x4 *)(x.base + head_off + (row0 + rsub) * kDim + col * 8);
 #pragma unroll
@@ -558,10 +544,7 @@ __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float sc
             u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w, scale[i], zero[i])
                              : dequant_row<BITS, DT, CLAMP>(w, scale, zero);
             if (TR == 1) out = hadamard_row<DT>(out, true);
-            if (TR == 2) {
-                const long long row = row0 + 4 * i + rsub;
-                out = add_anchor<DT>(out, one_anchor ? pass_anchor : load_anchor(anchors, anchor_shift, row), anchor_shift, row);
-            }
+            if (TR == 2) out = add_anchor<DT>(out, pass_anchor, anchor_shift, row0 + 4 * i + rsub);
             __builtin_nontemporal_store(out, dst + i * 64);
         }
         return;
@@ -574,10 +557,7 @@ __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float sc
         u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w, scale[i], zero[i])
                          : dequant_row<BITS, DT, CLAMP>(w, scale, zero);
         if (TR == 1) out = hadamard_row<DT>(out, true);     // (all 16 lanes of a row take part)
-        if (TR == 2) {
-            const long long row = row0 + (ok ? r : 0);
-            out = add_anchor<DT>(out, one_anchor ? pass_anchor : load_anchor(anchors, anchor_shift, row), anchor_shift, row);
-        }
+        if (TR == 2) out = add_anchor<DT>(out, pass_anchor, anchor_shift, row0 + (ok ? r : 0));
         if (ok) {
             bool b = false;
             const long long off = DENSE ? head_off + (row0 + r) * kDim : row_offset(x, head_off, row0 + r, b);

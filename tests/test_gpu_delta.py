@@ -11,7 +11,7 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
-@pytest.mark.parametrize("bits,group,period", [(4, 32, 32), (2, 64, 8), (3, 128, 16), (8, 32, 128), (4, 128, 64)])
+@pytest.mark.parametrize("bits,group,period", [(4, 32, 32), (2, 64, 64), (3, 128, 32), (8, 32, 128), (4, 128, 64)])
 def test_delta_contiguous(ref, dtype, bits, group, period):
     x = kvgen.make_kv(80 + bits, 2, 2, 128, 32 * 9 + 5, dtype)
     check_contiguous(ref, x, bits, bits, group, group, transform=2, anchor_period=period)
@@ -20,11 +20,11 @@ def test_delta_contiguous(ref, dtype, bits, group, period):
 @pytest.mark.parametrize("T", [1, 7, 8, 9, 31, 33, 129])
 def test_delta_short_sequences(ref, T):
     x = kvgen.make_kv(81, 1, 2, 128, T, torch.float16)
-    check_contiguous(ref, x, 4, 4, 32, 32, transform=2, anchor_period=8)
+    check_contiguous(ref, x, 4, 4, 32, 32, transform=2, anchor_period=64)
     check_contiguous(ref, x, 4, 4, 32, 32, transform=2, anchor_period=32)
 
 
-@pytest.mark.parametrize("period", [8, 32, 128])
+@pytest.mark.parametrize("period", [32, 64, 128])
 def test_delta_with_codec_and_ragged_tail(ref, period):
     x = kvgen.make_kv(82, 2, 4, 128, 128 * 5 + 37, torch.float16)
     check_contiguous(ref, x, 4, 4, 32, 32, codec=1, transform=2, anchor_period=period)
@@ -33,7 +33,7 @@ def test_delta_with_codec_and_ragged_tail(ref, period):
 
 def test_delta_codec_bf16_8_bits(ref):
     x = kvgen.make_kv(83, 1, 3, 128, 128 * 4 + 3, torch.bfloat16)
-    check_contiguous(ref, x, 8, 8, 32, 32, codec=1, transform=2, anchor_period=16)
+    check_contiguous(ref, x, 8, 8, 32, 32, codec=1, transform=2, anchor_period=64)
 
 
 def test_delta_mixed_with_passthrough(ref):
@@ -52,16 +52,16 @@ def test_delta_saturates_instead_of_overflowing(ref):
     x = torch.full((1, 2, 1, 64, 128), 60000.0, dtype=torch.float16)
     x[0, :, 0, 1::2] = -60000.0
     check_contiguous(ref, x, 4, 4, 32, 32, transform=2, anchor_period=32)
-    check_contiguous(ref, x, 8, 8, 32, 32, transform=2, anchor_period=8)
+    check_contiguous(ref, x, 8, 8, 32, 32, transform=2, anchor_period=128)
 
 
 def test_delta_correlated_tokens(ref):
     """Token-correlated data (what the stage is for): small differences around large anchors."""
     g = torch.Generator().manual_seed(86)
-    base = torch.randn(2, 2, 2, 20, 1, 128, generator=g) * 6.0
-    x = (base + 0.05 * torch.randn(2, 2, 2, 20, 16, 128, generator=g)).reshape(2, 2, 2, 320, 128).to(torch.float16)
-    check_contiguous(ref, x, 2, 2, 32, 32, transform=2, anchor_period=16)
-    check_contiguous(ref, x, 4, 4, 32, 32, codec=1, transform=2, anchor_period=16)
+    base = torch.randn(2, 2, 2, 10, 1, 128, generator=g) * 6.0
+    x = (base + 0.05 * torch.randn(2, 2, 2, 10, 32, 128, generator=g)).reshape(2, 2, 2, 320, 128).to(torch.float16)
+    check_contiguous(ref, x, 2, 2, 32, 32, transform=2, anchor_period=32)
+    check_contiguous(ref, x, 4, 4, 32, 32, codec=1, transform=2, anchor_period=32)
 
 
 def test_delta_paged(ref):
@@ -98,11 +98,11 @@ def test_delta_with_per_head_widths(ref):
     tv = rng.choice([2, 8], L * H).astype(np.uint8)
     x = kvgen.make_kv(88, L, H, 128, T, torch.float16)
     xu = kvgen.as_u16(x)
-    cfg = ref.config(dtype=1, layers=L, heads=H, group_k=32, group_v=32, transform=2, anchor_period=16,
+    cfg = ref.config(dtype=1, layers=L, heads=H, group_k=32, group_v=32, transform=2, anchor_period=64,
                      head_bits_k=tk, head_bits_v=tv)
     lay = ref.contiguous_layout(H, T, 128)
     want = ref.compress(cfg, xu[0, 0], xu[0, 1], lay, T)
-    plan = kvc.Plan(1, L, H, 128, 0, 0, 32, 32, 0, max_tokens=T, transform=2, anchor_period=16,
+    plan = kvc.Plan(1, L, H, 128, 0, 0, 32, 32, 0, max_tokens=T, transform=2, anchor_period=64,
                     head_bits_k=tk, head_bits_v=tv)
     xd = x.cuda()
     buf = gpu_compress(plan, [kvc.contiguous_request(xd, T)], [T])
@@ -123,9 +123,17 @@ def test_delta_period_mismatch_is_reported(ref):
     x = kvgen.make_kv(89, 1, 2, 128, T, torch.float16).cuda()
     plan = kvc.Plan(1, 1, 2, 128, 4, 4, 32, 32, 0, max_tokens=T, transform=2, anchor_period=32)
     buf = gpu_compress(plan, [kvc.contiguous_request(x, T)], [T])
-    buf.payload[28] = 16                                # the header now names another period
+    buf.payload[28] = 64                                # the header now names another period
     y = torch.zeros_like(x)
     buf.decompress([kvc.contiguous_request(y, T)], torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
     assert int(buf.status[0]) & kvc.DEV_BAD_HEADER
     assert not y.any()                                  # nothing was written
+
+
+def test_delta_short_runs_are_not_built():
+    """The format allows runs of 8 and 16 tokens; the kernels take one anchor per pass of 32 rows."""
+    for period in (8, 16):
+        with pytest.raises(kvc.KvcError) as e:
+            kvc.Plan(1, 1, 2, 128, 4, 4, 32, 32, 0, max_tokens=64, transform=2, anchor_period=period)
+        assert e.value.status == -2

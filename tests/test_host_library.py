@@ -40,7 +40,7 @@ def test_plan_validation(lib):
         with pytest.raises(kvc.KvcError) as e:
             kvc.Plan(**{**ok, **kw})
         assert e.value.status == -1, kw
-    unsupported = [dict(head_dim=64), dict(transform=3), dict(bits_k=16, codec=1)]
+    unsupported = [dict(head_dim=64), dict(transform=3), dict(transform=2, anchor_period=8), dict(transform=2, anchor_period=16), dict(bits_k=16, codec=1)]
     for kw in unsupported:
         with pytest.raises(kvc.KvcError) as e:
             kvc.Plan(**{**ok, **kw})
@@ -148,13 +148,13 @@ def test_delta_transform_sizes_and_inspect(lib, ref):
     import torch
     from paper_2605_13734_amd import kvgen
     for codec in (0, 1):
-        for (L, H, T, bk, bv, period) in [(1, 8, 1024, 4, 4, 32), (3, 2, 1000, 4, 2, 8), (1, 1, 1, 3, 3, 128),
-                                          (2, 4, 77, 8, 4, 64), (1, 2, 0, 4, 4, 16), (80, 8, 32768, 4, 4, 32)]:
+        for (L, H, T, bk, bv, period) in [(1, 8, 1024, 4, 4, 32), (3, 2, 1000, 4, 2, 32), (1, 1, 1, 3, 3, 128),
+                                          (2, 4, 77, 8, 4, 64), (1, 2, 0, 4, 4, 64), (80, 8, 32768, 4, 4, 32)]:
             plan = kvc.Plan(2, L, H, 128, bk, bv, 32, 32, codec, max_tokens=T, transform=2, anchor_period=period)
             cfg = ref.config(dtype=2, layers=L, heads=H, bits_k=bk, bits_v=bv, codec=codec, transform=2, anchor_period=period)
             assert plan.payload_size(T) == ref.payload_size(cfg, T)
-    plan = kvc.Plan(1, 2, 2, 128, 16, 4, 32, 32, 0, transform=2, anchor_period=16)      # K travels unchanged: V anchors only
-    cfg = ref.config(layers=2, heads=2, bits_k=16, bits_v=4, transform=2, anchor_period=16)
+    plan = kvc.Plan(1, 2, 2, 128, 16, 4, 32, 32, 0, transform=2, anchor_period=32)      # K travels unchanged: V anchors only
+    cfg = ref.config(layers=2, heads=2, bits_k=16, bits_v=4, transform=2, anchor_period=32)
     assert plan.payload_size(77) == ref.payload_size(cfg, 77)
     L, H, T = 2, 2, 150
     x = kvgen.as_u16(kvgen.make_kv(2, L, H, 128, T, torch.float16))
@@ -166,7 +166,7 @@ def test_delta_transform_sizes_and_inspect(lib, ref):
         assert rc == 0 and tokens == T and total == p.size
         assert (s.transform, s.anchor_period) == (2, 32)
         assert sec == ref.inspect(p)[4]
-        for pos, val in [(28, 16), (28, 0), (28, 33), (29, 1), (30, 1), (26, 1), (26, 3)]:
+        for pos, val in [(28, 64), (28, 0), (28, 33), (29, 1), (30, 1), (26, 1), (26, 3)]:
             bad = p.copy()
             bad[pos] = val
             assert kvc.payload_inspect(bad)[0] != 0, (pos, val)
@@ -205,7 +205,7 @@ def test_inspect_never_accepts_a_damaged_header(lib, ref):
     x = kvgen.as_u16(kvgen.make_kv(3, L, H, 128, T, torch.float16))
     lay = ref.contiguous_layout(H, T, 128)
     rng = np.random.default_rng(5)
-    for kw in (dict(), dict(codec=1), dict(transform=1), dict(transform=2, anchor_period=16), dict(bits_k=16, bits_v=2, group_v=64)):
+    for kw in (dict(), dict(codec=1), dict(transform=1), dict(transform=2, anchor_period=64), dict(bits_k=16, bits_v=2, group_v=64)):
         p = ref.compress(ref.config(layers=L, heads=H, **kw), x[0, 0], x[0, 1], lay, T)
         assert kvc.payload_inspect(p)[0] == 0
         accepted = set()
