@@ -48,6 +48,17 @@ def shift_count_in_last_vgpr(asm_path):
     return hits
 
 
+def spilling_kernels(asm_path):
+    """[(kernel symbol, scratch bytes per lane)] of the kernels that spill registers."""
+    text = open(asm_path).read()
+    out = []
+    for k, body in re.findall(r"\.amdhsa_kernel (\w+)\n(.*?)\.end_amdhsa_kernel", text, re.S):
+        n = int(re.search(r"\.amdhsa_private_segment_fixed_size (\d+)", body).group(1))
+        if n:
+            out.append((k, n))
+    return out
+
+
 def _compile(name):
     obj = os.path.join(OBJ, name.replace(".hip", ".o"))
     cmd = ["hipcc"] + FLAGS + ["-save-temps=obj", "-c", os.path.join(SRC, name), "-o", obj]
@@ -60,6 +71,10 @@ def _compile(name):
     if hits:
         raise RuntimeError("%s: 64-bit shift with its count in the last allocated VGPR (give the kernel register "
                            "headroom):\n%s" % (name, "\n".join("  %s: %s" % h for h in hits[:20])))
+    spills = spilling_kernels(asm)
+    if spills:
+        err += "\n%s: %d kernels spill registers (most: %d bytes per lane): %s" % (
+            name, len(spills), max(n for _, n in spills), ", ".join(k for k, _ in spills[:6]))
     stem = name.replace(".hip", "")
     for f in os.listdir(OBJ):                      # the temporaries are large and no longer needed
         if (f.startswith(stem + "-") or f.startswith(stem + ".hip-")) and f != stem + ".o":
