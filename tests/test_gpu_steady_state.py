@@ -73,3 +73,37 @@ def test_mixed_widths_and_groups_far_past_the_first_batch(ref):
         _, y0 = run(kvc.Plan(1, L, H, 128, bk, bv, gk, gv, 0, max_tokens=T), x)
         _, y1 = run(kvc.Plan(1, L, H, 128, bk, bv, gk, gv, 1, max_tokens=T), x)
         assert torch.equal(y1.view(torch.int16), y0.view(torch.int16)), (bk, bv, gk, gv)
+
+
+def test_per_head_widths_far_past_the_first_batch(ref):
+    """Width tables (one launch per width over a head list) at the same size: sampled heads of every
+    width against the oracle, codes, metadata and reconstruction."""
+    rng = np.random.default_rng(7)
+    tk = rng.choice([2, 3, 4, 8], L * H).astype(np.uint8)
+    tv = rng.choice([2, 8], L * H).astype(np.uint8)
+    x = kvgen.make_kv(98, L, H, 128, T, torch.float16, "cuda")
+    plan = kvc.Plan(1, L, H, 128, 0, 0, 32, 32, 0, max_tokens=T, head_bits_k=tk, head_bits_v=tv)
+    buf, y = run(plan, x)
+    hdr = buf.payload[:128].cpu().numpy()
+    rc, _, _, tokens, total, sec = kvc.payload_inspect(hdr)
+    assert rc == 0 and tokens == T and total == int(buf.out_bytes[0])
+    lay = ref.contiguous_layout(1, T, 128)
+    picks = [(0, 0), (0, 1), (L * H - 1, 0), (L * H - 1, 1)]
+    for w in (2, 3, 4, 8):                                   # one more head of every width
+        picks.append((int(np.nonzero(tk == w)[0][len(np.nonzero(tk == w)[0]) // 2]), 0))
+    for lh, kv in picks:
+        table = tv if kv else tk
+        bits = int(table[lh])
+        l, h = divmod(lh, H)
+        cfg1 = ref.config(dtype=1, layers=1, heads=1, bits_k=bits, bits_v=bits, group_k=32, group_v=32)
+        xh = kvgen.as_u16(x[l, kv, h].cpu().contiguous())
+        codes, meta = ref.compress_head(cfg1, kv, xh, lay, T, 0, 0)
+        off = int(table[:lh].astype(np.int64).sum()) * T * 16          # widths of the heads before, 16 bytes per bit and row
+        got = buf.payload[sec[8 if kv else 6] + off: sec[8 if kv else 6] + off + codes.size].cpu().numpy()
+        assert np.array_equal(got, codes), ("codes", lh, kv, bits)
+        mo = sec[2 if kv else 0] + lh * meta.size * 2
+        got_meta = buf.payload[mo: mo + meta.size * 2].cpu().numpy().view(np.uint16)
+        assert np.array_equal(got_meta, meta), ("meta", lh, kv, bits)
+        back = np.zeros_like(xh)
+        ref.decompress_head(cfg1, kv, codes, meta, T, 0, 0, back, lay)
+        assert np.array_equal(kvgen.as_u16(y[l, kv, h].cpu().contiguous()), back), ("reconstruction", lh, kv, bits)
