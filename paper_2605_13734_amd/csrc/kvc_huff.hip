@@ -228,29 +228,28 @@ struct BuildLds {
     int longest;
 };
 
+// Code lengths from the weights s.w[], by a workgroup of 256 threads (one symbol each): Huffman's
+// algorithm with two queues, a leaf before a joined node of the same weight and the lower symbol
+// first among equal leaves; while the longest code exceeds kMaxLen all weights are halved (rounded
+// up) and the construction is repeated.  Sorting, depths and halving are spread over the threads;
+// the 255 joins are one thread's work.
 __device__ __forceinline__ void build_lengths(BuildLds &s)
 {
     constexpr uint32_t kNone = 0xffffffffu;
-    const int lane = lane_id();
+    const int tid = threadIdx.x;
     for (;;) {
-        // position of each leaf among all leaves
-        int pos[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int k = lane + 64 * j;
-            const uint32_t wk = s.w[k];
-            int rank = 0;
-            for (int t = 0; t < 256; ++t) {
-                const uint32_t wt = s.w[t];
-                rank += (wt < wk || (wt == wk && t < k)) ? 1 : 0;
-            }
-            pos[j] = rank;
-            s.sw[rank] = wk;
+        // position of the thread's leaf among all leaves
+        const uint32_t wk = s.w[tid];
+        int pos = 0;
+        for (int t = 0; t < 256; ++t) {
+            const uint32_t wt = s.w[t];
+            pos += (wt < wk || (wt == wk && t < tid)) ? 1 : 0;
         }
-        if (lane < 2) s.sw[256 + lane] = kNone;
-        if (lane == 0) s.longest = 0;
-        wave_sync();
-        if (lane == 0) {
+        s.sw[pos] = wk;
+        if (tid < 2) s.sw[256 + tid] = kNone;
+        if (tid == 0) s.longest = 0;
+        __syncthreads();
+        if (tid == 0) {
             uint32_t wl = s.sw[0], wl1 = s.sw[1];      // front of the leaf queue and the one behind it
             uint32_t wj = kNone, wj1 = kNone;          // same for the queue of joined nodes
             int lq = 0, jq = 0, made = 0;
@@ -278,23 +277,17 @@ __device__ __forceinline__ void build_lengths(BuildLds &s)
                 ++made;
             }
         }
-        wave_sync();
-        int deepest = 0;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            int d = 1;
-            for (int i = s.parent_leaf[pos[j]]; i != 254 && d < 256; i = s.parent_int[i]) ++d;
-            s.len[lane + 64 * j] = (uint8_t)d;
-            deepest = max(deepest, d);
-        }
-        atomicMax(&s.longest, deepest);
-        wave_sync();
+        __syncthreads();
+        int d = 1;
+        for (int i = s.parent_leaf[pos]; i != 254 && d < 256; i = s.parent_int[i]) ++d;
+        s.len[tid] = (uint8_t)d;
+        atomicMax(&s.longest, d);
+        __syncthreads();
         if (s.longest <= kMaxLen) return;
-        for (int k = lane; k < 256; k += 64) {
-            const uint32_t v = (s.w[k] + 1) >> 1;
-            s.w[k] = v < 1 ? 1 : v;
-        }
-        wave_sync();
+        const uint32_t v = (wk + 1) >> 1;
+        __syncthreads();                               // everyone has seen `longest` before it is cleared
+        s.w[tid] = v < 1 ? 1 : v;
+        __syncthreads();
     }
 }
 
@@ -338,32 +331,40 @@ template <bool ORDER> __device__ __forceinline__ bool canonical_tables(BuildLds 
     return true;
 }
 
-__device__ __forceinline__ uint32_t code_of(const BuildLds &s, int sym)
-{
-    const int L = s.len[sym];
-    int rank = 0;
-    for (int t = 0; t < sym; ++t) rank += (s.len[t] == L) ? 1 : 0;
-    return s.first[L] + rank;
-}
-
 constexpr int kTableWaves = 8;      // waves that fill a decode table
 
-// grid = 2 workgroups of one wave: 0 builds the K table, 1 the V table
-__global__ __launch_bounds__(64) void build_tables_kernel(CoderArgs a)
+// grid = 2 workgroups of 256 threads (one symbol each): 0 builds the K table, 1 the V table
+__global__ __launch_bounds__(256) void build_tables_kernel(CoderArgs a)
 {
     __shared__ BuildLds s;
-    const int sec = blockIdx.x, lane = lane_id();
-    const uint32_t *hist = a.ws.hist + 256 * sec;
-    for (int k = lane; k < 256; k += 64) s.w[k] = hist[k] + 1;
-    wave_sync();
+    __shared__ uint32_t block_count[4][16];            // symbols of each length in each block of 64 symbols
+    const int sec = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
+    s.w[tid] = a.ws.hist[256 * sec + tid] + 1;
+    __syncthreads();
     build_lengths(s);
-    canonical_tables<false>(s);
-    uint8_t *lens = a.payload + a.off_aux + 256 * sec;
-    uint32_t *enc = a.ws.enc + 256 * sec;
-    for (int k = lane; k < 256; k += 64) {
-        lens[k] = s.len[k];
-        enc[k] = code_of(s, k) | ((uint32_t)s.len[k] << 16);
+    // canonical codes: first code of every length, and the symbol's place among the symbols of
+    // its length (those of lower blocks, then the lower lanes of its own block)
+    const int L = s.len[tid];
+    int within = 0;
+#pragma unroll
+    for (int l = 1; l <= kMaxLen; ++l) {
+        const unsigned long long same = __builtin_amdgcn_ballot_w64(L == l);
+        if (lane == 0) block_count[wave][l] = (uint32_t)__builtin_popcountll(same);
+        if (L == l) within = __builtin_popcountll(same & ((1ull << lane) - 1));
     }
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t next = 0;
+        for (int l = 1; l <= kMaxLen; ++l) {
+            s.first[l] = next;
+            next = (next + block_count[0][l] + block_count[1][l] + block_count[2][l] + block_count[3][l]) << 1;
+        }
+    }
+    __syncthreads();
+    uint32_t rank = (uint32_t)within;
+    for (int w = 0; w < wave; ++w) rank += block_count[w][L];
+    a.payload[a.off_aux + 256 * sec + tid] = (uint8_t)L;
+    a.ws.enc[256 * sec + tid] = (s.first[L] + rank) | ((uint32_t)L << 16);
 }
 
 // grid = 2 workgroups of kTableWaves waves: decode tables from the lengths stored in the payload
@@ -1007,7 +1008,7 @@ int launch_coder_tables(int bits_k, int bits_v, int group_k, int group_v, int dt
     if (rc) return rc;
     rc = hist_b<true>(bits_v, group_v, dtype, v, s);
     if (rc) return rc;
-    hipLaunchKernelGGL(build_tables_kernel, dim3(2), dim3(64), 0, s, k);
+    hipLaunchKernelGGL(build_tables_kernel, dim3(2), dim3(256), 0, s, k);
     return launched();
 }
 
