@@ -291,46 +291,6 @@ __device__ __forceinline__ void build_lengths(BuildLds &s)
     }
 }
 
-// Canonical order tables from len[]: count / first code / start index per length, and (ORDER)
-// the symbols sorted by (length, symbol).  Returns false if the lengths are not a complete code.
-template <bool ORDER> __device__ __forceinline__ bool canonical_tables(BuildLds &s)
-{
-    const int lane = lane_id();
-    if (lane < 16) s.count[lane] = 0;
-    wave_sync();
-    bool ok = true;
-    for (int k = lane; k < 256; k += 64) {
-        const int L = s.len[k];
-        if (L < 1 || L > kMaxLen) ok = false;
-        else atomicAdd(&s.count[L], 1u);
-    }
-    wave_sync();
-    if (lane == 0) {
-        uint32_t next = 0, at = 0, kraft = 0;
-        for (int L = 1; L <= kMaxLen; ++L) {
-            s.first[L] = next;
-            s.start[L] = at;
-            next = (next + s.count[L]) << 1;
-            at += s.count[L];
-            kraft += s.count[L] << (kMaxLen - L);
-        }
-        s.longest = (kraft == (1u << kMaxLen)) ? 1 : 0;
-    }
-    wave_sync();
-    ok = ok && s.longest == 1;
-    if (__builtin_amdgcn_ballot_w64(!ok) != 0) return false;
-    if (ORDER) {
-        for (int k = lane; k < 256; k += 64) {
-            const int L = s.len[k];
-            int rank = 0;
-            for (int t = 0; t < k; ++t) rank += (s.len[t] == L) ? 1 : 0;
-            s.by_len[s.start[L] + rank] = (uint16_t)k;
-        }
-        wave_sync();
-    }
-    return true;
-}
-
 constexpr int kTableWaves = 8;      // waves that fill a decode table
 
 // grid = 2 workgroups of 256 threads (one symbol each): 0 builds the K table, 1 the V table
@@ -371,18 +331,45 @@ __global__ __launch_bounds__(256) void build_tables_kernel(CoderArgs a)
 __global__ __launch_bounds__(kTableWaves * 64) void decode_prepare_kernel(CoderArgs a)
 {
     __shared__ BuildLds s;
+    __shared__ uint32_t block_count[4][16];            // symbols of each length in each block of 64 symbols
     __shared__ int s_ok;
     const int sec = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
     if (*a.q.status & KVC_DEV_BAD_HEADER) return;
-    if (wave == 0) {
-        const uint8_t *lens = a.payload + a.off_aux + 256 * sec;
-        for (int k = lane; k < 256; k += 64) s.len[k] = lens[k];
-        wave_sync();
-        const bool ok = canonical_tables<true>(s);
-        if (lane == 0) {
-            s_ok = ok ? 1 : 0;
-            if (!ok) atomicOr(a.q.status, KVC_DEV_BAD_TABLE);
+    // canonical order: the first four waves hold one symbol per thread
+    int mylen = 0, within = 0;
+    if (tid < 256) {
+        mylen = a.payload[a.off_aux + 256 * sec + tid];
+#pragma unroll
+        for (int l = 1; l <= kMaxLen; ++l) {
+            const unsigned long long same = __builtin_amdgcn_ballot_w64(mylen == l);
+            if (lane == 0) block_count[wave][l] = (uint32_t)__builtin_popcountll(same);
+            if (mylen == l) within = __builtin_popcountll(same & ((1ull << lane) - 1));
         }
+        const bool in_range = mylen >= 1 && mylen <= kMaxLen;
+        if (lane == 0) block_count[wave][0] = __builtin_amdgcn_ballot_w64(!in_range) != 0 ? 1u : 0u;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t next = 0, at = 0, kraft = 0;
+        for (int l = 1; l <= kMaxLen; ++l) {
+            const uint32_t n = block_count[0][l] + block_count[1][l] + block_count[2][l] + block_count[3][l];
+            s.count[l] = n;
+            s.first[l] = next;
+            s.start[l] = at;
+            next = (next + n) << 1;
+            at += n;
+            kraft += n << (kMaxLen - l);
+        }
+        const bool bad_len = (block_count[0][0] | block_count[1][0] | block_count[2][0] | block_count[3][0]) != 0;
+        const bool ok = !bad_len && kraft == (1u << kMaxLen);          // a complete prefix code
+        s_ok = ok ? 1 : 0;
+        if (!ok) atomicOr(a.q.status, KVC_DEV_BAD_TABLE);
+    }
+    __syncthreads();
+    if (s_ok && tid < 256) {
+        uint32_t rank = (uint32_t)within;
+        for (int w = 0; w < wave; ++w) rank += block_count[w][mylen];
+        s.by_len[s.start[mylen] + rank] = (uint16_t)tid;                    // symbols by (length, symbol)
     }
     __syncthreads();
     uint16_t *lut = a.ws.lut + 4096 * sec;
