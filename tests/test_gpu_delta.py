@@ -137,3 +137,32 @@ def test_delta_short_runs_are_not_built():
         with pytest.raises(kvc.KvcError) as e:
             kvc.Plan(1, 1, 2, 128, 4, 4, 32, 32, 0, max_tokens=64, transform=2, anchor_period=period)
         assert e.value.status == -2
+
+
+@pytest.mark.parametrize("codec", [0, 1])
+def test_delta_ragged_batch(ref, codec):
+    """A batch of requests of different lengths (one empty): every payload, with its own anchor
+    rows, equals the one the oracle makes for that request alone."""
+    L, H = 2, 4
+    lens = [70, 128, 0, 201, 33]
+    cfg = ref.config(dtype=2, layers=L, heads=H, bits_k=4, bits_v=2, group_k=64, group_v=64, codec=codec,
+                     transform=2, anchor_period=32)
+    plan = kvc.Plan(2, L, H, 128, 4, 2, 64, 64, codec, max_tokens=max(lens), max_batch=len(lens), transform=2,
+                    anchor_period=32)
+    xs = [kvgen.make_kv(110 + i, L, H, 128, max(T, 1), torch.bfloat16) for i, T in enumerate(lens)]
+    xd = [x.cuda() for x in xs]
+    buf = gpu_compress(plan, [kvc.contiguous_request(x, T) for x, T in zip(xd, lens)], lens)
+    for i, T in enumerate(lens):
+        xu = kvgen.as_u16(xs[i])
+        want = ref.compress(cfg, xu[0, 0], xu[0, 1], ref.contiguous_layout(H, max(T, 1), 128), T)
+        assert int(buf.status[i]) == 0
+        got = buf.payload_of(i)
+        assert np.array_equal(got, want), (i, first_diff(got, want))
+    ys = [torch.zeros_like(x) for x in xd]
+    buf.decompress([kvc.contiguous_request(y, T) for y, T in zip(ys, lens)], torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    for i, T in enumerate(lens):
+        xu = kvgen.as_u16(xs[i])
+        ru = np.zeros_like(xu)
+        assert ref.decompress(buf.payload_of(i), ru[0, 0], ru[0, 1], ref.contiguous_layout(H, max(T, 1), 128), cfg) == 0
+        assert np.array_equal(kvgen.as_u16(ys[i].cpu()), ru), i
