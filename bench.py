@@ -4,7 +4,7 @@
 One step = one pass of the whole path over one request of synthetic KV that is already
 resident in HBM: kvc_compress (tables, quantize + pack + Huffman encode + offset scan for
 K and V) followed by kvc_decompress (table set-up, decode + unpack + dequantize).
-Workload: the Llama-3.1-70B shape of the benchmark spec (80 layers, 8 KV heads, head_dim 128,
+Workload: the Llama-3.1-70B shape (80 layers, 8 KV heads, head_dim 128,
 32768 tokens, fp16, 10.74 GB), strategy 4-bit / group 32 followed by the lossless stage.
 
 Prints ONE JSON line.  `value` is the paper's effective throughput s_p = V / (t_enc + t_dec)
