@@ -107,7 +107,10 @@ __device__ __forceinline__ ChunkPos chunk_pos(const QuantArgs &a, long long chun
 // Quantize and pack the chunk's rows into the wave's LDS region (sub-block layout) and,
 // when `write_meta`, store the group metadata to the payload.  K group parameters are
 // exchanged through the 16 padding bytes that follow each sub-block.
-template <int BITS, int G, int DT, bool IS_V, bool DENSE>
+// XF = false leaves the code of stage T out (for launches that have no transform): in one kernel
+// with the plain path it costs the plain path its registers, most of all for token blocks of 64
+// and 128 rows.
+template <int BITS, int G, int DT, bool IS_V, bool DENSE, bool XF = true>
 __device__ __forceinline__ void quantize_chunk(const QuantArgs &a, const ChunkPos &c, uint8_t *lds, bool write_meta,
                                                bool &bad)
 {
@@ -119,8 +122,8 @@ __device__ __forceinline__ void quantize_chunk(const QuantArgs &a, const ChunkPo
         u32x4 raw[PU * 8];
 #pragma unroll
         for (int p = 0; p < PU; ++p) load_pass<DENSE>(a.x, c.head_off, row0 + p * kPassRows, a.tokens, raw + p * 8, bad);
-        if (a.rotate) rotate_rows<DT, PU * 8>(raw);
-        if (a.anchors)
+        if (XF && a.rotate) rotate_rows<DT, PU * 8>(raw);
+        if (XF && a.anchors)
             delta_rows<DT, DENSE, PU * 8>(a.x, c.head_off, row0, a.tokens, a.anchor_shift,
                                           head_anchors(a.anchors, c.lh, a.tokens, a.anchor_shift), write_meta, raw, bad);
         if (!IS_V) {
@@ -491,7 +494,7 @@ template <int BITS, int G, int DT, bool DENSE> constexpr int enc_min_waves()
     return (BITS <= 4 && G == 32 && DT == DT_F16 && DENSE) ? 4 : 1;
 }
 
-template <int BITS, int G, int DT, bool IS_V, bool DENSE>
+template <int BITS, int G, int DT, bool IS_V, bool DENSE, bool XF>
 __global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) __attribute__((amdgpu_waves_per_eu(enc_min_waves<BITS, G, DT, DENSE>())))
 void encode_kernel(CoderArgs a)
 {
@@ -526,7 +529,7 @@ void encode_kernel(CoderArgs a)
         ChunkPos c = chunk_pos(a.q, chunk);
         rows = c.rows;
         bool bad = false;
-        quantize_chunk<BITS, G, DT, IS_V, DENSE>(a.q, c, lds, true, bad);
+        quantize_chunk<BITS, G, DT, IS_V, DENSE, XF>(a.q, c, lds, true, bad);
         if (bad) atomicOr(a.q.status, KVC_DEV_BAD_BLOCK);
         wave_sync();
         PHASE(0, 1);
@@ -918,8 +921,15 @@ template <int BITS, int G, int DT, bool IS_V> static int encode_launch(const Cod
     constexpr int NW = ChunkGeom<BITS>::kWaves;
     const long long need = (a.chunks + NW - 1) / NW;
     if (need <= 0) return KVC_OK;
-    if (a.q.dense) hipLaunchKernelGGL((encode_kernel<BITS, G, DT, IS_V, true>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
-    else hipLaunchKernelGGL((encode_kernel<BITS, G, DT, IS_V, false>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
+    // K token blocks of 64 and 128 rows have a kernel of their own for launches without a transform
+    constexpr bool kSplit = !IS_V && G >= 64;
+    if (kSplit && !a.q.rotate && !a.q.anchors) {
+        if (a.q.dense) hipLaunchKernelGGL((encode_kernel<BITS, G, DT, IS_V, true, !kSplit>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
+        else hipLaunchKernelGGL((encode_kernel<BITS, G, DT, IS_V, false, !kSplit>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
+        return launched();
+    }
+    if (a.q.dense) hipLaunchKernelGGL((encode_kernel<BITS, G, DT, IS_V, true, true>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
+    else hipLaunchKernelGGL((encode_kernel<BITS, G, DT, IS_V, false, true>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
     return launched();
 }
 

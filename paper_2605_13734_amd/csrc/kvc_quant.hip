@@ -43,7 +43,9 @@ __device__ __forceinline__ void report(int *status, bool bad)
 
 // ---- K: groups along tokens, one per channel ------------------------------------------------
 
-template <int BITS, int G, int DT, bool DENSE>
+// XF = false leaves the code of stage T out (for launches without a transform): sharing a kernel
+// with it doubles the registers of the plain path for token blocks of 64 and 128 rows.
+template <int BITS, int G, int DT, bool DENSE, bool XF>
 __global__ __launch_bounds__(256) void compress_k_kernel(QuantArgs a)
 {
     __shared__ __attribute__((aligned(16))) float xch_all[4 * kXchFloats];
@@ -55,8 +57,8 @@ __global__ __launch_bounds__(256) void compress_k_kernel(QuantArgs a)
     u32x4 raw[P * 8];
 #pragma unroll
     for (int p = 0; p < P; ++p) load_pass<DENSE>(a.x, u.head_off, row0 + p * kPassRows, a.tokens, raw + p * 8, bad);
-    if (a.rotate) rotate_rows<DT, P * 8>(raw);
-    if (a.anchors)
+    if (XF && a.rotate) rotate_rows<DT, P * 8>(raw);
+    if (XF && a.anchors)
         delta_rows<DT, DENSE, P * 8>(a.x, u.head_off, row0, a.tokens, a.anchor_shift,
                                      head_anchors(a.anchors, u.lh, a.tokens, a.anchor_shift), true, raw, bad);
     KParams kp;
@@ -208,10 +210,15 @@ static inline dim3 grid_for(long long units) { return dim3((unsigned)((units + 3
 template <int BITS, int DT, bool DENSE> static int compress_bits_dt(int is_v, int group, const QuantArgs &a, hipStream_t s)
 {
     if (!is_v) {
+        const bool xf = a.rotate || a.anchors;
         switch (group) {
-        case 32: KVC_LAUNCH((compress_k_kernel<BITS, 32, DT, DENSE>), a, s);
-        case 64: KVC_LAUNCH((compress_k_kernel<BITS, 64, DT, DENSE>), a, s);
-        case 128: KVC_LAUNCH((compress_k_kernel<BITS, 128, DT, DENSE>), a, s);
+        case 32: KVC_LAUNCH((compress_k_kernel<BITS, 32, DT, DENSE, true>), a, s);
+        case 64:
+            if (xf) KVC_LAUNCH((compress_k_kernel<BITS, 64, DT, DENSE, true>), a, s);
+            KVC_LAUNCH((compress_k_kernel<BITS, 64, DT, DENSE, false>), a, s);
+        case 128:
+            if (xf) KVC_LAUNCH((compress_k_kernel<BITS, 128, DT, DENSE, true>), a, s);
+            KVC_LAUNCH((compress_k_kernel<BITS, 128, DT, DENSE, false>), a, s);
         }
     } else {
         switch (group) {

@@ -314,6 +314,9 @@ __device__ __forceinline__ void k_emit_rows(const u32x4 *raw, const KParams &kp,
             u32x2 w = k_quant_row<BITS, DT, CLAMP>(raw[p * 8 + i], kp, one);
             if (BITS == 3) w[0] = quad_words_from_24(w[0]);
             if (FULL || r < rows) store_codes<BITS>(code_row<BITS, SUB>(base, r), w);
+            // a token block of 64 or 128 rows: keep the scheduler from interleaving all rows, which
+            // would hold the floats of every row at once (255 registers and more)
+            if (P >= 2) __builtin_amdgcn_sched_barrier(0);
         }
 }
 
