@@ -921,8 +921,9 @@ template <int BITS, int G, int DT, bool IS_V> static int encode_launch(const Cod
     constexpr int NW = ChunkGeom<BITS>::kWaves;
     const long long need = (a.chunks + NW - 1) / NW;
     if (need <= 0) return KVC_OK;
-    // K token blocks of 64 and 128 rows have a kernel of their own for launches without a transform
-    constexpr bool kSplit = !IS_V && G >= 64;
+    // K token blocks of 64 and 128 rows, and V groups of 32 channels (the variant that is short of
+    // registers), have a kernel of their own for launches without a transform
+    constexpr bool kSplit = IS_V ? G == 32 : G >= 64;
     if (kSplit && !a.q.rotate && !a.q.anchors) {
         if (a.q.dense) hipLaunchKernelGGL((encode_kernel<BITS, G, DT, IS_V, true, !kSplit>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
         else hipLaunchKernelGGL((encode_kernel<BITS, G, DT, IS_V, false, !kSplit>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
