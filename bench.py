@@ -197,7 +197,7 @@ def main():
     torch.cuda.synchronize()
     import ctypes
     handles = (ctypes.c_void_p * n_ev)(*[e.cuda_event for e in evs])
-    kvc.trace(handles, n_ev)
+    kvc.trace(plan, handles, n_ev)
 
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -205,7 +205,7 @@ def main():
         step()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    recorded = kvc.trace(None, 0)
+    recorded = kvc.trace(plan, None, 0)
     assert recorded == n_ev, recorded
     assert int(buf.status[0]) == 0
 

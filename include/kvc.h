@@ -12,7 +12,8 @@
  * Conventions, for every entry point:
  *  - plain C types only; pointers are HOST pointers unless the comment says DEVICE;
  *  - the caller owns every buffer; the library allocates no device memory and, apart from
- *    launching kernels on the caller's stream, performs no device synchronisation;
+ *    launching kernels on the caller's stream, performs no device synchronisation (the one
+ *    host-to-device copy of the library is in kvc_workspace_init);
  *  - all device pointers must be 16-byte aligned; strides are in elements (2 bytes);
  *  - errors the host can see are returned (negative kvc_status) before anything is
  *    launched; errors only the device can see (bad block-table entry, corrupt payload)
@@ -86,7 +87,8 @@ enum { KVC_CODEC_NONE = 0, KVC_CODEC_HUFF8 = 1 };
  *                     follow each other in (layer, head) order, each with its own width; the
  *                     tables travel in the payload's auxiliary section (K table, then V table).
  *                     Which head gets which width is the caller's choice.  Not with a codec.
- *                     A plan with tables needs a workspace (kvc_workspace_size).
+ *                     A plan with tables needs a workspace (kvc_workspace_size) that has been
+ *                     through kvc_workspace_init.
  * Every group carries two fp16 values (scale, zero): the 32 bits per group that cap
  * 2-bit / group-32 at 16/(2+1) = 5.33x (section 7.3).
  */
@@ -133,9 +135,13 @@ typedef struct {
 typedef struct kvc_plan_s kvc_plan_t;      /* opaque, host memory */
 
 /*
- * Validate a (model, strategy) pair and fix the limits the workspace is sized for.
- * Returns KVC_OK and a plan in *out (release with kvc_plan_free), or an error and
- * *out = NULL.  Touches no device.
+ * A plan is one profile in the sense of section 3.1: the strategy chosen for a request when its
+ * KV movement begins and held for the whole request, together with the model shape it applies to.
+ * Validates the (model, strategy) pair and fixes the limits the workspace is sized for
+ * (max_tokens per request, max_batch requests per call).  Returns KVC_OK and a plan in *out
+ * (host memory, release with kvc_plan_free), KVC_ERR_ARG for a value outside the format,
+ * KVC_ERR_UNSUPPORTED for one the format has and this build does not run; *out = NULL on error.
+ * Touches no device.  The plan copies the width tables; a plan may be used by one thread at a time.
  */
 int kvc_plan(const kvc_model *model, const kvc_strategy *strategy, int64_t max_tokens,
              int32_t max_batch, kvc_plan_t **out);
@@ -157,6 +163,19 @@ int kvc_payload_size(const kvc_plan_t *plan, int64_t tokens, uint64_t *bytes, in
 size_t kvc_workspace_size(const kvc_plan_t *plan);
 
 /*
+ * Plans with per-head width tables (section 5.1, head-wise mixed precision) keep a device image
+ * of the tables in the first kvc_table_bytes(plan) bytes of the workspace.  kvc_workspace_init
+ * writes it: one copy from pageable HOST memory on `hip_stream`, which may block the host until
+ * the copy is staged and cannot be captured into a graph.  Call it once per (plan, workspace)
+ * before the first kvc_compress / kvc_decompress, and again only if something else has written
+ * those bytes; the calls themselves leave them alone.  For plans without tables both functions
+ * do nothing (0 bytes).  Returns KVC_OK, KVC_ERR_ARG (null or misaligned workspace) or
+ * KVC_ERR_DEVICE.
+ */
+size_t kvc_table_bytes(const kvc_plan_t *plan);
+int kvc_workspace_init(const kvc_plan_t *plan, void *workspace, void *hip_stream);
+
+/*
  * Compress n requests (n <= max_batch, each tokens <= max_tokens) with the plan's strategy.
  *   payload      DEVICE buffer; request i's payload starts at payload + payload_off[i]
  *   payload_off  HOST, n+1 ascending multiples of 16; payload_off[i+1]-payload_off[i] must
@@ -173,17 +192,27 @@ int kvc_compress(const kvc_plan_t *plan, const kvc_request *reqs, int32_t n, voi
                  void *workspace, void *hip_stream);
 
 /*
- * Inverse: rebuild K and V of n requests into dst[i] (layout may differ from the sender's).
- * dst[i].tokens must equal the payload's token count; the device checks each header against
- * the plan and sets KVC_DEV_BAD_HEADER (writing nothing for that request) on a mismatch.
- * Reconstruction: x^ = round(code*scale + zero) in the model dtype.
+ * The decompression stage at the receiving end of a KV movement (section 4: ... Communication ->
+ * Decompression -> Decode), the inverse of BS = C(Q(T(X))) (section 5.1): rebuild K and V of n
+ * requests into dst[i] (DEVICE; the layout, contiguous or paged, may differ from the sender's).
+ *   payload / payload_off   as for kvc_compress; payload_off[i+1]-payload_off[i] must cover the
+ *                           payload (without the codec: kvc_payload_size; with it: at least the
+ *                           part before the code sections; the device checks the rest)
+ *   dst[i].tokens           must equal the payload's token count
+ *   dev_status, workspace, hip_stream   as for kvc_compress
+ * The device checks each header (and width table) against the plan and sets KVC_DEV_BAD_HEADER,
+ * writing nothing for that request, on a mismatch; a damaged table, directory or chunk sets
+ * KVC_DEV_BAD_TABLE / KVC_DEV_BAD_CHUNK and the affected chunks are not written.  Host-visible
+ * errors (KVC_ERR_ARG, KVC_ERR_CAPACITY) are returned before anything is launched.
+ * Reconstruction: x^ = round(code*scale + zero) in the model dtype, then the inverse of stage T.
  */
 int kvc_decompress(const kvc_plan_t *plan, const void *payload, const uint64_t *payload_off,
                    const kvc_request *dst, int32_t n, int32_t *dev_status, void *workspace,
                    void *hip_stream);
 
 /*
- * Decode a 128-byte payload header held in HOST memory.  sections[10] receives five
+ * The bitstream BS of section 5.1 describes itself: decode a 128-byte payload header held in
+ * HOST memory into the model shape and strategy that produced it.  sections[10] receives five
  * (offset, bytes) pairs: K meta, V meta, coder tables+directory, K codes, V codes.
  * Any output pointer may be NULL.  Returns KVC_ERR_FORMAT for a bad magic, version or
  * field combination.
@@ -195,13 +224,14 @@ int kvc_payload_inspect(const void *header128, kvc_model *model, kvc_strategy *s
 int kvc_check_block_table(const int32_t *table, int64_t entries, int32_t num_phys_blocks);
 
 /*
- * Measurement hook, for benchmarks only (process-global, not thread-safe).  While an array of
- * `capacity` hipEvent_t handles is installed, every kvc_compress / kvc_decompress records,
- * per request and on the call's stream, four events: before the set-up kernels (tables),
- * before the K kernel, between the K and V kernels, and after the V kernel.  Returns the
- * number of events recorded since the previous call; NULL uninstalls.
+ * Measurement hook, for benchmarks only.  While an array of `capacity` hipEvent_t handles (HOST
+ * array, owned by the caller) is installed in a plan, every kvc_compress / kvc_decompress with
+ * that plan records, per request and on the call's stream, four events: before the set-up work
+ * (for the first request of a call: before anything the call enqueues), before the K pass,
+ * between the K and V passes, and after the V pass.  Returns the number of events recorded
+ * since the previous call; NULL uninstalls.  The state lives in the plan.
  */
-int kvc_trace(void **hip_events, int32_t capacity);
+int kvc_trace(kvc_plan_t *plan, void **hip_events, int32_t capacity);
 
 /*
  * Device self-test of the quantizer's arithmetic shortcuts (stage Q of section 5.1 fixes the

@@ -172,8 +172,8 @@ void ref_group_meta(const float *x, int n, int bits, uint16_t *scale_h, uint16_t
 /*
  * Codes (reading): q = clamp(round_half_even((x - zero) * (1/scale)), 0, 2^bits-1) with the
  * stored (rounded) zero and scale, each arithmetic step one rounded fp32 operation; a zero
- * scale gives code 0 everywhere.  The integer decision is taken in fp32 because that is the
- * precision the GPU kernel takes it in.
+ * scale gives code 0 everywhere.  The paper fixes no precision for the integer decision; it is
+ * taken in fp32, the precision of the two operations that produce its argument.
  */
 void ref_group_quantize(const float *x, int n, int bits, uint16_t scale_h, uint16_t zero_h,
                         uint8_t *q)

@@ -20,7 +20,13 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 OUT = os.path.join(HERE, "libkvc.so")
-SOURCES = ["kvc_api.hip", "kvc_quant.hip", "kvc_huff.hip", "kvc_selftest.hip", "kvc_policy.hip"]
+WIDTHS = (2, 3, 4, 8)
+# (source, code width or None): the kernel sources are compiled once per code width, which spreads
+# the build over the cores; the slowest units come first
+JOBS = ([("kvc_huff_enc.hip", b) for b in WIDTHS] + [("kvc_quant.hip", b) for b in WIDTHS] +
+        [("kvc_huff_dec.hip", b) for b in WIDTHS] +
+        [("kvc_huff_tables.hip", None), ("kvc_selftest.hip", None), ("kvc_service.hip", None),
+         ("kvc_api.hip", None), ("kvc_policy.hip", None)])
 # packed fp32 instructions are switched off for the device pass (flag for hipcc only)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall",
@@ -59,14 +65,21 @@ def spilling_kernels(asm_path):
     return out
 
 
-def _compile(name):
-    obj = os.path.join(OBJ, name.replace(".hip", ".o"))
-    cmd = ["hipcc"] + FLAGS + ["-save-temps=obj", "-c", os.path.join(SRC, name), "-o", obj]
+def _compile(job):
+    name, width = job
+    stem = name.replace(".hip", "") + ("_b%d" % width if width else "")
+    # -save-temps names its files after the source, so every job works on a copy named after itself
+    src = os.path.join(OBJ, stem + ".hip")
+    with open(src, "w") as f:
+        f.write('#include "%s"\n' % os.path.join(SRC, name))
+    obj = os.path.join(OBJ, stem + ".o")
+    cmd = ["hipcc"] + FLAGS + (["-DKVC_BITS=%d" % width] if width else []) + ["-I", SRC, "-save-temps=obj", "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s" % (name, err))
-    asm = os.path.join(OBJ, name.replace(".hip", "-hip-amdgcn-amd-amdhsa-gfx950.s"))
+    name = stem
+    asm = os.path.join(OBJ, stem + "-hip-amdgcn-amd-amdhsa-gfx950.s")
     hits = shift_count_in_last_vgpr(asm)
     if hits:
         raise RuntimeError("%s: 64-bit shift with its count in the last allocated VGPR (give the kernel register "
@@ -75,7 +88,6 @@ def _compile(name):
     if spills:
         err += "\n%s: %d kernels spill registers (most: %d bytes per lane): %s" % (
             name, len(spills), max(n for _, n in spills), ", ".join(k for k, _ in spills[:6]))
-    stem = name.replace(".hip", "")
     for f in os.listdir(OBJ):                      # the temporaries are large and no longer needed
         if (f.startswith(stem + "-") or f.startswith(stem + ".hip-")) and f != stem + ".o":
             os.remove(os.path.join(OBJ, f))
@@ -84,8 +96,8 @@ def _compile(name):
 
 def build(verbose=False):
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=4) as ex:
-        results = list(ex.map(_compile, SOURCES))
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 4)) as ex:
+        results = list(ex.map(_compile, JOBS))
     if verbose:
         for _, err in results:
             if err.strip():

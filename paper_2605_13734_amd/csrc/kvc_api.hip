@@ -22,6 +22,9 @@ struct kvc_plan_s {
     uint8_t *blob;              // host image of the device tables, see table_layout
     size_t blob_bytes;          // multiple of 256; the workspace starts with a copy of it
     int width_count[2][4];      // heads per width 2, 3, 4, 8
+    // measurement hook (kvc_trace): events recorded between the stages of a call
+    hipEvent_t *trace;
+    int trace_cap, trace_n;
 };
 
 static const int kWidths[4] = {2, 3, 4, 8};
@@ -60,19 +63,19 @@ static int width_at(const kvc_plan_t *p, int is_v, long long lh)
 }
 
 // Optional measurement hook (kvc_trace): events recorded between the stages of a call.
-static hipEvent_t *g_trace = nullptr;
-static int g_trace_cap = 0, g_trace_n = 0;
-static void mark(hipStream_t s)
+static void mark(const kvc_plan_t *plan, hipStream_t s)
 {
-    if (g_trace && g_trace_n < g_trace_cap) hipEventRecord(g_trace[g_trace_n++], s);
+    kvc_plan_t *p = const_cast<kvc_plan_t *>(plan);
+    if (p->trace && p->trace_n < p->trace_cap && hipEventRecord(p->trace[p->trace_n], s) == hipSuccess) ++p->trace_n;
 }
 
-extern "C" int kvc_trace(void **hip_events, int32_t capacity)
+extern "C" int kvc_trace(kvc_plan_t *plan, void **hip_events, int32_t capacity)
 {
-    const int recorded = g_trace_n;
-    g_trace = (hipEvent_t *)hip_events;
-    g_trace_cap = hip_events ? capacity : 0;
-    g_trace_n = 0;
+    if (!plan) return 0;
+    const int recorded = plan->trace_n;
+    plan->trace = (hipEvent_t *)hip_events;
+    plan->trace_cap = hip_events ? capacity : 0;
+    plan->trace_n = 0;
     return recorded;
 }
 
@@ -460,12 +463,15 @@ static int launch_tensor(const kvc_plan_t *p, int is_v, bool compress, QuantArgs
     return KVC_OK;
 }
 
-// The plan's device tables at the start of the workspace (every call brings them again: the
-// workspace belongs to the caller between calls).
-static int upload_tables(const kvc_plan_t *p, void *workspace, hipStream_t s)
+extern "C" size_t kvc_table_bytes(const kvc_plan_t *plan) { return plan ? plan->blob_bytes : 0; }
+
+extern "C" int kvc_workspace_init(const kvc_plan_t *plan, void *workspace, void *hip_stream)
 {
-    if (!p->blob_bytes) return KVC_OK;
-    return hipMemcpyAsync(workspace, p->blob, p->blob_bytes, hipMemcpyHostToDevice, s) == hipSuccess ? KVC_OK : KVC_ERR_DEVICE;
+    if (!plan) return KVC_ERR_ARG;
+    if (!plan->blob_bytes) return KVC_OK;
+    if (!workspace || ((uintptr_t)workspace & 15)) return KVC_ERR_ARG;
+    return hipMemcpyAsync(workspace, plan->blob, plan->blob_bytes, hipMemcpyHostToDevice, (hipStream_t)hip_stream) == hipSuccess
+               ? KVC_OK : KVC_ERR_DEVICE;
 }
 
 static CoderArgs coder_args(const kvc_plan_t *p, const QuantArgs &q, int is_v, uint8_t *payload,
@@ -512,9 +518,12 @@ static int check_batch(const kvc_plan_t *p, const kvc_request *reqs, int32_t n, 
 
 #define KVC_TRY(expr) do { int rc__ = (expr); if (rc__ != KVC_OK) return rc__; } while (0)
 
-extern "C" int kvc_compress(const kvc_plan_t *plan, const kvc_request *reqs, int32_t n, void *payload,
-                            const uint64_t *payload_off, uint64_t *out_bytes, int32_t *dev_status,
-                            void *workspace, void *hip_stream)
+// The launch sequence of kvc_compress on a given workspace (the caller's, or the library's own
+// static one): one service launch for all requests, then per request the coder's tables and one
+// pass per tensor.
+static int compress_on(const kvc_plan_t *plan, const kvc_request *reqs, int32_t n, void *payload,
+                       const uint64_t *payload_off, uint64_t *out_bytes, int32_t *dev_status,
+                       void *workspace, hipStream_t s)
 {
     KVC_TRY(check_batch(plan, reqs, n, payload, payload_off, workspace));
     if (!out_bytes || !dev_status || ((uintptr_t)out_bytes & 7) || ((uintptr_t)dev_status & 3)) return KVC_ERR_ARG;
@@ -523,67 +532,93 @@ extern "C" int kvc_compress(const kvc_plan_t *plan, const kvc_request *reqs, int
         geometry(plan, reqs[i].tokens, &g);
         if (payload_off[i + 1] - payload_off[i] < (uint64_t)g.total) return KVC_ERR_CAPACITY;
     }
-    hipStream_t s = (hipStream_t)hip_stream;
     const kvc_strategy &st = plan->strat;
     const int dt = plan->model.dtype;
-    KVC_TRY(launch_fill_u32((uint32_t *)dev_status, 0, n, s));
-    KVC_TRY(upload_tables(plan, workspace, s));
+    mark(plan, s);
+    for (int first = 0; first < n; first += kPrologueBatch) {
+        PrologueArgs pa;
+        memset(&pa, 0, sizeof pa);
+        pa.n = n - first < kPrologueBatch ? n - first : kPrologueBatch;
+        for (int j = 0; j < pa.n; ++j) {
+            const int i = first + j;
+            Geometry g;
+            geometry(plan, reqs[i].tokens, &g);
+            uint8_t *pl = (uint8_t *)payload + payload_off[i];
+            PrologueItem &it = pa.item[j];
+            it.payload = (uint32_t *)pl;
+            make_header(plan, reqs[i].tokens, g, &it.header);
+            // alignment padding after the V metadata and after the coder's or the width tables is zero
+            it.pad_off[0] = g.off_meta_v + g.meta_v;
+            it.pad_words[0] = (a16(g.meta_v) - g.meta_v) / 4;
+            it.pad_off[1] = g.off_aux + g.aux_base;
+            it.pad_words[1] = (a16(g.aux_base) - g.aux_base) / 4;
+            if (plan->blob_bytes) {
+                // the width tables and their padding: a copy of the image at the start of the workspace
+                it.aux_src = (const uint32_t *)workspace;
+                it.aux_off = g.off_aux;
+                it.aux_words = a16(g.aux_base) / 4;
+                it.pad_words[1] = 0;
+            }
+            it.out_bytes = (unsigned long long *)(out_bytes + i);
+            it.status = dev_status + i;
+            if (!st.codec) {
+                it.total = (unsigned long long)g.total;
+                it.write_total = 1;
+            } else {
+                uint8_t *ws = (uint8_t *)workspace + plan->blob_bytes + (size_t)i * plan->ws_request;
+                CoderArgs c = coder_args(plan, QuantArgs(), 0, pl, g, ws, 0, nullptr);
+                // histograms, ticket and scan state start from zero
+                it.zero[0] = c.ws.hist;
+                it.zero_words[0] = 2 * 256;
+                it.zero[1] = c.ws.ticket;
+                it.zero_words[1] = 64 + 2 * c.total_wgs + 2;
+                if (c.total_chunks == 0) {
+                    // empty request: no workgroup runs that could close the directory and header
+                    put64((uint8_t *)it.header.w + 40, (uint64_t)g.off_codes_k);
+                    put64((uint8_t *)it.header.w + 112, (uint64_t)g.off_codes_k);
+                    it.dir0 = (uint32_t *)(pl + g.off_aux + 512);
+                    it.total = (unsigned long long)g.off_codes_k;
+                    it.write_total = 1;
+                }
+            }
+        }
+        KVC_TRY(launch_compress_prologue(pa, s));
+    }
     for (int i = 0; i < n; ++i) {
         const kvc_request *r = &reqs[i];
         Geometry g;
         geometry(plan, r->tokens, &g);
         uint8_t *pl = (uint8_t *)payload + payload_off[i];
-        HeaderBytes hb;
-        make_header(plan, r->tokens, g, &hb);
-        KVC_TRY(launch_write_header(pl, hb, s));
-        // alignment padding after the V metadata and after the coder tables is zero
-        if (a16(g.meta_v) != g.meta_v)
-            KVC_TRY(launch_fill_u32((uint32_t *)(pl + g.off_meta_v + g.meta_v), 0, (a16(g.meta_v) - g.meta_v) / 4, s));
-        if (plan->blob_bytes) {
-            // the width tables and their padding: a device copy of the image at the start of the workspace
-            if (hipMemcpyAsync(pl + g.off_aux, workspace, (size_t)a16(g.aux_base), hipMemcpyDeviceToDevice, s) != hipSuccess)
-                return KVC_ERR_DEVICE;
-        } else if (a16(g.aux_base) != g.aux_base)
-            KVC_TRY(launch_fill_u32((uint32_t *)(pl + g.off_aux + g.aux_base), 0, (a16(g.aux_base) - g.aux_base) / 4, s));
         QuantArgs qk = quant_args(plan, r, 0, pl, g, dev_status + i, true);
         QuantArgs qv = quant_args(plan, r, 1, pl, g, dev_status + i, true);
+        if (i > 0) mark(plan, s);
         if (!st.codec) {
-            mark(s);
-            mark(s);
+            mark(plan, s);
             KVC_TRY(launch_tensor(plan, 0, true, qk, (const uint8_t *)workspace, s));
-            mark(s);
+            mark(plan, s);
             KVC_TRY(launch_tensor(plan, 1, true, qv, (const uint8_t *)workspace, s));
-            mark(s);
-            KVC_TRY(launch_fill_u32((uint32_t *)(out_bytes + i), (uint32_t)g.total, 1, s));
-            KVC_TRY(launch_fill_u32((uint32_t *)(out_bytes + i) + 1, (uint32_t)((uint64_t)g.total >> 32), 1, s));
+            mark(plan, s);
         } else {
             uint8_t *ws = (uint8_t *)workspace + plan->blob_bytes + (size_t)i * plan->ws_request;
             const long long cap = (long long)(payload_off[i + 1] - payload_off[i]);
             CoderArgs ck = coder_args(plan, qk, 0, pl, g, ws, cap, out_bytes + i);
             CoderArgs cv = coder_args(plan, qv, 1, pl, g, ws, cap, out_bytes + i);
-            // histograms, ticket and scan state start from zero
-            KVC_TRY(launch_fill_u32((uint32_t *)ws, 0, 2 * 256, s));
-            KVC_TRY(launch_fill_u32(ck.ws.ticket, 0, 64, s));
-            KVC_TRY(launch_fill_u32((uint32_t *)ck.ws.state, 0, 2 * ck.total_wgs + 2, s));
-            mark(s);
             KVC_TRY(launch_coder_tables(st.bits_k, st.bits_v, st.group_k, st.group_v, dt, ck, cv, s));
-            mark(s);
+            mark(plan, s);
             KVC_TRY(launch_encode_section(st.bits_k, st.group_k, dt, ck, s));
-            mark(s);
+            mark(plan, s);
             KVC_TRY(launch_encode_section(st.bits_v, st.group_v, dt, cv, s));
-            mark(s);
-            if (ck.total_chunks == 0) {
-                // empty request: no workgroup runs that could close the directory and header
-                put64((uint8_t *)hb.w + 40, (uint64_t)g.off_codes_k);
-                put64((uint8_t *)hb.w + 112, (uint64_t)g.off_codes_k);
-                KVC_TRY(launch_write_header(pl, hb, s));
-                KVC_TRY(launch_fill_u32((uint32_t *)(pl + g.off_aux + 512), 0, 1, s));
-                KVC_TRY(launch_fill_u32((uint32_t *)(out_bytes + i), (uint32_t)g.off_codes_k, 1, s));
-                KVC_TRY(launch_fill_u32((uint32_t *)(out_bytes + i) + 1, 0, 1, s));
-            }
+            mark(plan, s);
         }
     }
     return KVC_OK;
+}
+
+extern "C" int kvc_compress(const kvc_plan_t *plan, const kvc_request *reqs, int32_t n, void *payload,
+                            const uint64_t *payload_off, uint64_t *out_bytes, int32_t *dev_status,
+                            void *workspace, void *hip_stream)
+{
+    return compress_on(plan, reqs, n, payload, payload_off, out_bytes, dev_status, workspace, (hipStream_t)hip_stream);
 }
 
 extern "C" int kvc_decompress(const kvc_plan_t *plan, const void *payload, const uint64_t *payload_off,
@@ -592,48 +627,64 @@ extern "C" int kvc_decompress(const kvc_plan_t *plan, const void *payload, const
 {
     KVC_TRY(check_batch(plan, dst, n, payload, payload_off, workspace));
     if (!dev_status || ((uintptr_t)dev_status & 3)) return KVC_ERR_ARG;
-    for (int i = 0; i < n; ++i)
-        if (payload_off[i + 1] - payload_off[i] < kHeader) return KVC_ERR_CAPACITY;
-    hipStream_t s = (hipStream_t)hip_stream;
     const kvc_strategy &st = plan->strat;
+    for (int i = 0; i < n; ++i) {
+        Geometry g;
+        geometry(plan, dst[i].tokens, &g);
+        const long long cap = (long long)(payload_off[i + 1] - payload_off[i]);
+        if (cap < kHeader || (!st.codec && cap < g.total) || (st.codec && cap < g.off_codes_k)) return KVC_ERR_CAPACITY;
+    }
+    hipStream_t s = (hipStream_t)hip_stream;
     const int dt = plan->model.dtype;
-    KVC_TRY(launch_fill_u32((uint32_t *)dev_status, 0, n, s));
-    KVC_TRY(upload_tables(plan, workspace, s));
+    mark(plan, s);
+    for (int first = 0; first < n; first += kCheckBatch) {
+        CheckArgs ca;
+        memset(&ca, 0, sizeof ca);
+        ca.n = n - first < kCheckBatch ? n - first : kCheckBatch;
+        for (int j = 0; j < ca.n; ++j) {
+            const int i = first + j;
+            Geometry g;
+            geometry(plan, dst[i].tokens, &g);
+            const uint8_t *pl = (const uint8_t *)payload + payload_off[i];
+            CheckItem &it = ca.item[j];
+            it.payload = (const uint32_t *)pl;
+            make_header(plan, dst[i].tokens, g, &it.expect);
+            // words 10/11 (total), 26..31 (code sizes) depend on the data when the coder is on
+            it.mask = st.codec ? 0x03fff3ffu : 0xffffffffu;
+            if (plan->blob_bytes) {       // the payload's width tables must be the plan's
+                it.tables = pl + g.off_aux;
+                it.plan_tables = (const uint8_t *)workspace;
+                it.table_bytes = g.aux_base;
+            }
+            it.status = dev_status + i;
+        }
+        KVC_TRY(launch_decompress_prologue(ca, s));
+    }
     for (int i = 0; i < n; ++i) {
         const kvc_request *r = &dst[i];
         Geometry g;
         geometry(plan, r->tokens, &g);
         uint8_t *pl = (uint8_t *)payload + payload_off[i];
         const long long cap = (long long)(payload_off[i + 1] - payload_off[i]);
-        if (!st.codec && cap < g.total) return KVC_ERR_CAPACITY;
-        if (st.codec && cap < g.off_codes_k) return KVC_ERR_CAPACITY;
-        HeaderBytes hb;
-        make_header(plan, r->tokens, g, &hb);
-        // words 10/11 (total), 26..31 (code sizes) depend on the data when the coder is on
-        const uint32_t mask = st.codec ? 0x03fff3ffu : 0xffffffffu;
-        KVC_TRY(launch_check_header(pl, hb, mask, dev_status + i, s));
-        if (plan->blob_bytes)       // the payload's width tables must be the plan's
-            KVC_TRY(launch_check_bytes(pl + g.off_aux, (const uint8_t *)workspace, g.aux_base, dev_status + i, s));
         QuantArgs qk = quant_args(plan, r, 0, pl, g, dev_status + i, false);
         QuantArgs qv = quant_args(plan, r, 1, pl, g, dev_status + i, false);
+        if (i > 0) mark(plan, s);
         if (!st.codec) {
-            mark(s);
-            mark(s);
+            mark(plan, s);
             KVC_TRY(launch_tensor(plan, 0, false, qk, (const uint8_t *)workspace, s));
-            mark(s);
+            mark(plan, s);
             KVC_TRY(launch_tensor(plan, 1, false, qv, (const uint8_t *)workspace, s));
-            mark(s);
+            mark(plan, s);
         } else {
             uint8_t *ws = (uint8_t *)workspace + plan->blob_bytes + (size_t)i * plan->ws_request;
             CoderArgs ck = coder_args(plan, qk, 0, pl, g, ws, cap, nullptr);
             CoderArgs cv = coder_args(plan, qv, 1, pl, g, ws, cap, nullptr);
-            mark(s);
             KVC_TRY(launch_decode_prepare(ck, s));
-            mark(s);
+            mark(plan, s);
             KVC_TRY(launch_decode_section(st.bits_k, st.group_k, dt, ck, s));
-            mark(s);
+            mark(plan, s);
             KVC_TRY(launch_decode_section(st.bits_v, st.group_v, dt, cv, s));
-            mark(s);
+            mark(plan, s);
         }
     }
     return KVC_OK;

@@ -1,0 +1,299 @@
+// Lossless stage, set-up kernels: the table sample (byte histogram of up to 16 chunks per section),
+// the code construction (Huffman lengths, canonical codes) and the decode tables.  See kvc_huff.h.
+
+#include "kvc_huff.h"
+
+namespace kvc {
+
+// ---- table sample: histogram of up to 16 chunks per section ------------------------------------
+
+template <int BITS, int G, int DT, bool IS_V>
+__global__ __launch_bounds__(64) void hist_kernel(CoderArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t lds[ChunkGeom<BITS>::kLds];
+    __shared__ uint32_t hist[256];
+    const int i = blockIdx.x, lane = lane_id();
+    const long long n = a.chunks;
+    const long long chunk = (long long)i * n / 16;
+    if (i > 0 && (long long)(i - 1) * n / 16 == chunk) return;      // each chunk counted once
+    for (int k = lane; k < 256; k += 64) hist[k] = 0;
+    ChunkPos c = chunk_pos(a.q, chunk);
+    bool bad = false;
+    quantize_chunk<BITS, G, DT, IS_V, false>(a.q, c, lds, false, bad);
+    wave_sync();
+    constexpr int W = ChunkGeom<BITS>::kWords;
+    uint32_t sym[W];
+    load_sub<BITS>(lds, sym);
+    const int valid = min(max(c.rows - 2 * lane, 0), 2) * (W / 2);
+#pragma unroll
+    for (int k = 0; k < W; ++k)
+        if (k < valid) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) atomicAdd(&hist[(sym[k] >> (8 * b)) & 255u], 1u);
+        }
+    wave_sync();
+    uint32_t *g = a.ws.hist + (IS_V ? 256 : 0);
+    for (int k = lane; k < 256; k += 64)
+        if (hist[k]) atomicAdd(&g[k], hist[k]);
+}
+
+// ---- code construction (one wave per section) ---------------------------------------------------
+
+// Huffman code lengths of 256 symbols from weights w[] (LDS), joining the two nodes with the
+// smallest (weight, id) each time: leaves have id = symbol, the k-th joined node id 256 + k.
+// Leaves sorted by (weight, symbol) form one queue, joined nodes (created in non-decreasing
+// weight order) the other; the heads of the two queues are the two candidates.  The joining
+// itself is sequential (lane 0): it keeps the two front weights of either queue in registers
+// and reads one position ahead, so that no step waits for LDS.  Weights stay far below 2^32
+// (a table sample is at most 16 chunks of 16 KB).
+struct BuildLds {
+    uint32_t w[256];               // leaf weights by symbol
+    uint32_t sw[258];              // leaf weights in queue order, then two sentinels
+    uint32_t wi[256];              // weights of the joined nodes, in order of creation
+    uint16_t parent_leaf[256];     // by queue position: index of the joined node above the leaf
+    uint16_t parent_int[256];      // by joined node: index of the joined node above it
+    uint8_t len[256];
+    uint32_t count[16], first[16], start[16];
+    uint16_t by_len[256];          // symbols by (length, symbol)
+    int longest;
+};
+
+// Code lengths from the weights s.w[], by a workgroup of 256 threads (one symbol each): Huffman's
+// algorithm with two queues, a leaf before a joined node of the same weight and the lower symbol
+// first among equal leaves; while the longest code exceeds kMaxLen all weights are halved (rounded
+// up) and the construction is repeated.  Sorting, depths and halving are spread over the threads;
+// the 255 joins are one thread's work.
+__device__ __forceinline__ void build_lengths(BuildLds &s)
+{
+    constexpr uint32_t kNone = 0xffffffffu;
+    const int tid = threadIdx.x;
+    for (;;) {
+        // position of the thread's leaf among all leaves
+        const uint32_t wk = s.w[tid];
+        int pos = 0;
+        for (int t = 0; t < 256; ++t) {
+            const uint32_t wt = s.w[t];
+            pos += (wt < wk || (wt == wk && t < tid)) ? 1 : 0;
+        }
+        s.sw[pos] = wk;
+        if (tid < 2) s.sw[256 + tid] = kNone;
+        if (tid == 0) s.longest = 0;
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t wl = s.sw[0], wl1 = s.sw[1];      // front of the leaf queue and the one behind it
+            uint32_t wj = kNone, wj1 = kNone;          // same for the queue of joined nodes
+            int lq = 0, jq = 0, made = 0;
+            for (int k = 0; k < 255; ++k) {
+                uint32_t sum = 0;
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    if (wl <= wj) {                    // a leaf wins a tie: its id is lower
+                        sum += wl;
+                        s.parent_leaf[lq] = (uint16_t)made;
+                        ++lq;
+                        wl = wl1;
+                        wl1 = s.sw[lq + 1];
+                    } else {
+                        sum += wj;
+                        s.parent_int[jq] = (uint16_t)made;
+                        ++jq;
+                        wj = wj1;
+                        wj1 = jq + 1 < made ? s.wi[jq + 1] : kNone;
+                    }
+                }
+                s.wi[made] = sum;
+                if (made == jq) wj = sum;
+                else if (made == jq + 1) wj1 = sum;
+                ++made;
+            }
+        }
+        __syncthreads();
+        int d = 1;
+        for (int i = s.parent_leaf[pos]; i != 254 && d < 256; i = s.parent_int[i]) ++d;
+        s.len[tid] = (uint8_t)d;
+        atomicMax(&s.longest, d);
+        __syncthreads();
+        if (s.longest <= kMaxLen) return;
+        const uint32_t v = (wk + 1) >> 1;
+        __syncthreads();                               // everyone has seen `longest` before it is cleared
+        s.w[tid] = v < 1 ? 1 : v;
+        __syncthreads();
+    }
+}
+
+constexpr int kTableWaves = 8;      // waves that fill a decode table
+
+// grid = 2 workgroups of 256 threads (one symbol each): 0 builds the K table, 1 the V table
+__global__ __launch_bounds__(256) void build_tables_kernel(CoderArgs a)
+{
+    __shared__ BuildLds s;
+    __shared__ uint32_t block_count[4][16];            // symbols of each length in each block of 64 symbols
+    const int sec = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
+    s.w[tid] = a.ws.hist[256 * sec + tid] + 1;
+    __syncthreads();
+    build_lengths(s);
+    // canonical codes: first code of every length, and the symbol's place among the symbols of
+    // its length (those of lower blocks, then the lower lanes of its own block)
+    const int L = s.len[tid];
+    int within = 0;
+#pragma unroll
+    for (int l = 1; l <= kMaxLen; ++l) {
+        const unsigned long long same = __builtin_amdgcn_ballot_w64(L == l);
+        if (lane == 0) block_count[wave][l] = (uint32_t)__builtin_popcountll(same);
+        if (L == l) within = __builtin_popcountll(same & ((1ull << lane) - 1));
+    }
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t next = 0;
+        for (int l = 1; l <= kMaxLen; ++l) {
+            s.first[l] = next;
+            next = (next + block_count[0][l] + block_count[1][l] + block_count[2][l] + block_count[3][l]) << 1;
+        }
+    }
+    __syncthreads();
+    uint32_t rank = (uint32_t)within;
+    for (int w = 0; w < wave; ++w) rank += block_count[w][L];
+    a.payload[a.off_aux + 256 * sec + tid] = (uint8_t)L;
+    a.ws.enc[256 * sec + tid] = (s.first[L] + rank) | ((uint32_t)L << 16);
+}
+
+// grid = 2 workgroups of kTableWaves waves: decode tables from the lengths stored in the payload
+__global__ __launch_bounds__(kTableWaves * 64) void decode_prepare_kernel(CoderArgs a)
+{
+    __shared__ BuildLds s;
+    __shared__ uint32_t block_count[4][16];            // symbols of each length in each block of 64 symbols
+    __shared__ int s_ok;
+    const int sec = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
+    if (*a.q.status & KVC_DEV_BAD_HEADER) return;
+    // canonical order: the first four waves hold one symbol per thread
+    int mylen = 0, within = 0;
+    if (tid < 256) {
+        mylen = a.payload[a.off_aux + 256 * sec + tid];
+#pragma unroll
+        for (int l = 1; l <= kMaxLen; ++l) {
+            const unsigned long long same = __builtin_amdgcn_ballot_w64(mylen == l);
+            if (lane == 0) block_count[wave][l] = (uint32_t)__builtin_popcountll(same);
+            if (mylen == l) within = __builtin_popcountll(same & ((1ull << lane) - 1));
+        }
+        const bool in_range = mylen >= 1 && mylen <= kMaxLen;
+        if (lane == 0) block_count[wave][0] = __builtin_amdgcn_ballot_w64(!in_range) != 0 ? 1u : 0u;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t next = 0, at = 0, kraft = 0;
+        for (int l = 1; l <= kMaxLen; ++l) {
+            const uint32_t n = block_count[0][l] + block_count[1][l] + block_count[2][l] + block_count[3][l];
+            s.count[l] = n;
+            s.first[l] = next;
+            s.start[l] = at;
+            next = (next + n) << 1;
+            at += n;
+            kraft += n << (kMaxLen - l);
+        }
+        const bool bad_len = (block_count[0][0] | block_count[1][0] | block_count[2][0] | block_count[3][0]) != 0;
+        const bool ok = !bad_len && kraft == (1u << kMaxLen);          // a complete prefix code
+        s_ok = ok ? 1 : 0;
+        if (!ok) atomicOr(a.q.status, KVC_DEV_BAD_TABLE);
+    }
+    __syncthreads();
+    if (s_ok && tid < 256) {
+        uint32_t rank = (uint32_t)within;
+        for (int w = 0; w < wave; ++w) rank += block_count[w][mylen];
+        s.by_len[s.start[mylen] + rank] = (uint16_t)tid;                    // symbols by (length, symbol)
+    }
+    __syncthreads();
+    uint16_t *lut = a.ws.lut + 4096 * sec;
+    if (!s_ok) {
+        for (int i = tid; i < 4096; i += kTableWaves * 64) lut[i] = (uint16_t)(1u << 8);      // symbol 0, length 1
+        return;
+    }
+    // entry i describes the code word that is a prefix of the 12-bit string i
+    for (int i = tid; i < 4096; i += kTableWaves * 64) {
+        uint16_t e = (uint16_t)(1u << 8);
+        for (int L = 1; L <= kMaxLen; ++L) {
+            const uint32_t c = (uint32_t)i >> (kMaxLen - L);
+            if (c >= s.first[L] && c - s.first[L] < s.count[L]) {
+                e = (uint16_t)(s.by_len[s.start[L] + c - s.first[L]] | (L << 8));
+                break;
+            }
+        }
+        lut[i] = e;
+    }
+}
+
+// ---- launchers ----------------------------------------------------------------------------------
+
+template <int BITS, int G, int DT, bool IS_V> static int hist_launch(const CoderArgs &a, hipStream_t s)
+{
+    if (a.chunks <= 0) return KVC_OK;
+    hipLaunchKernelGGL((hist_kernel<BITS, G, DT, IS_V>), dim3(16), dim3(64), 0, s, a);
+    return launched();
+}
+
+template <int BITS, int DT, bool ISV> static int hist_g(int group, const CoderArgs &a, hipStream_t s)
+{
+    switch (group) {
+    case 32: return hist_launch<BITS, 32, DT, ISV>(a, s);
+    case 64: return hist_launch<BITS, 64, DT, ISV>(a, s);
+    case 128: return hist_launch<BITS, 128, DT, ISV>(a, s);
+    }
+    return KVC_ERR_UNSUPPORTED;
+}
+
+template <int BITS, bool ISV> static int hist_d(int group, int dtype, const CoderArgs &a, hipStream_t s)
+{
+    return dtype == DT_F16 ? hist_g<BITS, DT_F16, ISV>(group, a, s) : hist_g<BITS, DT_BF16, ISV>(group, a, s);
+}
+
+template <bool ISV> static int hist_b(int bits, int group, int dtype, const CoderArgs &a, hipStream_t s)
+{
+    switch (bits) {
+    case 2: return hist_d<2, ISV>(group, dtype, a, s);
+    case 3: return hist_d<3, ISV>(group, dtype, a, s);
+    case 4: return hist_d<4, ISV>(group, dtype, a, s);
+    case 8: return hist_d<8, ISV>(group, dtype, a, s);
+    }
+    return KVC_ERR_UNSUPPORTED;
+}
+
+int launch_coder_tables(int bits_k, int bits_v, int group_k, int group_v, int dtype, const CoderArgs &k,
+                        const CoderArgs &v, hipStream_t s)
+{
+    int rc = hist_b<false>(bits_k, group_k, dtype, k, s);
+    if (rc) return rc;
+    rc = hist_b<true>(bits_v, group_v, dtype, v, s);
+    if (rc) return rc;
+    hipLaunchKernelGGL(build_tables_kernel, dim3(2), dim3(256), 0, s, k);
+    return launched();
+}
+
+int launch_decode_prepare(const CoderArgs &k, hipStream_t s)
+{
+    hipLaunchKernelGGL(decode_prepare_kernel, dim3(2), dim3(kTableWaves * 64), 0, s, k);
+    return launched();
+}
+
+int launch_encode_section(int bits, int group, int dtype, const CoderArgs &a, hipStream_t s)
+{
+    switch (bits) {
+    case 2: return launch_encode_bits2(group, dtype, a, s);
+    case 3: return launch_encode_bits3(group, dtype, a, s);
+    case 4: return launch_encode_bits4(group, dtype, a, s);
+    case 8: return launch_encode_bits8(group, dtype, a, s);
+    }
+    return KVC_ERR_UNSUPPORTED;
+}
+
+int launch_decode_section(int bits, int group, int dtype, const CoderArgs &a, hipStream_t s)
+{
+    (void)group;
+    switch (bits) {
+    case 2: return launch_decode_bits2(dtype, a, s);
+    case 3: return launch_decode_bits3(dtype, a, s);
+    case 4: return launch_decode_bits4(dtype, a, s);
+    case 8: return launch_decode_bits8(dtype, a, s);
+    }
+    return KVC_ERR_UNSUPPORTED;
+}
+
+}  // namespace kvc

@@ -45,12 +45,51 @@ struct HeaderBytes { uint32_t w[32]; };
 
 int launch_compress_tensor(int is_v, int bits, int group, int dtype, const QuantArgs &a, hipStream_t s);
 int launch_decompress_tensor(int is_v, int bits, int group, int dtype, const QuantArgs &a, hipStream_t s);
-int launch_write_header(uint8_t *dst, const HeaderBytes &h, hipStream_t s);
-// Compare a payload header with the one the plan implies; `mask` bit i = compare word i.
-int launch_check_header(const uint8_t *hdr, const HeaderBytes &expect, uint32_t mask, int *status,
-                        hipStream_t s);
+// one translation unit per code width (kvc_quant.hip compiled with -DKVC_BITS=...)
+#define KVC_DECLARE_QUANT(B)                                                                              \
+    int launch_compress_bits##B(int is_v, int group, int dtype, const QuantArgs &a, hipStream_t s);      \
+    int launch_decompress_bits##B(int is_v, int dtype, const QuantArgs &a, hipStream_t s);
+KVC_DECLARE_QUANT(2) KVC_DECLARE_QUANT(3) KVC_DECLARE_QUANT(4) KVC_DECLARE_QUANT(8)
+#undef KVC_DECLARE_QUANT
+// Service work of one request before its tensors are compressed (see compress_prologue_kernel).
+struct PrologueItem {
+    uint32_t *payload;              // request payload base
+    HeaderBytes header;
+    long long pad_off[2], pad_words[2];     // zero padding: byte offset inside the payload, 32-bit words
+    const uint32_t *aux_src;        // device image of the width tables, copied to payload + aux_off
+    long long aux_off, aux_words;
+    uint32_t *zero[2];              // coder scratch that starts from zero: histograms; ticket and scan state
+    long long zero_words[2];
+    unsigned long long *out_bytes;  // the request's size word
+    unsigned long long total;
+    int write_total;                // the size is known on the host (no coder, or an empty request)
+    uint32_t *dir0;                 // empty request with the coder: the directory's only entry
+    int *status;
+};
+constexpr int kPrologueBatch = 12;  // requests per launch (the argument block stays below 4 KB)
+struct PrologueArgs {
+    PrologueItem item[kPrologueBatch];
+    int n;
+};
+
+// Header (and width table) check of one request before it is decompressed.
+struct CheckItem {
+    const uint32_t *payload;
+    HeaderBytes expect;
+    uint32_t mask;                  // bit i = compare header word i
+    const uint8_t *tables, *plan_tables;    // width tables in the payload and their device image
+    long long table_bytes;
+    int *status;
+};
+constexpr int kCheckBatch = 20;
+struct CheckArgs {
+    CheckItem item[kCheckBatch];
+    int n;
+};
+
+int launch_compress_prologue(const PrologueArgs &a, hipStream_t s);
+int launch_decompress_prologue(const CheckArgs &a, hipStream_t s);
 int launch_fill_u32(uint32_t *dst, uint32_t value, long long n, hipStream_t s);
-int launch_check_bytes(const uint8_t *a, const uint8_t *b, long long n, int *status, hipStream_t s);
 
 // ---- lossless stage (codec 1) -----------------------------------------------------------
 
@@ -84,5 +123,11 @@ int launch_coder_tables(int bits_k, int bits_v, int group_k, int group_v, int dt
 int launch_encode_section(int bits, int group, int dtype, const CoderArgs &a, hipStream_t s);
 int launch_decode_prepare(const CoderArgs &k, hipStream_t s);
 int launch_decode_section(int bits, int group, int dtype, const CoderArgs &a, hipStream_t s);
+// one translation unit per code width (kvc_huff_enc.hip / kvc_huff_dec.hip compiled with -DKVC_BITS=...)
+#define KVC_DECLARE_CODER(B)                                                                  \
+    int launch_encode_bits##B(int group, int dtype, const CoderArgs &a, hipStream_t s);       \
+    int launch_decode_bits##B(int dtype, const CoderArgs &a, hipStream_t s);
+KVC_DECLARE_CODER(2) KVC_DECLARE_CODER(3) KVC_DECLARE_CODER(4) KVC_DECLARE_CODER(8)
+#undef KVC_DECLARE_CODER
 
 }  // namespace kvc

@@ -1,0 +1,50 @@
+// Shared pieces of the codec-free kernels: work-unit addressing and the launch helper.
+// One wave per work unit, four units per workgroup.
+#pragma once
+
+#include "kvc_internal.h"
+#include "kvc_tile.h"
+#include "../../include/kvc.h"
+
+namespace kvc {
+
+struct UnitPos {
+    long long lh;        // layer * heads + head
+    long long blk;       // unit index inside the head
+    long long head_off;  // element offset of x[l][h][0][0]
+};
+
+__device__ __forceinline__ bool unit_pos(const QuantArgs &a, UnitPos &u)
+{
+    long long unit = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (unit >= a.total_units) return false;
+    const long long slot = unit / a.units_per_head;
+    u.lh = a.head_list ? a.head_list[slot] : slot;
+    u.blk = unit - slot * a.units_per_head;
+    long long l = u.lh / a.heads, h = u.lh - l * a.heads;
+    u.head_off = l * a.x.stride_layer + h * a.x.stride_head;
+    return true;
+}
+
+// first code byte of head lh (width BITS) in its section
+template <int BITS> __device__ __forceinline__ uint8_t *head_codes(const QuantArgs &a, long long lh)
+{
+    const long long widths = a.bits_before ? a.bits_before[lh] : lh * BITS;
+    return a.codes + widths * a.tokens * 16;
+}
+
+__device__ __forceinline__ void report(int *status, bool bad)
+{
+    if (bad) atomicOr(status, KVC_DEV_BAD_BLOCK);
+}
+
+static inline dim3 grid_for(long long units) { return dim3((unsigned)((units + 3) / 4)); }
+
+#define KVC_LAUNCH(kernel, a, s)                                                        \
+    do {                                                                                \
+        if ((a).total_units > 0)                                                        \
+            hipLaunchKernelGGL(kernel, grid_for((a).total_units), dim3(256), 0, s, a);  \
+        return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_DEVICE;               \
+    } while (0)
+
+}  // namespace kvc

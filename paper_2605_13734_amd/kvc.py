@@ -17,7 +17,7 @@ DEV_BAD_BLOCK, DEV_BAD_HEADER, DEV_BAD_CHUNK, DEV_BAD_TABLE, DEV_SCAN_TIMEOUT = 
 
 SYMBOLS = ["kvc_plan", "kvc_plan_free", "kvc_payload_size", "kvc_workspace_size", "kvc_compress",
            "kvc_decompress", "kvc_payload_inspect", "kvc_check_block_table", "kvc_status_string",
-           "kvc_trace", "kvc_selftest", "kvc_profile_throughput", "kvc_benefit_threshold", "kvc_policy_build",
+           "kvc_trace", "kvc_selftest", "kvc_table_bytes", "kvc_workspace_init", "kvc_profile_throughput", "kvc_benefit_threshold", "kvc_policy_build",
            "kvc_policy_lookup"]
 
 
@@ -83,7 +83,10 @@ def load():
                                           C.POINTER(C.c_int64), C.POINTER(C.c_uint64),
                                           C.POINTER(C.c_uint64)]
         L.kvc_check_block_table.argtypes = [C.c_void_p, C.c_int64, C.c_int32]
-        L.kvc_trace.argtypes = [C.c_void_p, C.c_int32]
+        L.kvc_trace.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
+        L.kvc_table_bytes.argtypes = [C.c_void_p]
+        L.kvc_table_bytes.restype = C.c_size_t
+        L.kvc_workspace_init.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.kvc_selftest.argtypes = [C.c_void_p, C.c_void_p]
         L.kvc_profile_throughput.argtypes = [C.POINTER(Profile)]
         L.kvc_profile_throughput.restype = C.c_double
@@ -206,9 +209,16 @@ def payload_inspect(header_bytes):
     return rc, m, s, t.value, total.value, list(sec)
 
 
-def trace(events, capacity):
-    """kvc_trace: install (or, with None, remove) an array of hipEvent_t handles."""
-    return load().kvc_trace(events, capacity)
+def trace(plan, events, capacity):
+    """kvc_trace: install (or, with None, remove) an array of hipEvent_t handles in a plan."""
+    return load().kvc_trace(plan._h, events, capacity)
+
+
+def workspace_init(plan, workspace_ptr, stream=None):
+    """kvc_workspace_init: the device image of a plan's width tables at the start of a workspace."""
+    rc = load().kvc_workspace_init(plan._h, workspace_ptr, stream)
+    if rc != OK:
+        raise KvcError("kvc_workspace_init", rc)
 
 
 def profile_throughput(cr, s_enc, s_dec):
@@ -268,6 +278,8 @@ class Buffers:
         self.status = torch.zeros(len(sizes), dtype=torch.int32, device=device)
         ws = plan.workspace_size()
         self.workspace = torch.empty(max(ws, 256), dtype=torch.uint8, device=device)
+        if load().kvc_table_bytes(plan._h):
+            workspace_init(plan, self.workspace.data_ptr(), torch.cuda.current_stream().cuda_stream)
 
     def compress(self, requests, stream=None):
         compress(self.plan, requests, self.payload.data_ptr(), self.offsets, self.out_bytes.data_ptr(),
