@@ -238,7 +238,7 @@ int kvc_trace(kvc_plan_t *plan, void **hip_events, int32_t capacity);
  * results; the kernels reach them with cheaper instruction sequences).  Each count is the
  * number of inputs, over the whole domain a shortcut is used on, for which it differs from
  * the plain IEEE operation; every count must be zero.
- *   counts[0..3]  (max - min) / (2^b - 1) for b = 2, 3, 4, 8: all floats in [0, 2^17]
+ *   counts[0..3]  min((max - min) / (2^b - 1), 65504) for b = 2, 3, 4, 8: all floats >= 0 and +infinity
  *   counts[4]     1 / scale: all positive finite fp16 scales
  *   counts[5]     x - zero read from a packed fp16 pair: all pairs of finite fp16 values
  *   counts[6]     float -> byte with insertion: round-to-nearest-even, all floats in [0, 255]

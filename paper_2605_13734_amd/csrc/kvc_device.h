@@ -288,8 +288,9 @@ template <int BITS, int DT> __device__ __forceinline__ GroupParams make_group(fl
     g.zero = (DT == DT_F16) ? lo : f16_bits_to_f32(zb);
     g.inv = (sh == 0.0f) ? 0.0f : rcp_f16_exact(sh);
     g.meta = sb | (zb << 16);
-    // with a normal fp16 scale and zero == min, (x - zero) * inv rounds into [0, 2^bits - 1]
-    g.clamp = sh < 6.103515625e-05f || (DT != DT_F16 && g.zero != mn);
+    // with a normal fp16 scale that was not limited and zero == min, (x - zero) * inv rounds into
+    // [0, 2^bits - 1]; a bfloat16 group can have its zero point or its scale limited to the fp16 range
+    g.clamp = sh < 6.103515625e-05f || (DT != DT_F16 && (g.zero != mn || sh >= 65504.0f));
     return g;
 }
 

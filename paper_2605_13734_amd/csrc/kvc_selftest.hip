@@ -19,16 +19,19 @@ __device__ __forceinline__ void count(unsigned long long *slot, unsigned long lo
     if (m != 0 && (threadIdx.x & 63) == 0) atomicAdd(slot, bad);
 }
 
-// range / (2^BITS - 1) for every float range in [0, 2^17]
+// range / (2^BITS - 1), limited to 65504 as the metadata stores it, for every non-negative float
+// range including +infinity (max - min of two finite bfloat16 values can overflow).  fp16 input
+// only reaches ranges up to 2 * 65504, where the limit never applies and the quotient itself is
+// compared.
 template <int BITS> __global__ __launch_bounds__(256) void selftest_div_kernel(unsigned long long *slot)
 {
     constexpr float qmax = (float)((1 << BITS) - 1);
-    const uint32_t last = 0x48000000u;                     // 2^17
+    const uint32_t last = 0x7f800000u;                     // +infinity
     unsigned long long bad = 0;
     for (unsigned long long u = blockIdx.x * 256ull + threadIdx.x; u <= last; u += gridDim.x * 256ull) {
         const float r = __uint_as_float((uint32_t)u);
-        const float want = r / qmax;                       // correctly rounded division
-        bad += __float_as_uint(div_levels<BITS>(r)) != __float_as_uint(want);
+        const float want = fminf(r / qmax, 65504.0f);      // correctly rounded division
+        bad += __float_as_uint(fminf(rounded_f32(div_levels<BITS>(r)), 65504.0f)) != __float_as_uint(want);
     }
     count(slot, bad);
 }

@@ -21,8 +21,9 @@ def dev_bytes(t, off, n):
     return t[off: off + n].cpu().numpy()
 
 
-def head_cfg(ref, dt, bk, bv, gk, gv, codec=0):
-    return ref.config(dtype=dt, layers=1, heads=1, bits_k=bk, bits_v=bv, group_k=gk, group_v=gv, codec=codec)
+def head_cfg(ref, dt, bk, bv, gk, gv, codec=0, transform=0, anchor_period=0):
+    return ref.config(dtype=dt, layers=1, heads=1, bits_k=bk, bits_v=bv, group_k=gk, group_v=gv, codec=codec,
+                      transform=transform, anchor_period=anchor_period)
 
 
 def oracle_head(ref, cfg1, is_v, xh_u16, T):
@@ -30,16 +31,19 @@ def oracle_head(ref, cfg1, is_v, xh_u16, T):
     lay = ref.contiguous_layout(1, T, 128)
     codes, meta = ref.compress_head(cfg1, is_v, xh_u16, lay, T, 0, 0)
     back = np.zeros_like(xh_u16)
-    ref.decompress_head(cfg1, is_v, codes, meta, T, 0, 0, back, lay)
+    # delta transform: the anchors are the first rows of the runs, as they stand in the tensor
+    anchors = np.ascontiguousarray(xh_u16[::cfg1.anchor_period]) if cfg1.transform == 2 else None
+    ref.decompress_head(cfg1, is_v, codes, meta, T, 0, 0, back, lay, anchors)
     return codes, meta, back
 
 
-def check_sampled_heads(ref, buf, i, x_head, y_head, L, H, T, dt, bk, bv, gk, gv, samples):
-    """x_head(l, kv, h) / y_head(l, kv, h) -> CPU [T, 128] tensors of input / GPU reconstruction."""
+def check_sampled_heads(ref, buf, i, x_head, y_head, L, H, T, dt, bk, bv, gk, gv, samples, transform=0, anchor_period=0):
+    """x_head(l, kv, h) / y_head(l, kv, h) -> CPU [T, 128] tensors of input / GPU reconstruction.
+    `buf` holds a codec-free payload."""
     hdr = dev_bytes(buf.payload, buf.offsets[i], 128)
     rc, _, _, tokens, total, sec = kvc.payload_inspect(hdr)
     assert rc == 0 and tokens == T and total == int(buf.out_bytes[i])
-    cfg1 = head_cfg(ref, dt, bk, bv, gk, gv)
+    cfg1 = head_cfg(ref, dt, bk, bv, gk, gv, 0, transform, anchor_period)
     base = buf.offsets[i]
     for (l, kv, h) in samples:
         bits, g = (bv, gv) if kv else (bk, gk)
@@ -54,6 +58,30 @@ def check_sampled_heads(ref, buf, i, x_head, y_head, L, H, T, dt, bk, bv, gk, gv
         yh = kvgen.as_u16(y_head(l, kv, h).contiguous())
         d = ulp_distance_16(yh, back)
         assert d.max() <= 1 and int((d != 0).sum()) == 0, ("reconstruction", l, kv, h)
+
+
+def check_sampled_bodies(ref, buf, x_head, L, H, T, dt, bk, bv, gk, gv, picks, transform=0, anchor_period=0):
+    """`buf` holds a payload made with the lossless stage: the coder bodies of the chunks in `picks`
+    ((kv, chunk index in its section) pairs) are rebuilt by the oracle, from the input and the code
+    tables found in the payload, and compared byte for byte, size and place included."""
+    hdr = dev_bytes(buf.payload, buf.offsets[0], 128)
+    rc, _, _, tokens, total, sec = kvc.payload_inspect(hdr)
+    assert rc == 0 and tokens == T and total == int(buf.out_bytes[0])
+    cph = -(-T // 128)
+    n = L * H * cph
+    d = dev_bytes(buf.payload, sec[4] + 512, 4 * (2 * n + 1)).view("<u4").astype(np.int64) * 16
+    tabs = dev_bytes(buf.payload, sec[4], 512)
+    cfg1 = head_cfg(ref, dt, bk, bv, gk, gv, 1, transform, anchor_period)
+    lay1 = ref.contiguous_layout(1, T, 128)
+    for kv, ch in picks:
+        lh, cb = divmod(ch, cph)
+        l, h = divmod(lh, H)
+        xh = kvgen.as_u16(x_head(l, kv, h).contiguous())
+        body = ref.encode_chunk_at(cfg1, kv, xh, lay1, T, cb, tabs[256 * kv: 256 * kv + 256])
+        j = kv * n + ch
+        assert d[j + 1] - d[j] == body.size, ("size", kv, ch)
+        got = dev_bytes(buf.payload, sec[6] + int(d[j]), body.size)
+        assert np.array_equal(got, body), ("body", kv, ch)
 
 
 def test_llama8b_shape_both_strategies(ref):

@@ -123,6 +123,49 @@ def test_degenerate_values(ref):
         check_contiguous(ref, x, bits, bits, 32, 32)
 
 
+def bf16_edge_tensor():
+    """bf16 values that fp16 metadata cannot hold as they are: magnitudes beyond 65504 (the zero
+    point is limited to the fp16 range and then differs from the minimum), ranges beyond 2^17 up
+    to and past the point where the scale saturates at 65504, a range that overflows fp32, minima
+    and ranges below fp16's normal range (subnormal zero points and scales), fp32 subnormals,
+    constant and signed-zero groups; each planted along tokens for K and along channels for V."""
+    x = kvgen.make_kv(5, 1, 2, 128, 128, torch.bfloat16)
+    big = 3.0e38
+    rows = [
+        torch.full((32,), 1.5),                               # constant group
+        torch.tensor([0.0, -0.0] * 16),                       # zeros of both signs only
+        torch.linspace(-1e5, 3e5, 32),                        # beyond fp16, range 4e5 > 2^17
+        torch.tensor([big, -big] * 16),                       # max - min overflows fp32
+        torch.linspace(7e4, 9e4, 32),                         # minimum above 65504
+        torch.linspace(1e-6, 3e-6, 32),                       # minimum and range below fp16's normal range
+        torch.linspace(-3e-6, 2.0, 32),                       # subnormal zero point, ordinary scale
+        torch.linspace(1e-40, 1e-39, 32),                     # fp32 subnormals
+        torch.linspace(-65504.0 * 3, 65504.0 * 12, 32),       # 4-bit scale exactly at the limit
+        torch.linspace(-2.0 ** 17, 2.0 ** 17, 32),
+        torch.linspace(-70000, -66000, 32),                   # whole group below -65504
+        torch.tensor([1e30, -1e30] * 16),
+    ]
+    for i, r in enumerate(rows):
+        r = r.to(torch.bfloat16)
+        x[0, 0, i % 2, 32 * (i % 4): 32 * (i % 4) + 32, i] = r        # K: 32 tokens of channel i
+        x[0, 1, i % 2, i, 32 * (i % 4): 32 * (i % 4) + 32] = r        # V: 32 channels of token i
+    x[0, 1, 1, 40, :] = torch.linspace(-1e5, 3e5, 128).to(torch.bfloat16)       # a group of 128 channels
+    x[0, 0, 1, :, 40] = torch.linspace(-1e5, 3e5, 128).to(torch.bfloat16)       # a group of 128 tokens
+    assert torch.isfinite(x.float()).all()
+    return x
+
+
+@pytest.mark.parametrize("codec", [0, 1])
+@pytest.mark.parametrize("bits", [2, 3, 4, 8])
+def test_degenerate_values_bf16(ref, bits, codec):
+    """The bf16-only paths of the metadata (zero point limited to +-65504, scale saturated at
+    65504, clamped codes when the zero point is not the minimum): payload and reconstruction."""
+    x = bf16_edge_tensor()
+    check_contiguous(ref, x, bits, bits, 32, 32, codec=codec)
+    check_contiguous(ref, x, bits, bits, 128, 128, codec=codec)
+    check_contiguous(ref, x, bits, bits, 64, 64, codec=codec, transform=2, anchor_period=32)
+
+
 @pytest.mark.parametrize("bits,group,codec", [(4, 32, 0), (2, 64, 0), (3, 128, 0), (8, 32, 0), (16, 32, 0)])
 def test_paged_layout(ref, bits, group, codec):
     """Compress from pages == compress from the same data stored contiguously; decompress into

@@ -8,14 +8,15 @@ the first 1024 workgroups).  For every code width, both tensor types and both st
 * the lossless stage is exactly that: reconstructions with and without it are the same bits
   (a property that holds at any size), on three decompressions of the same payload;
 * compressing twice gives the same payload bytes (the chunk-offset scan is order independent);
-* sampled (layer, head) slices of the codec-free payload and reconstruction equal the oracle's.
+* sampled (layer, head) slices of the codec-free payload and reconstruction equal the oracle's,
+  with and without a transform, and sampled coder bodies equal the oracle's byte for byte.
 """
 import numpy as np
 import pytest
 import torch
 
 from paper_2605_13734_amd import kvc, kvgen
-from test_gpu_full_size import check_sampled_heads
+from test_gpu_full_size import check_sampled_bodies, check_sampled_heads
 
 pytestmark = pytest.mark.gpu
 
@@ -41,15 +42,18 @@ def test_lossless_stage_changes_no_bit_far_past_the_first_batch(ref, dtype, bits
     x = kvgen.make_kv(90 + bits, L, H, 128, T, dtype, "cuda")
     st = torch.cuda.current_stream().cuda_stream
     plain, y0 = run(kvc.Plan(dt, L, H, 128, bits, bits, group, group, 0, max_tokens=T, **kw), x)
-    if not kw:
-        samples = [(0, 0, 0), (L - 1, 1, H - 1), (L // 2, 0, 3), (7, 1, 5)]
-        check_sampled_heads(ref, plain, 0, lambda l, kv, h: x[l, kv, h].cpu(), lambda l, kv, h: y0[l, kv, h].cpu(),
-                            L, H, T, dt, bits, bits, group, group, samples)
+    samples = [(0, 0, 0), (L - 1, 1, H - 1), (L // 2, 0, 3), (7, 1, 5)]
+    check_sampled_heads(ref, plain, 0, lambda l, kv, h: x[l, kv, h].cpu(), lambda l, kv, h: y0[l, kv, h].cpu(),
+                        L, H, T, dt, bits, bits, group, group, samples, **kw)
     del plain
     plan = kvc.Plan(dt, L, H, 128, bits, bits, group, group, 1, max_tokens=T, **kw)
     buf, y1 = run(plan, x)
     total = int(buf.out_bytes[0])
     first = buf.payload[:total].clone()
+    n = L * H * (T // 128)
+    rng = np.random.default_rng(bits * 131 + group)
+    picks = [(0, 0), (1, n - 1)] + [(int(rng.integers(0, 2)), int(rng.integers(0, n))) for _ in range(6)]
+    check_sampled_bodies(ref, buf, lambda l, kv, h: x[l, kv, h].cpu(), L, H, T, dt, bits, bits, group, group, picks, **kw)
     for rep in range(3):
         bad = (y1.view(torch.int16) != y0.view(torch.int16))
         n = int(bad.sum())
