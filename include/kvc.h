@@ -192,6 +192,27 @@ int kvc_compress(const kvc_plan_t *plan, const kvc_request *reqs, int32_t n, voi
                  void *workspace, void *hip_stream);
 
 /*
+ * kvc_compress for callers that cannot allocate device memory and have no workspace to hand in:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments and results as kvc_compress, without the workspace: the coder's scratch (histograms,
+ * code tables, work-order counter, chunk-offset scan state) lives in a static device array of
+ * KVC_STATIC_WORKSPACE_BYTES inside the library, one copy per GPU, held until the process ends.
+ * The call allocates nothing and clears what must start from zero itself.
+ *   - the stream must belong to the current device;
+ *   - plans whose kvc_workspace_size exceeds KVC_STATIC_WORKSPACE_BYTES are refused with
+ *     KVC_ERR_CAPACITY (4 MiB covers the lossless stage up to layers * kv_heads *
+ *     ceil(max_tokens / 128) * max_batch = 250,000 chunks per tensor, e.g. 80 x 8 x 32768 x 1);
+ *   - plans with per-head width tables are refused with KVC_ERR_UNSUPPORTED (their tables live
+ *     in a caller workspace);
+ *   - all calls on one GPU share the array: two calls that overlap in time on one GPU (different
+ *     streams or threads) race; calls in stream order on one stream do not.
+ */
+#define KVC_STATIC_WORKSPACE_BYTES (4u << 20)
+int kvc_compress_static(const kvc_plan_t *plan, const kvc_request *reqs, int32_t n, void *payload,
+                        const uint64_t *payload_off, uint64_t *out_bytes, int32_t *dev_status,
+                        void *hip_stream);
+
+/*
  * The decompression stage at the receiving end of a KV movement (section 4: ... Communication ->
  * Decompression -> Decode), the inverse of BS = C(Q(T(X))) (section 5.1): rebuild K and V of n
  * requests into dst[i] (DEVICE; the layout, contiguous or paged, may differ from the sender's).

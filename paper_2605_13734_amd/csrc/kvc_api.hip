@@ -5,6 +5,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "../../include/kvc.h"
 #include "kvc_internal.h"
 
@@ -619,6 +621,44 @@ extern "C" int kvc_compress(const kvc_plan_t *plan, const kvc_request *reqs, int
                             void *workspace, void *hip_stream)
 {
     return compress_on(plan, reqs, n, payload, payload_off, out_bytes, dev_status, workspace, (hipStream_t)hip_stream);
+}
+
+// ---- kvc_compress for callers that cannot allocate: the workspace is a static device array ----
+
+// Every GPU the library runs on holds its own copy of this array until the process ends.  In host
+// code the name is only a handle for hipGetSymbolAddress; the address it returns, one per device,
+// is what the kernels and fills receive.
+static __device__ __align__(256) unsigned char scratch[KVC_STATIC_WORKSPACE_BYTES];
+
+static const int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_lock;
+
+// the current device's copy of `scratch` (looked up once per device)
+static int static_workspace(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return KVC_ERR_DEVICE;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return KVC_ERR_DEVICE;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return KVC_OK;
+}
+
+extern "C" int kvc_compress_static(const kvc_plan_t *plan, const kvc_request *reqs, int32_t n, void *payload,
+                                   const uint64_t *payload_off, uint64_t *out_bytes, int32_t *dev_status,
+                                   void *hip_stream)
+{
+    if (!plan) return KVC_ERR_ARG;
+    if (plan->blob_bytes) return KVC_ERR_UNSUPPORTED;      // width tables live in a caller workspace (kvc_workspace_init)
+    if (kvc_workspace_size(plan) > (size_t)KVC_STATIC_WORKSPACE_BYTES) return KVC_ERR_CAPACITY;
+    void *ws = nullptr;
+    KVC_TRY(static_workspace(&ws));
+    return compress_on(plan, reqs, n, payload, payload_off, out_bytes, dev_status, ws, (hipStream_t)hip_stream);
 }
 
 extern "C" int kvc_decompress(const kvc_plan_t *plan, const void *payload, const uint64_t *payload_off,

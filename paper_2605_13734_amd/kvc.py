@@ -17,7 +17,7 @@ DEV_BAD_BLOCK, DEV_BAD_HEADER, DEV_BAD_CHUNK, DEV_BAD_TABLE, DEV_SCAN_TIMEOUT = 
 
 SYMBOLS = ["kvc_plan", "kvc_plan_free", "kvc_payload_size", "kvc_workspace_size", "kvc_compress",
            "kvc_decompress", "kvc_payload_inspect", "kvc_check_block_table", "kvc_status_string",
-           "kvc_trace", "kvc_selftest", "kvc_table_bytes", "kvc_workspace_init", "kvc_profile_throughput", "kvc_benefit_threshold", "kvc_policy_build",
+           "kvc_trace", "kvc_selftest", "kvc_table_bytes", "kvc_workspace_init", "kvc_compress_static", "kvc_profile_throughput", "kvc_benefit_threshold", "kvc_policy_build",
            "kvc_policy_lookup"]
 
 
@@ -77,6 +77,8 @@ def load():
         L.kvc_workspace_size.restype = C.c_size_t
         L.kvc_compress.argtypes = [C.c_void_p, C.POINTER(Request), C.c_int32, C.c_void_p,
                                    C.POINTER(C.c_uint64), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.kvc_compress_static.argtypes = [C.c_void_p, C.POINTER(Request), C.c_int32, C.c_void_p,
+                                          C.POINTER(C.c_uint64), C.c_void_p, C.c_void_p, C.c_void_p]
         L.kvc_decompress.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(Request),
                                      C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.kvc_payload_inspect.argtypes = [C.c_void_p, C.POINTER(Model), C.POINTER(Strategy),
@@ -187,6 +189,16 @@ def compress(plan, requests, payload_ptr, offsets, out_bytes_ptr, status_ptr, wo
                              status_ptr, workspace_ptr, stream)
     if rc != OK:
         raise KvcError("kvc_compress", rc)
+
+
+def compress_static(plan, requests, payload_ptr, offsets, out_bytes_ptr, status_ptr, stream=None):
+    """kvc_compress_static: kvc_compress on the library's own static workspace (allocates nothing)."""
+    n = len(requests)
+    reqs = (Request * n)(*requests)
+    rc = load().kvc_compress_static(plan._h, reqs, n, payload_ptr, _offsets(offsets), out_bytes_ptr,
+                                    status_ptr, stream)
+    if rc != OK:
+        raise KvcError("kvc_compress_static", rc)
 
 
 def decompress(plan, payload_ptr, offsets, requests, status_ptr, workspace_ptr=None, stream=None):
