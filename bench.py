@@ -4,11 +4,19 @@
 One step = one pass of the whole path over one request of synthetic KV that is already
 resident in HBM: kvc_compress (tables, quantize + pack + Huffman encode + offset scan for
 K and V) followed by kvc_decompress (table set-up, decode + unpack + dequantize).
-Workload: the Llama-3.1-70B shape (80 layers, 8 KV heads, head_dim 128,
+Headline workload: the Llama-3.1-70B shape (80 layers, 8 KV heads, head_dim 128,
 32768 tokens, fp16, 10.74 GB), strategy 4-bit / group 32 followed by the lossless stage.
 
 Prints ONE JSON line.  `value` is the paper's effective throughput s_p = V / (t_enc + t_dec)
 (section 3.1: harmonic combination of encode and decode throughput over uncompressed bytes).
+Beside the headline the line carries
+  roofline      the slowest kernel against the published HBM peak, with the rate a kernel of the
+                same access shape and no arithmetic reaches in the same run (`ceiling_GBps`);
+  configs       every other workload of the measurement plan (tiny, 8B shape with both strategies,
+                the Qwen3-shape ragged batch, the paged 128K sweep over widths and groups):
+                per-direction time, GB/s of KV and fraction of the HBM peak;
+  streamed      the headline tensor as 80 one-layer calls on two streams against the single call;
+  cpu_baseline  the oracle on one host core and, layer-sharded over plain threads, on all of them.
 """
 import argparse
 import json
@@ -30,6 +38,8 @@ WORKLOADS = {
     "llama70b_32k_fp16_hadamard_int4g32": (80, 8, 32768, "f16", 4, 4, 32, 32, 0, 1),
     "llama70b_32k_fp16_delta32_int4g32_huff8": (80, 8, 32768, "f16", 4, 4, 32, 32, 1, (2, 32)),
     "llama70b_32k_fp16_delta32_int4g32": (80, 8, 32768, "f16", 4, 4, 32, 32, 0, (2, 32)),
+    "llama70b_32k_fp16_int4g128_huff8": (80, 8, 32768, "f16", 4, 4, 128, 128, 1),
+    "llama70b_32k_fp16_int2g64": (80, 8, 32768, "f16", 2, 2, 64, 64, 0),
     # per-head widths: a seeded random half of the heads at 8 bits, the other half at 2 (the paper's
     # MixHQ takes the split from trained head masks, which are not available here)
     "llama70b_32k_fp16_mixhq_8_2_g32": (80, 8, 32768, "f16", 4, 4, 32, 32, 0, 0, (8, 2)),
@@ -39,10 +49,21 @@ WORKLOADS = {
 }
 
 
+def host_cores():
+    """Cores this process may use: the scheduler's affinity set, at most the 16 a one-GPU job is given."""
+    try:
+        n = len(os.sched_getaffinity(0))
+    except AttributeError:
+        n = os.cpu_count() or 1
+    return max(1, min(16, n))
+
+
 def cpu_baseline(x_dev, layers, heads, tokens, dt, bits_k, bits_v, gk, gv, codec, transform, sample_layers,
                  head_bits=None, anchor_period=0):
-    """The oracle as it stands, single-threaded, on the first `sample_layers` layers."""
+    """The oracle as it stands, single-threaded, on the first `sample_layers` layers; then the same
+    code layer-sharded over plain threads (one one-layer request per layer, layers are independent)."""
     import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
     from oracle import ref
     from paper_2605_13734_amd import kvgen
     xs = x_dev[:sample_layers].cpu()
@@ -60,10 +81,37 @@ def cpu_baseline(x_dev, layers, heads, tokens, dt, bits_k, bits_v, gk, gv, codec
     t2 = time.perf_counter()
     assert rc == 0
     nbytes = xu.nbytes
-    return {"value": round(nbytes / (t2 - t0) / 1e9, 5), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": "first %d of %d layers (%.0f MB of fp16 KV), compress %.2f s + decompress %.2f s"
-                      % (sample_layers, layers, nbytes / 1e6, t1 - t0, t2 - t1),
-            "s_enc": round(nbytes / (t1 - t0) / 1e9, 5), "s_dec": round(nbytes / (t2 - t1) / 1e9, 5)}
+    res = {"value": round(nbytes / (t2 - t0) / 1e9, 5), "unit": "GB/s", "cores": 1, "kind": "oracle",
+           "sample": "first %d of %d layers (%.0f MB of fp16 KV), compress %.2f s + decompress %.2f s"
+                     % (sample_layers, layers, nbytes / 1e6, t1 - t0, t2 - t1),
+           "s_enc": round(nbytes / (t1 - t0) / 1e9, 5), "s_dec": round(nbytes / (t2 - t1) / 1e9, 5)}
+    del xs, xu, out, payload
+
+    # all cores: one thread per core, each compresses and decompresses whole layers as one-layer requests
+    cores = host_cores()
+    n_layers = min(layers, 2 * cores)
+    xa = kvgen.as_u16(x_dev[:n_layers].cpu())
+    back = np.zeros_like(xa)
+
+    def one_layer(l):
+        c1 = ref.config(dtype=dt, layers=1, heads=heads, bits_k=bits_k, bits_v=bits_v, group_k=gk, group_v=gv,
+                        codec=codec, transform=transform, anchor_period=anchor_period,
+                        head_bits_k=head_bits[0][l * heads:(l + 1) * heads] if head_bits else None,
+                        head_bits_v=head_bits[1][l * heads:(l + 1) * heads] if head_bits else None)
+        p = ref.compress(c1, xa[l, 0], xa[l, 1], lay, tokens)
+        assert ref.decompress(p, back[l, 0], back[l, 1], lay, c1) == 0
+        return p.size
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=cores) as ex:
+        sizes = list(ex.map(one_layer, range(n_layers)))
+    t1 = time.perf_counter()
+    res["all_cores"] = {"value": round(xa.nbytes / (t1 - t0) / 1e9, 5), "unit": "GB/s", "cores": cores,
+                        "os_cpu_count": os.cpu_count(),
+                        "sample": "first %d of %d layers as one-layer requests on %d threads, compress + decompress %.2f s"
+                                  % (n_layers, layers, cores, t1 - t0)}
+    assert all(s > 0 for s in sizes)
+    return res
 
 
 POLICY_STRATEGIES = [
@@ -72,56 +120,171 @@ POLICY_STRATEGIES = [
     ("int4g32", 4, 4, 32, 32, 0, 0),
     ("int4g32_huff8", 4, 4, 32, 32, 1, 0),
     ("hadamard_int4g32", 4, 4, 32, 32, 0, 1),
+    ("hadamard_int4g32_huff8", 4, 4, 32, 32, 1, 1),
     ("delta32_int4g32", 4, 4, 32, 32, 0, (2, 32)),
+    ("delta32_int4g32_huff8", 4, 4, 32, 32, 1, (2, 32)),
     ("delta128_int2g64", 2, 2, 64, 64, 0, (2, 128)),
     ("k4v2g64", 4, 2, 64, 64, 0, 0),
     ("int3g64", 3, 3, 64, 64, 0, 0),
     ("int2g64", 2, 2, 64, 64, 0, 0),
+    ("int4g128_huff8", 4, 4, 128, 128, 1, 0),
     ("int2g128_huff8", 2, 2, 128, 128, 1, 0),
 ]
+
+
+def time_directions(buf, src, dst, steps, warmup=1):
+    """(compress ms, decompress ms) per call, HIP events on the stream the kernels run on."""
+    import torch
+    stream = torch.cuda.current_stream().cuda_stream
+    for _ in range(max(1, warmup)):
+        buf.compress(src, stream)
+        buf.decompress(dst, stream)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    ev[0].record()
+    for _ in range(steps):
+        buf.compress(src, stream)
+    ev[1].record()
+    for _ in range(steps):
+        buf.decompress(dst, stream)
+    ev[2].record()
+    torch.cuda.synchronize()
+    for i in range(len(buf.tokens)):
+        assert int(buf.status[i]) == 0, "device status %d" % int(buf.status[i])
+    return ev[0].elapsed_time(ev[1]) / steps, ev[1].elapsed_time(ev[2]) / steps
+
+
+def direction_report(name, V, payload_bytes, t_enc, t_dec, extra=None):
+    """The paper's profile of one workload (section 3.1) and the HBM bytes it moved per second."""
+    moved = V + payload_bytes
+    r = {"workload": name, "kv_bytes": V, "payload_bytes": payload_bytes, "cr": round(V / payload_bytes, 4),
+         "compress_ms": round(t_enc, 4), "decompress_ms": round(t_dec, 4),
+         "s_enc_GBps": round(V / t_enc / 1e6, 1), "s_dec_GBps": round(V / t_dec / 1e6, 1),
+         "hbm_frac_compress": round(moved / t_enc / 1e6 / HBM_PEAK_GBS, 4),
+         "hbm_frac_decompress": round(moved / t_dec / 1e6 / HBM_PEAK_GBS, 4)}
+    if extra:
+        r.update(extra)
+    return r
 
 
 def policy_table(x, y, dt, L, H, T, steps):
     """Measures (cr, s_enc, s_dec) of several strategies on the same tensor and turns them into the
     piecewise policy of section 6.1 (kvc_policy_build): which strategy to use below which bandwidth."""
-    import ctypes
-    import torch
     from paper_2605_13734_amd import kvc
     V = x.numel() * 2
-    stream = torch.cuda.current_stream().cuda_stream
     profiles, rows = [], []
     for name, bk, bv, gk, gv, codec, tr in POLICY_STRATEGIES:
         tr, period = tr if isinstance(tr, tuple) else (tr, 0)
         plan = kvc.Plan(dt, L, H, 128, bk, bv, gk, gv, codec, max_tokens=T, transform=tr, anchor_period=period)
         buf = kvc.Buffers(plan, [T], "cuda:0")
-        src, dst = [kvc.contiguous_request(x)], [kvc.contiguous_request(y)]
-        buf.compress(src, stream)
-        buf.decompress(dst, stream)
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-        ev[0].record()
-        for _ in range(steps):
-            buf.compress(src, stream)
-        ev[1].record()
-        for _ in range(steps):
-            buf.decompress(dst, stream)
-        ev[2].record()
-        torch.cuda.synchronize()
-        assert int(buf.status[0]) == 0
-        t_enc, t_dec = ev[0].elapsed_time(ev[1]) / steps, ev[1].elapsed_time(ev[2]) / steps
-        cr = V / int(buf.out_bytes[0])
+        t_enc, t_dec = time_directions(buf, [kvc.contiguous_request(x)], [kvc.contiguous_request(y)], steps)
+        payload = int(buf.out_bytes[0])
+        cr = V / payload
         prof = (cr, V / t_enc / 1e6, V / t_dec / 1e6)                       # GB/s of fp16 KV
         profiles.append(prof)
-        rows.append({"name": name, "cr": round(cr, 4), "s_enc_GBps": round(prof[1], 1), "s_dec_GBps": round(prof[2], 1),
-                     "s_p_GBps": round(kvc.profile_throughput(*prof), 1),
-                     "break_even_bandwidth_GBps": round(kvc.benefit_threshold(*prof), 1)})
+        row = direction_report(name, V, payload, t_enc, t_dec)
+        row.update({"s_p_GBps": round(kvc.profile_throughput(*prof), 1),
+                    "break_even_bandwidth_GBps": round(kvc.benefit_threshold(*prof), 1)})
+        rows.append(row)
         del buf, plan
     rc, table = kvc.policy_build(profiles)
     assert rc == 0
     segs = []
     for k, (x_from, prof) in enumerate(table):
-        segs.append({"profile": rows[prof]["name"] if prof >= 0 else "uncompressed",
+        segs.append({"profile": rows[prof]["workload"] if prof >= 0 else "uncompressed",
                      "bandwidth_below_GBps": None if x_from == 0 else round(1.0 / x_from, 1)})
     return {"profiles": rows, "table": segs}
+
+
+def other_configs(steps):
+    """The workloads of the measurement plan besides the headline, each generated, timed and freed."""
+    import torch
+    from paper_2605_13734_amd import kvc, kvgen
+    dev = "cuda:0"
+    out = []
+
+    def contiguous(name, L, H, T, dtype, dt, bk, bv, gk, gv, codec, n):
+        x = kvgen.make_kv(0, L, H, 128, T, dtype, dev)
+        y = torch.empty_like(x)
+        plan = kvc.Plan(dt, L, H, 128, bk, bv, gk, gv, codec, max_tokens=T)
+        buf = kvc.Buffers(plan, [T], dev)
+        t_enc, t_dec = time_directions(buf, [kvc.contiguous_request(x)], [kvc.contiguous_request(y)], n)
+        out.append(direction_report(name, x.numel() * 2, int(buf.out_bytes[0]), t_enc, t_dec))
+        return x, y
+
+    # tiny: launch-bound, reported as latency per call
+    contiguous("tiny_fp16_int4g32", 1, 8, 1024, torch.float16, kvc.F16, 4, 4, 32, 32, 0, 200)
+    out[-1]["note"] = "4 MB of KV: the times are launch latencies per call (prologue + K pass + V pass)"
+    contiguous("tiny_fp16_int4g32_huff8", 1, 8, 1024, torch.float16, kvc.F16, 4, 4, 32, 32, 1, 200)
+    # Llama-3.1-8B shape, 8192 tokens, bf16, both strategies
+    contiguous("llama8b_8k_bf16_int2g64", 32, 8, 8192, torch.bfloat16, kvc.BF16, 2, 2, 64, 64, 0, 20)
+    contiguous("llama8b_8k_bf16_int4g32", 32, 8, 8192, torch.bfloat16, kvc.BF16, 4, 4, 32, 32, 0, 20)
+    torch.cuda.empty_cache()
+
+    # Qwen3-235B attention shape: 94 layers, 4 KV heads, bf16, ragged batch of 4, K 4-bit / V 2-bit, group 64
+    L, H = 94, 4
+    lens = kvgen.request_lengths(0, 4, 16384, 32768)
+    xs = [kvgen.make_kv(100 + i, L, H, 128, T, torch.bfloat16, dev) for i, T in enumerate(lens)]
+    ys = [torch.empty_like(x) for x in xs]
+    plan = kvc.Plan(kvc.BF16, L, H, 128, 4, 2, 64, 64, 0, max_tokens=max(lens), max_batch=4)
+    buf = kvc.Buffers(plan, lens, dev)
+    t_enc, t_dec = time_directions(buf, [kvc.contiguous_request(x) for x in xs], [kvc.contiguous_request(y) for y in ys], steps)
+    V = sum(x.numel() * 2 for x in xs)
+    out.append(direction_report("qwen3_235b_ragged4_bf16_k4v2g64", V, int(buf.out_bytes.sum()), t_enc, t_dec,
+                                {"tokens": lens, "layers": L, "kv_heads": H}))
+    del xs, ys, buf, plan
+    torch.cuda.empty_cache()
+
+    # paged 128K: Llama-3.1-8B shape, 131072 tokens in pages of 16 tokens through a random block table,
+    # compressing from the pages and decompressing into pages under another table
+    L, H, T, bt = 32, 8, 131072, 16
+    pool, table = kvgen.make_paged(0, L, H, 128, T, torch.float16, dev, bt)
+    table2 = kvgen.block_table(7, T // bt, T // bt, dev)
+    dst = torch.empty_like(pool)
+    V = L * 2 * H * T * 128 * 2
+    for bits in (2, 3, 4, 8):
+        for g in (32, 64, 128):
+            plan = kvc.Plan(kvc.F16, L, H, 128, bits, bits, g, g, 0, max_tokens=T)
+            buf = kvc.Buffers(plan, [T], dev)
+            t_enc, t_dec = time_directions(buf, [kvc.paged_request(pool, table, T)], [kvc.paged_request(dst, table2, T)], steps)
+            out.append(direction_report("paged128k_fp16_int%dg%d" % (bits, g), V, int(buf.out_bytes[0]), t_enc, t_dec))
+            del buf, plan
+    # and the lossless stage from and into pages
+    plan = kvc.Plan(kvc.F16, L, H, 128, 4, 4, 32, 32, 1, max_tokens=T)
+    buf = kvc.Buffers(plan, [T], dev)
+    t_enc, t_dec = time_directions(buf, [kvc.paged_request(pool, table, T)], [kvc.paged_request(dst, table2, T)], steps)
+    out.append(direction_report("paged128k_fp16_int4g32_huff8", V, int(buf.out_bytes[0]), t_enc, t_dec))
+    del pool, dst, buf, plan
+    torch.cuda.empty_cache()
+    return out
+
+
+def streamed(x, y, dt, L, H, T, bk, bv, gk, gv, codec, single_ms):
+    """Layer-streamed use: the tensor as L one-layer calls, alternating between two streams (layer l+1
+    is compressed while layer l would be on the wire), against the single call."""
+    import torch
+    from paper_2605_13734_amd import kvc
+    plan = kvc.Plan(dt, 1, H, 128, bk, bv, gk, gv, codec, max_tokens=T)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    bufs = [kvc.Buffers(plan, [T], "cuda:0") for _ in range(L)]      # every layer keeps its payload
+    torch.cuda.synchronize()
+    res = {}
+    for name, call in (("compress", lambda l, s: bufs[l].compress([kvc.contiguous_request(x[l:l + 1])], s.cuda_stream)),
+                       ("decompress", lambda l, s: bufs[l].decompress([kvc.contiguous_request(y[l:l + 1])], s.cuda_stream))):
+        for rep in range(2):                                          # the first round warms up
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for l in range(L):
+                call(l, streams[l & 1])
+            torch.cuda.synchronize()
+            res[name + "_ms"] = round((time.perf_counter() - t0) * 1e3, 4)
+    for b in bufs:
+        assert int(b.status[0]) == 0
+    res["payload_bytes"] = int(sum(int(b.out_bytes[0]) for b in bufs))
+    res["calls"] = L
+    res["single_call_compress_ms"] = round(single_ms[0], 4)
+    res["single_call_decompress_ms"] = round(single_ms[1], 4)
+    res["note"] = "wall clock over %d one-layer calls on two streams, host launch time included" % L
+    return res
 
 
 def main():
@@ -131,6 +294,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="llama70b_32k_fp16_int4g32_huff8", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="skip the other configs and the streamed mode (short runs under a profiler)")
     ap.add_argument("--policy", action="store_true",
                     help="also measure a set of strategies and print the analytic policy table")
     ap.add_argument("--cpu-sample-layers", type=int, default=4)
@@ -238,9 +403,37 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get(args.workload, {}).get(dom)
+
+    # the practical ceiling: the same bytes in the same access shape with no arithmetic (both directions)
+    rows = L * H * T
+    per_row = -(-(alg["k"] - 2 * n_half) // rows)                   # payload-side bytes per token row
+    row_bytes = max(16, min(256, (per_row + 15) // 16 * 16))
+    pe = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    reps = 5
+    kvc.stream_probe(0, x.data_ptr(), buf.payload.data_ptr(), rows, row_bytes, stream)
+    kvc.stream_probe(1, buf.payload.data_ptr(), y.data_ptr(), rows, row_bytes, stream)
+    pe[0].record()
+    for _ in range(reps):
+        kvc.stream_probe(0, x.data_ptr(), buf.payload.data_ptr(), rows, row_bytes, stream)
+    pe[1].record()
+    for _ in range(reps):
+        kvc.stream_probe(1, buf.payload.data_ptr(), y.data_ptr(), rows, row_bytes, stream)
+    pe[2].record()
+    torch.cuda.synchronize()
+    probe_bytes = rows * (256 + row_bytes)
+    ceiling = {"compress": probe_bytes * reps / pe[0].elapsed_time(pe[1]) / 1e6,
+               "decompress": probe_bytes * reps / pe[1].elapsed_time(pe[2]) / 1e6}
+    buf.compress(src, stream)                     # the probe wrote over the payload
+    torch.cuda.synchronize()
+
+    dom_ceiling = ceiling["compress" if dom.startswith("compress") else "decompress"]
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(dom_bytes / dom_ms / 1e6, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dom_bytes / dom_ms / 1e6 / HBM_PEAK_GBS, 4),
-                "traffic": traffic, "avg_ms": round(dom_ms, 4), "algorithmic_bytes": dom_bytes}
+                "traffic": traffic, "avg_ms": round(dom_ms, 4), "algorithmic_bytes": dom_bytes,
+                "ceiling_GBps": round(dom_ceiling, 1), "frac_of_ceiling": round(dom_bytes / dom_ms / 1e6 / dom_ceiling, 4),
+                "ceiling": {"what": "kvc_stream_probe: one tensor pass of this workload's bytes (256 B + %d B per token row) "
+                                    "in the kernels' access shape, no arithmetic" % row_bytes,
+                            "compress_GBps": round(ceiling["compress"], 1), "decompress_GBps": round(ceiling["decompress"], 1)}}
     per_kernel = {k: {"avg_ms": round(ms, 4), "GBps_rw": round(b / ms / 1e6, 1),
                       "frac_hbm": round(b / ms / 1e6 / HBM_PEAK_GBS, 4)} for k, (ms, b) in kernels.items()}
 
@@ -277,9 +470,16 @@ def main():
     }
     if args.policy:
         out["policy"] = policy_table(x, y, dt, L, H, T, max(2, args.steps // 3))
+    if not args.headline_only:
+        if not mix and not transform:
+            out["streamed"] = streamed(x, y, dt, L, H, T, bk, bv, gk, gv, codec, (t_enc, t_dec))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(x, L, H, T, dt, bk, bv, gk, gv, codec, transform,
                                            min(args.cpu_sample_layers, L), head_bits, anchor_period)
+    if not args.headline_only:
+        del x, y, buf, plan
+        torch.cuda.empty_cache()
+        out["configs"] = other_configs(max(3, args.steps // 2))
     print(json.dumps(out))
     return 0
 

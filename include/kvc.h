@@ -255,6 +255,24 @@ int kvc_check_block_table(const int32_t *table, int64_t entries, int32_t num_phy
 int kvc_trace(kvc_plan_t *plan, void **hip_events, int32_t capacity);
 
 /*
+ * Measurement aid, for benchmarks only: moves bytes in the access shape of a tensor pass with no
+ * arithmetic, so that a benchmark can put the memory system's practical ceiling for this pattern
+ * beside the published HBM peak (the path is bound by HBM bandwidth: every element is read once
+ * and written once in the other form, sections 3.1 and 5.1 give the two directions).
+ *   mode 0  the compress direction: one wave per 128 token rows reads 128 x 256 bytes from `src`
+ *           (four serial passes of 32 rows, 16 bytes per lane and access) and writes
+ *           128 x payload_row_bytes to `dst`
+ *   mode 1  the decompress direction: the same with the two sides exchanged
+ *   rows               token rows of 256 bytes (a multiple of 128)
+ *   payload_row_bytes  bytes per row on the payload side: a multiple of 16 in [16, 256]
+ * `src` and `dst` are DEVICE buffers owned by the caller, 16-byte aligned, of rows x 256 and
+ * rows x payload_row_bytes bytes (mode 0; exchanged for mode 1).  Enqueued on `hip_stream`.
+ * Returns KVC_OK, KVC_ERR_ARG, KVC_ERR_CAPACITY (more than 2^32 chunks) or KVC_ERR_DEVICE.
+ */
+int kvc_stream_probe(int mode, const void *src, void *dst, int64_t rows, int32_t payload_row_bytes,
+                     void *hip_stream);
+
+/*
  * Device self-test of the quantizer's arithmetic shortcuts (stage Q of section 5.1 fixes the
  * results; the kernels reach them with cheaper instruction sequences).  Each count is the
  * number of inputs, over the whole domain a shortcut is used on, for which it differs from

@@ -25,7 +25,7 @@ WIDTHS = (2, 3, 4, 8)
 # the build over the cores; the slowest units come first
 JOBS = ([("kvc_huff_enc.hip", b) for b in WIDTHS] + [("kvc_quant.hip", b) for b in WIDTHS] +
         [("kvc_huff_dec.hip", b) for b in WIDTHS] +
-        [("kvc_huff_tables.hip", None), ("kvc_selftest.hip", None), ("kvc_service.hip", None),
+        [("kvc_huff_tables.hip", None), ("kvc_selftest.hip", None), ("kvc_service.hip", None), ("kvc_probe.hip", None),
          ("kvc_api.hip", None), ("kvc_policy.hip", None)])
 # packed fp32 instructions are switched off for the device pass (flag for hipcc only)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",

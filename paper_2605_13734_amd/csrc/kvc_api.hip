@@ -409,6 +409,8 @@ static TensorView view_of(const kvc_request *r, int is_v)
     if (r->block_table)
         while ((1 << v.bt_shift) < r->block_tokens) ++v.bt_shift;
     v.num_phys_blocks = r->num_phys_blocks;
+    v.bt_wave = (r->block_table && r->block_tokens >= 4 && r->stride_token < (1ll << 24) &&
+                 (long long)r->block_tokens * r->stride_token < (1ll << 31)) ? 1 : 0;
     return v;
 }
 
@@ -426,6 +428,7 @@ static QuantArgs quant_args(const kvc_plan_t *p, const kvc_request *r, int is_v,
     a.heads = p->model.kv_heads;
     a.group = group;
     a.dense = (!r->block_table && r->stride_token == kDim) ? 1 : 0;
+    a.head_minor = (r->stride_head < r->stride_token && !p->has_table[is_v]) ? 1 : 0;
     a.rotate = (p->strat.transform == KVC_T_HADAMARD && bits != 16) ? 1 : 0;
     if (anchor_rows(p, is_v, r->tokens) > 0) {
         a.anchors = (uint16_t *)(payload + (is_v ? g.off_anchors_v : g.off_anchors_k));

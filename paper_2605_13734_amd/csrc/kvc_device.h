@@ -31,6 +31,8 @@ struct TensorView {
     const int *block_table;     // null = contiguous
     int bt_shift;               // log2(block_tokens)
     int num_phys_blocks;
+    int bt_wave;                // blocks of 4 tokens or more whose rows lie within 2^31 elements at a stride
+                                // below 2^24: a pass needs one table entry per 4 rows, read once per wave
 };
 
 // Bit casts go through by-value scalars: applying __builtin_bit_cast directly to an element
@@ -39,6 +41,10 @@ __device__ __forceinline__ half2_t as_half2(uint32_t u) { return __builtin_bit_c
 __device__ __forceinline__ uint32_t as_u32(half2_t h) { return __builtin_bit_cast(uint32_t, h); }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+// The wave's index inside its workgroup, as a value the compiler knows to be the same in all lanes:
+// everything derived from it (unit and chunk numbers, head offsets, block-table entries) is then
+// computed once per wave by the scalar unit instead of once per lane.
+__device__ __forceinline__ int wave_id() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
 
 // Element offset of row t of head (l, h).  A block-table entry out of range is reported
 // through `bad` and replaced by block 0, so the address is always inside the pool.
@@ -50,6 +56,38 @@ __device__ __forceinline__ long long row_offset(const TensorView &v, long long h
     if ((unsigned)blk >= (unsigned)v.num_phys_blocks) { bad = true; blk = 0; }
     return head_off + (long long)blk * v.stride_block +
            (t & ((1ll << v.bt_shift) - 1)) * v.stride_token;
+}
+
+// Element offsets of the lane's 8 rows of the pass that starts at row0 (a multiple of 32; row0 and
+// head_off the same in all lanes): row = row0 + 4*i + rsub, rows past the end of the sequence
+// replaced by the last one.  With a block table whose blocks hold 4 tokens or more, the four rows
+// 4*i .. 4*i+3 share a block: its entry is read and turned into a base once per wave, and a lane
+// adds its row's place inside the block with a 24-bit multiply.
+__device__ __forceinline__ void pass_offsets(const TensorView &v, long long head_off, long long row0, long long tokens,
+                                             long long off[8], bool &bad)
+{
+    const int rsub = lane_id() >> 4;
+    if (v.block_table == nullptr || !v.bt_wave) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            long long row = row0 + 4 * i + rsub;
+            row = row < tokens ? row : tokens - 1;
+            off[i] = row_offset(v, head_off, row, bad);
+        }
+        return;
+    }
+    const int mask = (1 << v.bt_shift) - 1;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        long long first = row0 + 4 * i;
+        first = first < tokens ? first : tokens - 1;
+        int blk = __builtin_amdgcn_readfirstlane(v.block_table[first >> v.bt_shift]);
+        if ((unsigned)blk >= (unsigned)v.num_phys_blocks) { bad = true; blk = 0; }
+        const long long base = head_off + (long long)blk * v.stride_block;
+        long long row = row0 + 4 * i + rsub;
+        row = row < tokens ? row : tokens - 1;
+        off[i] = base + (long long)__umul24((unsigned)((int)row & mask), (unsigned)v.stride_token);
+    }
 }
 
 // ---- 16-bit floats ----------------------------------------------------------------------

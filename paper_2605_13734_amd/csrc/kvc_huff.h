@@ -121,6 +121,45 @@ __device__ __forceinline__ void quantize_chunk(const QuantArgs &a, const ChunkPo
     }
 }
 
+// The same for a full chunk whose rows are contiguous (dense layout, no transform), with the loads
+// of AHEAD units in flight: while unit u is worked on, the rows of the next AHEAD - 1 units are
+// already on their way (a wave has AHEAD * RU * 256 bytes in flight instead of one unit's).
+template <int BITS, int G, int DT, bool IS_V, int AHEAD>
+__device__ __forceinline__ void quantize_chunk_ahead(const QuantArgs &a, const ChunkPos &c, uint8_t *lds)
+{
+    constexpr int RU = IS_V ? kPassRows : G, PU = RU / kPassRows, NU = kChunkRows / RU, UL = PU * 8;
+    constexpr int NB = AHEAD < NU ? AHEAD : NU;         // buffers
+    const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
+    u32x4 raw[NB][UL];
+    const u32x4 *p = (const u32x4 *)(a.x.base + c.head_off + (c.row0 + rsub) * kDim + col * 8);
+#pragma unroll
+    for (int u = 0; u < NB; ++u)
+#pragma unroll
+        for (int i = 0; i < UL; ++i) raw[u][i] = __builtin_nontemporal_load(p + (u * UL + i) * 64);
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+        const long long row0 = c.row0 + u * RU;
+        u32x4 *r = raw[u % NB];
+        if (!IS_V) {
+            const long long nb = (a.tokens + G - 1) / G;
+            KParams kp;
+            uint8_t *meta_block = a.meta + (c.lh * nb + row0 / G) * (kDim * 4);
+            k_group_params<BITS, DT, UL, ChunkGeom<BITS>::kSubStride>(r, lds + ChunkGeom<BITS>::kSubBytes, meta_block, kp);
+            k_emit<BITS, DT, PU, true>(r, kp, code_row<BITS, true>(lds, u * RU), kChunkRows);
+        } else {
+            constexpr int NG = kDim / G;
+            VParams vp;
+            v_pass_params<BITS, G, DT>(r, vp);
+            uint32_t *meta = (uint32_t *)a.meta + (c.lh * a.tokens + row0) * NG;
+            v_emit<BITS, G, DT, true>(r, vp, code_row<BITS, true>(lds, u * RU), kChunkRows, meta);
+        }
+        if (u + NB < NU) {
+#pragma unroll
+            for (int i = 0; i < UL; ++i) r[i] = __builtin_nontemporal_load(p + ((u + NB) * UL + i) * 64);
+        }
+    }
+}
+
 // The lane's sub-block (rows 2*lane, 2*lane+1) from LDS into registers.
 template <int BITS> __device__ __forceinline__ void load_sub(const uint8_t *lds, uint32_t *sym)
 {

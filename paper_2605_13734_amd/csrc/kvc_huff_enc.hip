@@ -107,6 +107,9 @@ template <int W> __device__ __forceinline__ void encode_two(const uint32_t *sym,
 // registers too without spilling (the other variants would spill, so they keep what they need).
 template <int BITS, int G, int DT, bool DENSE> constexpr int enc_min_waves()
 {
+#ifdef KVC_EXP_AHEAD
+    return (BITS <= 4 && G == 32 && DT == DT_F16 && DENSE) ? KVC_EXP_AHEAD : 1;
+#endif
     return (BITS <= 4 && G == 32 && DT == DT_F16 && DENSE) ? 4 : 1;
 }
 
@@ -122,7 +125,7 @@ void encode_kernel(CoderArgs a)
     __shared__ unsigned long long s_excl;
     __shared__ uint32_t s_ticket;
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
+    const int tid = threadIdx.x, wave = wave_id(), lane = lane_id();
     if (tid == 0) s_ticket = atomicAdd(a.ws.ticket, 1u);
     for (int k = tid; k < 256; k += NW * 64) {
         const uint32_t e = a.ws.enc[(IS_V ? 256 : 0) + k];       // code | length << 16
@@ -130,7 +133,7 @@ void encode_kernel(CoderArgs a)
         enc.code[k] = (uint16_t)((e & 0xfffu) | ((e >> 16) << 12));
     }
     __syncthreads();
-    const long long ticket = s_ticket;                 // global order over K and V workgroups
+    const long long ticket = (unsigned)__builtin_amdgcn_readfirstlane((int)s_ticket);     // global order over K and V workgroups (the same in all lanes)
     const long long chunk = (ticket - a.wg_base) * NW + wave;
     const bool live = chunk < a.chunks;
     uint8_t *lds = lds_all + wave * Geo::kLds;
@@ -143,6 +146,10 @@ void encode_kernel(CoderArgs a)
         ChunkPos c = chunk_pos(a.q, chunk);
         rows = c.rows;
         bool bad = false;
+#ifdef KVC_EXP_AHEAD
+        if (DENSE && c.rows == kChunkRows && !(XF && (a.q.rotate || a.q.anchors))) quantize_chunk_ahead<BITS, G, DT, IS_V, KVC_EXP_UNITS>(a.q, c, lds);
+        else
+#endif
         quantize_chunk<BITS, G, DT, IS_V, DENSE, XF>(a.q, c, lds, true, bad);
         if (bad) atomicOr(a.q.status, KVC_DEV_BAD_BLOCK);
         wave_sync();

@@ -17,6 +17,8 @@ struct QuantArgs {
     int heads;
     int group;                  // runtime copy of the group size
     int dense;                  // rows of a head are contiguous: stride_token == head_dim, no block table
+    int head_minor;             // the heads of a token lie next to each other (stride_head < stride_token, as in a
+                                // paged pool): neighbouring work units then take the same tokens of neighbouring heads
     int rotate;                 // stage T: rows are Hadamard-transformed on the way in / back on the way out
     // stage T, delta transform: the tensor's anchor rows inside the payload,
     // [layer * heads + head][ceil(tokens / period)][128] (null = transform off), period = 1 << anchor_shift

@@ -16,11 +16,20 @@ struct UnitPos {
 
 __device__ __forceinline__ bool unit_pos(const QuantArgs &a, UnitPos &u)
 {
-    long long unit = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    long long unit = (long long)blockIdx.x * 4 + wave_id();
     if (unit >= a.total_units) return false;
-    const long long slot = unit / a.units_per_head;
-    u.lh = a.head_list ? a.head_list[slot] : slot;
-    u.blk = unit - slot * a.units_per_head;
+    if (a.head_minor) {
+        // unit = (layer * units_per_head + block) * heads + head: the four waves of a workgroup read or
+        // write the same token rows of four neighbouring heads, which are contiguous in memory
+        const long long t = unit / a.heads;
+        const long long l = t / a.units_per_head;
+        u.blk = t - l * a.units_per_head;
+        u.lh = l * a.heads + (unit - t * a.heads);
+    } else {
+        const long long slot = unit / a.units_per_head;
+        u.lh = a.head_list ? a.head_list[slot] : slot;
+        u.blk = unit - slot * a.units_per_head;
+    }
     long long l = u.lh / a.heads, h = u.lh - l * a.heads;
     u.head_off = l * a.x.stride_layer + h * a.x.stride_head;
     return true;

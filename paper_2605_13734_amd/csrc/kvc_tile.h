@@ -31,13 +31,19 @@ __device__ __forceinline__ void load_pass(const TensorView &v, long long head_of
         for (int i = 0; i < 8; ++i) raw[i] = __builtin_nontemporal_load(p + i * 64);
         return;
     }
+    long long off[8];
+    if (DENSE) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        long long row = row0 + 4 * i + rsub;
-        row = row < tokens ? row : tokens - 1;
-        const long long off = DENSE ? head_off + row * kDim : row_offset(v, head_off, row, bad);
-        raw[i] = __builtin_nontemporal_load((const u32x4 *)(v.base + off + col * 8));
+        for (int i = 0; i < 8; ++i) {
+            long long row = row0 + 4 * i + rsub;
+            row = row < tokens ? row : tokens - 1;
+            off[i] = head_off + row * kDim;
+        }
+    } else {
+        pass_offsets(v, head_off, row0, tokens, off, bad);
     }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) raw[i] = __builtin_nontemporal_load((const u32x4 *)(v.base + off[i] + col * 8));
 }
 
 __device__ __forceinline__ uint32_t xlane_u32(uint32_t v, int xor_mask)
@@ -539,34 +545,43 @@ __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float sc
     // the caller may have that one anchor in flight already
     u32x4 pass_anchor = {0, 0, 0, 0};
     if (TR == 2) pass_anchor = loaded_anchor ? *loaded_anchor : load_anchor(anchors, anchor_shift, row0);
+    // every load of the pass (packed codes, block-table entries) is issued before the first store: the
+    // compiler cannot move a load across a store it cannot tell apart from it, and a pass that alternates
+    // them pays one memory round trip per row
+    u32x2 w[8];
     if (DENSE && rows >= kPassRows) {
         u32x4 *dst = (u32x4 *)(x.base + head_off + (row0 + rsub) * kDim + col * 8);
 #pragma unroll
+        for (int i = 0; i < 8; ++i) w[i] = fetch_codes<BITS, LAYOUT>(codes, row_base + 4 * i + rsub);
+#pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const u32x2 w = fetch_codes<BITS, LAYOUT>(codes, row_base + 4 * i + rsub);
-            u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w, scale[i], zero[i])
-                             : dequant_row<BITS, DT, CLAMP>(w, scale, zero);
+            u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w[i], scale[i], zero[i])
+                             : dequant_row<BITS, DT, CLAMP>(w[i], scale, zero);
             if (TR == 1) out = hadamard_row<DT>(out, true);
             if (TR == 2) out = add_anchor<DT>(out, pass_anchor, anchor_shift, row0 + 4 * i + rsub);
             __builtin_nontemporal_store(out, dst + i * 64);
         }
         return;
     }
+    long long off[8];
+    bool b = false;
+    if (!DENSE) pass_offsets(x, head_off, row0, row0 + rows, off, b);       // a bad block makes the whole pass suspect:
+    bad |= b;                                                             // nothing of it is stored
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int r = 4 * i + rsub;
         const bool ok = r < rows;                       // uniform over each quad of lanes
-        const u32x2 w = fetch_codes<BITS, LAYOUT>(codes, row_base + (ok ? r : 0));
-        u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w, scale[i], zero[i])
-                         : dequant_row<BITS, DT, CLAMP>(w, scale, zero);
+        w[i] = fetch_codes<BITS, LAYOUT>(codes, row_base + (ok ? r : 0));
+        if (DENSE) off[i] = head_off + (row0 + (ok ? r : 0)) * kDim;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = 4 * i + rsub;
+        u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w[i], scale[i], zero[i])
+                         : dequant_row<BITS, DT, CLAMP>(w[i], scale, zero);
         if (TR == 1) out = hadamard_row<DT>(out, true);     // (all 16 lanes of a row take part)
-        if (TR == 2) out = add_anchor<DT>(out, pass_anchor, anchor_shift, row0 + (ok ? r : 0));
-        if (ok) {
-            bool b = false;
-            const long long off = DENSE ? head_off + (row0 + r) * kDim : row_offset(x, head_off, row0 + r, b);
-            if (!b) *(u32x4 *)(x.base + off + col * 8) = out;
-            bad |= b;
-        }
+        if (TR == 2) out = add_anchor<DT>(out, pass_anchor, anchor_shift, row0 + (r < rows ? r : 0));
+        if (r < rows && !b) __builtin_nontemporal_store(out, (u32x4 *)(x.base + off[i] + col * 8));
     }
 }
 

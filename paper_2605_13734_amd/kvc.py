@@ -17,7 +17,7 @@ DEV_BAD_BLOCK, DEV_BAD_HEADER, DEV_BAD_CHUNK, DEV_BAD_TABLE, DEV_SCAN_TIMEOUT = 
 
 SYMBOLS = ["kvc_plan", "kvc_plan_free", "kvc_payload_size", "kvc_workspace_size", "kvc_compress",
            "kvc_decompress", "kvc_payload_inspect", "kvc_check_block_table", "kvc_status_string",
-           "kvc_trace", "kvc_selftest", "kvc_table_bytes", "kvc_workspace_init", "kvc_compress_static", "kvc_profile_throughput", "kvc_benefit_threshold", "kvc_policy_build",
+           "kvc_trace", "kvc_selftest", "kvc_table_bytes", "kvc_workspace_init", "kvc_compress_static", "kvc_stream_probe", "kvc_profile_throughput", "kvc_benefit_threshold", "kvc_policy_build",
            "kvc_policy_lookup"]
 
 
@@ -89,6 +89,7 @@ def load():
         L.kvc_table_bytes.argtypes = [C.c_void_p]
         L.kvc_table_bytes.restype = C.c_size_t
         L.kvc_workspace_init.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        L.kvc_stream_probe.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]
         L.kvc_selftest.argtypes = [C.c_void_p, C.c_void_p]
         L.kvc_profile_throughput.argtypes = [C.POINTER(Profile)]
         L.kvc_profile_throughput.restype = C.c_double
@@ -257,6 +258,13 @@ def policy_lookup(table, bandwidth):
     a, b, c = C.c_int32(0), C.c_int32(0), C.c_int32(0)
     rc = load().kvc_policy_lookup(arr, len(table), bandwidth, C.byref(a), C.byref(b), C.byref(c))
     return rc, a.value, b.value, c.value
+
+
+def stream_probe(mode, src_ptr, dst_ptr, rows, payload_row_bytes, stream=None):
+    """kvc_stream_probe: bytes moved in the access shape of a tensor pass, without arithmetic."""
+    rc = load().kvc_stream_probe(mode, src_ptr, dst_ptr, rows, payload_row_bytes, stream)
+    if rc != OK:
+        raise KvcError("kvc_stream_probe", rc)
 
 
 SELFTEST_COUNTS = 8
