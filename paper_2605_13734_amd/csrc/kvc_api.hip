@@ -492,8 +492,9 @@ static CoderArgs coder_args(const kvc_plan_t *p, const QuantArgs &q, int is_v, u
     c.chunks = is_v ? g.chunks_v : g.chunks_k;
     c.chunk_base = is_v ? g.chunks_k : 0;
     c.total_chunks = g.chunks_k + g.chunks_v;
-    // chunks per encode workgroup: 2 at 8 bits, 4 otherwise (LDS footprint of a chunk)
-    const int nw_k = p->strat.bits_k == 8 ? 2 : 4, nw_v = p->strat.bits_v == 8 ? 2 : 4;
+    // chunks per encode workgroup
+    const int nw_k = enc_waves(p->strat.bits_k, p->strat.group_k, p->model.dtype, q.dense != 0);
+    const int nw_v = enc_waves(p->strat.bits_v, p->strat.group_v, p->model.dtype, q.dense != 0);
     const long long wg_k = (g.chunks_k + nw_k - 1) / nw_k, wg_v = (g.chunks_v + nw_v - 1) / nw_v;
     c.wg_base = is_v ? wg_k : 0;
     c.total_wgs = wg_k + wg_v;
@@ -571,7 +572,7 @@ static int compress_on(const kvc_plan_t *plan, const kvc_request *reqs, int32_t 
                 it.write_total = 1;
             } else {
                 uint8_t *ws = (uint8_t *)workspace + plan->blob_bytes + (size_t)i * plan->ws_request;
-                CoderArgs c = coder_args(plan, QuantArgs(), 0, pl, g, ws, 0, nullptr);
+                CoderArgs c = coder_args(plan, quant_args(plan, &reqs[i], 0, pl, g, dev_status + i, true), 0, pl, g, ws, 0, nullptr);
                 // histograms, ticket and scan state start from zero
                 it.zero[0] = c.ws.hist;
                 it.zero_words[0] = 2 * 256;

@@ -28,7 +28,7 @@ namespace kvc {
 // the arrival count in bits 40..47; the sum of sizes is the workgroup's aggregate once the
 // count is complete.  Sizes and prefixes are in 16-byte units.
 constexpr unsigned long long kFlagPrefix = 2ull << 62, kValueMask = (1ull << 40) - 1;
-constexpr int kAggShift = 40, kAggComplete = 4;
+constexpr int kAggShift = 40, kAggComplete = 8;
 constexpr int kSpinLimit = 1 << 20;
 
 template <int BITS> struct ChunkGeom {
@@ -37,7 +37,6 @@ template <int BITS> struct ChunkGeom {
     static constexpr int kSubStride = kSubBytes + 16;      // LDS stride (bank spread, 16-byte aligned)
     static constexpr int kWords = kSubBytes / 4;           // words a lane holds for its sub-block
     static constexpr int kLds = kSubs * kSubStride;        // LDS bytes per wave
-    static constexpr int kWaves = BITS == 8 ? 2 : 4;       // encoder: waves (= chunks) per workgroup
     static constexpr int kDecWaves = BITS == 8 ? 2 : 4;    // decoder: waves per workgroup (they share the 8 KB table)
 };
 
@@ -89,74 +88,50 @@ __device__ __forceinline__ ChunkPos chunk_pos(const QuantArgs &a, long long chun
 // XF = false leaves the code of stage T out (for launches that have no transform): in one kernel
 // with the plain path it costs the plain path its registers, most of all for token blocks of 64
 // and 128 rows.
+template <int BITS, int G, int DT, bool IS_V> struct UnitGeom {
+    static constexpr int kRows = IS_V ? kPassRows : G;             // rows of a unit: a pass, or a K token block
+    static constexpr int kPasses = kRows / kPassRows, kUnits = kChunkRows / kRows;
+};
+
+// One unit of a chunk: the rows [u * kRows, ...) of the chunk are loaded, transformed, quantized and
+// packed; their codes go to the rows lds_row0 ... of the LDS region.
+template <int BITS, int G, int DT, bool IS_V, bool DENSE, bool XF = true>
+__device__ __forceinline__ void quantize_unit(const QuantArgs &a, const ChunkPos &c, int u, uint8_t *lds, int lds_row0,
+                                              bool write_meta, bool &bad)
+{
+    constexpr int RU = UnitGeom<BITS, G, DT, IS_V>::kRows, PU = UnitGeom<BITS, G, DT, IS_V>::kPasses;
+    const long long row0 = c.row0 + u * RU;
+    u32x4 raw[PU * 8];
+#pragma unroll
+    for (int p = 0; p < PU; ++p) load_pass<DENSE>(a.x, c.head_off, row0 + p * kPassRows, a.tokens, raw + p * 8, bad);
+    if (XF && a.rotate) rotate_rows<DT, PU * 8>(raw);
+    if (XF && a.anchors)
+        delta_rows<DT, DENSE, PU * 8>(a.x, c.head_off, row0, a.tokens, a.anchor_shift,
+                                      head_anchors(a.anchors, c.lh, a.tokens, a.anchor_shift), write_meta, raw, bad);
+    if (!IS_V) {
+        const long long nb = (a.tokens + G - 1) / G;
+        KParams kp;
+        uint8_t *meta_block = write_meta ? a.meta + (c.lh * nb + row0 / G) * (kDim * 4) : nullptr;
+        k_group_params<BITS, DT, PU * 8, ChunkGeom<BITS>::kSubStride>(raw, lds + ChunkGeom<BITS>::kSubBytes, meta_block, kp);
+        k_emit<BITS, DT, PU, true>(raw, kp, code_row<BITS, true>(lds, lds_row0), c.rows - u * RU);
+    } else {
+        constexpr int NG = kDim / G;
+        VParams vp;
+        v_pass_params<BITS, G, DT>(raw, vp);
+        uint32_t *meta = write_meta ? (uint32_t *)a.meta + (c.lh * a.tokens + row0) * NG : nullptr;
+        v_emit<BITS, G, DT, true>(raw, vp, code_row<BITS, true>(lds, lds_row0), c.rows - u * RU, meta);
+    }
+}
+
 template <int BITS, int G, int DT, bool IS_V, bool DENSE, bool XF = true>
 __device__ __forceinline__ void quantize_chunk(const QuantArgs &a, const ChunkPos &c, uint8_t *lds, bool write_meta,
                                                bool &bad)
 {
-    constexpr int RU = IS_V ? kPassRows : G, PU = RU / kPassRows, NU = kChunkRows / RU;
+    constexpr int RU = UnitGeom<BITS, G, DT, IS_V>::kRows, NU = UnitGeom<BITS, G, DT, IS_V>::kUnits;
 #pragma unroll 1
     for (int u = 0; u < NU; ++u) {
         if (u * RU >= c.rows) break;
-        const long long row0 = c.row0 + u * RU;
-        u32x4 raw[PU * 8];
-#pragma unroll
-        for (int p = 0; p < PU; ++p) load_pass<DENSE>(a.x, c.head_off, row0 + p * kPassRows, a.tokens, raw + p * 8, bad);
-        if (XF && a.rotate) rotate_rows<DT, PU * 8>(raw);
-        if (XF && a.anchors)
-            delta_rows<DT, DENSE, PU * 8>(a.x, c.head_off, row0, a.tokens, a.anchor_shift,
-                                          head_anchors(a.anchors, c.lh, a.tokens, a.anchor_shift), write_meta, raw, bad);
-        if (!IS_V) {
-            const long long nb = (a.tokens + G - 1) / G;
-            KParams kp;
-            uint8_t *meta_block = write_meta ? a.meta + (c.lh * nb + row0 / G) * (kDim * 4) : nullptr;
-            k_group_params<BITS, DT, PU * 8, ChunkGeom<BITS>::kSubStride>(raw, lds + ChunkGeom<BITS>::kSubBytes, meta_block, kp);
-            k_emit<BITS, DT, PU, true>(raw, kp, code_row<BITS, true>(lds, u * RU), c.rows - u * RU);
-        } else {
-            constexpr int NG = kDim / G;
-            VParams vp;
-            v_pass_params<BITS, G, DT>(raw, vp);
-            uint32_t *meta = write_meta ? (uint32_t *)a.meta + (c.lh * a.tokens + row0) * NG : nullptr;
-            v_emit<BITS, G, DT, true>(raw, vp, code_row<BITS, true>(lds, u * RU), c.rows - u * RU, meta);
-        }
-    }
-}
-
-// The same for a full chunk whose rows are contiguous (dense layout, no transform), with the loads
-// of AHEAD units in flight: while unit u is worked on, the rows of the next AHEAD - 1 units are
-// already on their way (a wave has AHEAD * RU * 256 bytes in flight instead of one unit's).
-template <int BITS, int G, int DT, bool IS_V, int AHEAD>
-__device__ __forceinline__ void quantize_chunk_ahead(const QuantArgs &a, const ChunkPos &c, uint8_t *lds)
-{
-    constexpr int RU = IS_V ? kPassRows : G, PU = RU / kPassRows, NU = kChunkRows / RU, UL = PU * 8;
-    constexpr int NB = AHEAD < NU ? AHEAD : NU;         // buffers
-    const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
-    u32x4 raw[NB][UL];
-    const u32x4 *p = (const u32x4 *)(a.x.base + c.head_off + (c.row0 + rsub) * kDim + col * 8);
-#pragma unroll
-    for (int u = 0; u < NB; ++u)
-#pragma unroll
-        for (int i = 0; i < UL; ++i) raw[u][i] = __builtin_nontemporal_load(p + (u * UL + i) * 64);
-#pragma unroll
-    for (int u = 0; u < NU; ++u) {
-        const long long row0 = c.row0 + u * RU;
-        u32x4 *r = raw[u % NB];
-        if (!IS_V) {
-            const long long nb = (a.tokens + G - 1) / G;
-            KParams kp;
-            uint8_t *meta_block = a.meta + (c.lh * nb + row0 / G) * (kDim * 4);
-            k_group_params<BITS, DT, UL, ChunkGeom<BITS>::kSubStride>(r, lds + ChunkGeom<BITS>::kSubBytes, meta_block, kp);
-            k_emit<BITS, DT, PU, true>(r, kp, code_row<BITS, true>(lds, u * RU), kChunkRows);
-        } else {
-            constexpr int NG = kDim / G;
-            VParams vp;
-            v_pass_params<BITS, G, DT>(r, vp);
-            uint32_t *meta = (uint32_t *)a.meta + (c.lh * a.tokens + row0) * NG;
-            v_emit<BITS, G, DT, true>(r, vp, code_row<BITS, true>(lds, u * RU), kChunkRows, meta);
-        }
-        if (u + NB < NU) {
-#pragma unroll
-            for (int i = 0; i < UL; ++i) r[i] = __builtin_nontemporal_load(p + ((u + NB) * UL + i) * 64);
-        }
+        quantize_unit<BITS, G, DT, IS_V, DENSE, XF>(a, c, u, lds, u * RU, write_meta, bad);
     }
 }
 

@@ -114,11 +114,11 @@ template <int BITS, int G, int DT, bool DENSE> constexpr int enc_min_waves()
 }
 
 template <int BITS, int G, int DT, bool IS_V, bool DENSE, bool XF>
-__global__ __launch_bounds__(ChunkGeom<BITS>::kWaves * 64) __attribute__((amdgpu_waves_per_eu(enc_min_waves<BITS, G, DT, DENSE>())))
+__global__ __launch_bounds__(enc_waves(BITS, G, DT, DENSE) * 64) __attribute__((amdgpu_waves_per_eu(enc_min_waves<BITS, G, DT, DENSE>())))
 void encode_kernel(CoderArgs a)
 {
     using Geo = ChunkGeom<BITS>;
-    constexpr int W = Geo::kWords, NW = Geo::kWaves;
+    constexpr int W = Geo::kWords, NW = enc_waves(BITS, G, DT, DENSE);
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * Geo::kLds];
     __shared__ EncTables enc;
     __shared__ uint32_t s_units[NW];
@@ -290,7 +290,7 @@ void encode_kernel(CoderArgs a)
 
 template <int BITS, int G, int DT, bool IS_V> static int encode_launch(const CoderArgs &a, hipStream_t s)
 {
-    constexpr int NW = ChunkGeom<BITS>::kWaves;
+    const int NW = enc_waves(BITS, G, DT, a.q.dense != 0);
     const long long need = (a.chunks + NW - 1) / NW;
     if (need <= 0) return KVC_OK;
     // K token blocks of 64 and 128 rows, and V groups of 32 channels (the variant that is short of

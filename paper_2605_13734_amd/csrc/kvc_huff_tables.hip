@@ -7,30 +7,33 @@ namespace kvc {
 
 // ---- table sample: histogram of up to 16 chunks per section ------------------------------------
 
+// grid = 16 sample chunks x the units of a chunk, one wave each: the wave quantizes its unit (one
+// load round trip) and counts the byte values of the packed rows.
 template <int BITS, int G, int DT, bool IS_V>
 __global__ __launch_bounds__(64) void hist_kernel(CoderArgs a)
 {
+    using Unit = UnitGeom<BITS, G, DT, IS_V>;
+    constexpr int RW = 4 * BITS;                         // words of a packed row
+    // (a whole chunk's region: the K group parameters travel through the padding of all 64 sub-blocks)
     __shared__ __attribute__((aligned(16))) uint8_t lds[ChunkGeom<BITS>::kLds];
     __shared__ uint32_t hist[256];
-    const int i = blockIdx.x, lane = lane_id();
+    const int i = blockIdx.x / Unit::kUnits, u = blockIdx.x - i * Unit::kUnits, lane = lane_id();
     const long long n = a.chunks;
     const long long chunk = (long long)i * n / 16;
     if (i > 0 && (long long)(i - 1) * n / 16 == chunk) return;      // each chunk counted once
-    for (int k = lane; k < 256; k += 64) hist[k] = 0;
     ChunkPos c = chunk_pos(a.q, chunk);
+    if (u * Unit::kRows >= c.rows) return;
+    for (int k = lane; k < 256; k += 64) hist[k] = 0;
     bool bad = false;
-    quantize_chunk<BITS, G, DT, IS_V, false>(a.q, c, lds, false, bad);
+    quantize_unit<BITS, G, DT, IS_V, false>(a.q, c, u, lds, 0, false, bad);
     wave_sync();
-    constexpr int W = ChunkGeom<BITS>::kWords;
-    uint32_t sym[W];
-    load_sub<BITS>(lds, sym);
-    const int valid = min(max(c.rows - 2 * lane, 0), 2) * (W / 2);
+    const int rows = min(c.rows - u * Unit::kRows, Unit::kRows);
+    for (int w = lane; w < rows * RW; w += 64) {
+        const int r = w / RW;
+        const uint32_t word = *(const uint32_t *)(code_row<BITS, true>(lds, r) + (w - r * RW) * 4);
 #pragma unroll
-    for (int k = 0; k < W; ++k)
-        if (k < valid) {
-#pragma unroll
-            for (int b = 0; b < 4; ++b) atomicAdd(&hist[(sym[k] >> (8 * b)) & 255u], 1u);
-        }
+        for (int b = 0; b < 4; ++b) atomicAdd(&hist[(word >> (8 * b)) & 255u], 1u);
+    }
     wave_sync();
     uint32_t *g = a.ws.hist + (IS_V ? 256 : 0);
     for (int k = lane; k < 256; k += 64)
@@ -43,9 +46,8 @@ __global__ __launch_bounds__(64) void hist_kernel(CoderArgs a)
 // smallest (weight, id) each time: leaves have id = symbol, the k-th joined node id 256 + k.
 // Leaves sorted by (weight, symbol) form one queue, joined nodes (created in non-decreasing
 // weight order) the other; the heads of the two queues are the two candidates.  The joining
-// itself is sequential (lane 0): it keeps the two front weights of either queue in registers
-// and reads one position ahead, so that no step waits for LDS.  Weights stay far below 2^32
-// (a table sample is at most 16 chunks of 16 KB).
+// itself is sequential (lane 0).  Weights stay far below 2^32 (a table sample is at most 16
+// chunks of 16 KB).
 struct BuildLds {
     uint32_t w[256];               // leaf weights by symbol
     uint32_t sw[258];              // leaf weights in queue order, then two sentinels
@@ -76,35 +78,29 @@ __device__ __forceinline__ void build_lengths(BuildLds &s)
             pos += (wt < wk || (wt == wk && t < tid)) ? 1 : 0;
         }
         s.sw[pos] = wk;
+        s.wi[tid] = kNone;                             // a joined node that does not exist yet never wins
         if (tid < 2) s.sw[256 + tid] = kNone;
         if (tid == 0) s.longest = 0;
         __syncthreads();
         if (tid == 0) {
-            uint32_t wl = s.sw[0], wl1 = s.sw[1];      // front of the leaf queue and the one behind it
-            uint32_t wj = kNone, wj1 = kNone;          // same for the queue of joined nodes
-            int lq = 0, jq = 0, made = 0;
-            for (int k = 0; k < 255; ++k) {
-                uint32_t sum = 0;
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    if (wl <= wj) {                    // a leaf wins a tie: its id is lower
-                        sum += wl;
-                        s.parent_leaf[lq] = (uint16_t)made;
-                        ++lq;
-                        wl = wl1;
-                        wl1 = s.sw[lq + 1];
-                    } else {
-                        sum += wj;
-                        s.parent_int[jq] = (uint16_t)made;
-                        ++jq;
-                        wj = wj1;
-                        wj1 = jq + 1 < made ? s.wi[jq + 1] : kNone;
-                    }
-                }
+            // Every join reads the two front entries of both queues in one go (one LDS round trip) and
+            // decides in registers; the entries it writes are read by later joins only.
+            int lq = 0, jq = 0;
+            for (int made = 0; made < 255; ++made) {
+                const uint32_t a0 = s.sw[lq], a1 = s.sw[lq + 1], b0 = s.wi[jq], b1 = s.wi[jq + 1];
+                const bool first_leaf = a0 <= b0;      // a leaf wins a tie: its id is lower
+                const uint32_t la = first_leaf ? a1 : a0, jb = first_leaf ? b0 : b1;     // the fronts after the first pick
+                const bool second_leaf = la <= jb;
+                const uint32_t sum = (first_leaf ? a0 : b0) + (second_leaf ? la : jb);
+                uint16_t *p0 = first_leaf ? &s.parent_leaf[lq] : &s.parent_int[jq];
+                lq += first_leaf ? 1 : 0;
+                jq += first_leaf ? 0 : 1;
+                uint16_t *p1 = second_leaf ? &s.parent_leaf[lq] : &s.parent_int[jq];
+                lq += second_leaf ? 1 : 0;
+                jq += second_leaf ? 0 : 1;
+                *p0 = (uint16_t)made;
+                *p1 = (uint16_t)made;
                 s.wi[made] = sum;
-                if (made == jq) wj = sum;
-                else if (made == jq + 1) wj1 = sum;
-                ++made;
             }
         }
         __syncthreads();
@@ -226,7 +222,7 @@ __global__ __launch_bounds__(kTableWaves * 64) void decode_prepare_kernel(CoderA
 template <int BITS, int G, int DT, bool IS_V> static int hist_launch(const CoderArgs &a, hipStream_t s)
 {
     if (a.chunks <= 0) return KVC_OK;
-    hipLaunchKernelGGL((hist_kernel<BITS, G, DT, IS_V>), dim3(16), dim3(64), 0, s, a);
+    hipLaunchKernelGGL((hist_kernel<BITS, G, DT, IS_V>), dim3(16 * UnitGeom<BITS, G, DT, IS_V>::kUnits), dim3(64), 0, s, a);
     return launched();
 }
 

@@ -104,6 +104,14 @@ struct CoderScratch {
     uint32_t *ticket;           // work-order counter
 };
 
+// Chunks (= waves) per encoder workgroup.  One look-back per workgroup is the encoder's serial part,
+// so the variants whose registers allow 512 threads (2- to 4-bit codes, groups of 32, fp16 rows in
+// the dense layout) take eight chunks per workgroup; 8-bit chunks need twice the LDS and take two.
+constexpr int enc_waves(int bits, int group, int dtype, bool dense)
+{
+    return bits == 8 ? 2 : (group == 32 && dtype == DT_F16 && dense) ? 8 : 4;
+}
+
 struct CoderArgs {
     QuantArgs q;                // tensor, meta, tokens, status ...
     uint8_t *payload;           // request payload base
