@@ -43,6 +43,7 @@ WORKLOADS = {
     # per-head widths: a seeded random half of the heads at 8 bits, the other half at 2 (the paper's
     # MixHQ takes the split from trained head masks, which are not available here)
     "llama70b_32k_fp16_mixhq_8_2_g32": (80, 8, 32768, "f16", 4, 4, 32, 32, 0, 0, (8, 2)),
+    "llama70b_32k_fp16_mixhq_8_2_g32_huff8": (80, 8, 32768, "f16", 4, 4, 32, 32, 1, 0, (8, 2)),
     "llama8b_8k_bf16_int4g32": (32, 8, 8192, "bf16", 4, 4, 32, 32, 0),
     "llama8b_8k_bf16_int2g64": (32, 8, 8192, "bf16", 2, 2, 64, 64, 0),
     "tiny_fp16_int4g32": (1, 8, 1024, "f16", 4, 4, 32, 32, 0),

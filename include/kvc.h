@@ -86,7 +86,9 @@ enum { KVC_CODEC_NONE = 0, KVC_CODEC_HUFF8 = 1 };
  *                     bits_k (bits_v) = 0.  kvc_plan copies the tables.  The codes of the heads
  *                     follow each other in (layer, head) order, each with its own width; the
  *                     tables travel in the payload's auxiliary section (K table, then V table).
- *                     Which head gets which width is the caller's choice.  Not with a codec.
+ *                     Which head gets which width is the caller's choice.  With a codec the chunks
+ *                     of a tensor are ordered by width (2, 3, 4, 8), then by (layer, head, chunk),
+ *                     and every width has its own code table (docs/FORMAT.md).
  *                     A plan with tables needs a workspace (kvc_workspace_size) that has been
  *                     through kvc_workspace_init.
  * Every group carries two fp16 values (scale, zero): the 32 bits per group that cap

@@ -394,7 +394,32 @@ static int bits_ok(int b) { return b == 2 || b == 3 || b == 4 || b == 8 || b == 
  * (layer, head) order, each with its own width, and the tables travel in the payload's
  * auxiliary section (K table, then V table, one byte per head).  Which head gets which width is
  * the caller's business (the paper takes it from trained head masks).
+ *
+ * Together with the lossless stage (section 5.1 composes any quantizer with any codec): the chunks of
+ * a section are then ordered by width first (2, 3, 4, 8), inside a width by (layer, head, chunk), and
+ * every width present in a tensor has its own code table, built from a sample of that width's chunks
+ * (bytes that pack four 2-bit codes and bytes that hold one 8-bit code have nothing in common).  The
+ * auxiliary section starts with eight tables of 256 length bytes, K widths 2, 3, 4, 8, then V widths
+ * 2, 3, 4, 8 (all zero for a width the tensor does not use; a tensor without a table counts as one
+ * width), then the directory in that chunk order, then the width tables.
  */
+static const int WIDTHS[4] = {2, 3, 4, 8};
+
+static int bits_at(const ref_config *c, int is_v, int64_t lh);
+
+static int has_tables(const ref_config *c) { return c->head_bits_k || c->head_bits_v; }
+
+/* bytes of code tables at the start of the auxiliary section (codec 1) */
+static int64_t code_table_bytes(const ref_config *c) { return has_tables(c) ? 8 * 256 : 2 * 256; }
+
+/* heads of tensor is_v whose width is `bits`, in (layer, head) order; returns their number */
+static int64_t heads_of_width(const ref_config *c, int is_v, int bits, int64_t *list)
+{
+    int64_t n = 0;
+    for (int64_t lh = 0; lh < (int64_t)c->layers * c->heads; ++lh)
+        if (bits_at(c, is_v, lh) == bits) { if (list) list[n] = lh; ++n; }
+    return n;
+}
 static int bits_at(const ref_config *c, int is_v, int64_t lh)
 {
     const uint8_t *t = is_v ? c->head_bits_v : c->head_bits_k;
@@ -422,7 +447,6 @@ int ref_check_config(const ref_config *c)
     if (c->layers < 1 || c->heads < 1 || c->head_dim < 8 || c->head_dim % 8) return REF_ERR_ARG;
     if ((int64_t)c->layers * c->heads > MAX_HEADS || c->head_dim > 1024) return REF_ERR_ARG;
     if (!table_ok(c, 0) || !table_ok(c, 1)) return REF_ERR_ARG;
-    if ((c->head_bits_k || c->head_bits_v) && c->codec) return REF_ERR_UNSUPPORTED;
     if ((!c->head_bits_k && !bits_ok(c->bits_k)) || (!c->head_bits_v && !bits_ok(c->bits_v))) return REF_ERR_ARG;
     if (c->bits_k != 16 && (c->group_k < 1 || c->group_k > CHUNK_ROWS || CHUNK_ROWS % c->group_k))
         return REF_ERR_ARG;
@@ -474,7 +498,7 @@ static void layout_of(const ref_config *c, int64_t T, geometry *g)
         g->codes_v += T * D * bits_at(c, 1, lh) / 8;
     }
     g->chunks_k = g->chunks_v = LH * ref_chunks_per_head(T);
-    g->aux = c->codec ? 512 + 4 * (g->chunks_k + g->chunks_v + 1) : 0;
+    g->aux = c->codec ? code_table_bytes(c) + 4 * (g->chunks_k + g->chunks_v + 1) : 0;
     g->aux += (c->head_bits_k ? LH : 0) + (c->head_bits_v ? LH : 0);
     g->anchors_k = 2 * LH * anchor_rows(c, 0, T) * D;
     g->anchors_v = 2 * LH * anchor_rows(c, 1, T) * D;
@@ -783,6 +807,8 @@ int ref_inspect(const uint8_t *p, ref_config *c, int64_t *tokens, uint64_t *tota
         int64_t LH = (int64_t)c->layers * c->heads;
         const uint8_t *aux = p + get_u64(p + 80);
         if (p[27] & ~3) return REF_ERR_FORMAT;
+        if (c->codec && p[27])       /* behind the eight code tables and the directory */
+            aux += 8 * 256 + 4 * (2 * LH * ref_chunks_per_head((int64_t)get_u64(p + 32)) + 1);
         if (p[27] & 1) { c->head_bits_k = aux; aux += LH; }
         if (p[27] & 2) c->head_bits_v = aux;
     }
@@ -841,50 +867,64 @@ int ref_compress(const ref_config *c, const void *k, const void *v, const ref_la
                 if (rc) return rc;
             }
     }
-    if (!c->codec) {
-        uint8_t *tab = payload + g.off_aux;
+    {
+        /* the width tables follow the coder's tables and directory (if any) */
         int64_t LH = (int64_t)c->layers * c->heads;
+        uint8_t *tab = payload + g.off_aux + (c->codec ? code_table_bytes(c) + 4 * (g.chunks_k + g.chunks_v + 1) : 0);
         if (c->head_bits_k) { memcpy(tab, c->head_bits_k, (size_t)LH); tab += LH; }
         if (c->head_bits_v) memcpy(tab, c->head_bits_v, (size_t)LH);
+    }
+    if (!c->codec) {
         write_header(payload, c, T, &g, g.codes_k, g.codes_v, g.total);
         if (out_bytes) *out_bytes = (uint64_t)g.total;
         return REF_OK;
     }
 
-    /* C: tables from the sample, then chunk after chunk; the directory holds the running
-     * sum of body sizes in units of 16 bytes (entry i = where chunk i starts, K chunks
-     * first, one more entry for the end). */
+    /* C: per tensor and width, a table from the sample, then chunk after chunk; the directory holds
+     * the running sum of body sizes in units of 16 bytes (entry i = where chunk i starts, K chunks
+     * first, one more entry for the end).  Without width tables a tensor is one width and the
+     * chunk order is (layer, head, chunk). */
     uint8_t *aux = payload + g.off_aux;
+    const int64_t tab_bytes = code_table_bytes(c), LHall = (int64_t)c->layers * c->heads;
     int64_t cph = ref_chunks_per_head(T), dir = 0, idx = 0, bytes_codes[2];
     uint8_t *out = payload + g.off_codes_k;
+    int64_t *list = (int64_t *)malloc(sizeof(int64_t) * (size_t)(LHall + 1));
+    if (!list) return REF_ERR_ARG;
     for (int is_v = 0; is_v < 2; ++is_v) {
-        int row_bytes = c->head_dim * (is_v ? c->bits_v : c->bits_k) / 8;
-        int64_t n = is_v ? g.chunks_v : g.chunks_k, start = dir;
-        uint32_t hist[256];
-        int64_t last = -1;
-        memset(hist, 0, sizeof hist);
-        for (int i = 0; i < 16 && n > 0; ++i) {
-            int64_t ch = (int64_t)i * n / 16;
-            if (ch == last) continue;
-            last = ch;
-            int64_t lh = ch / cph, cb = ch % cph;
-            int64_t r0 = cb * CHUNK_ROWS, r1 = r0 + CHUNK_ROWS > T ? T : r0 + CHUNK_ROWS;
-            const uint8_t *raw = codes[is_v] + (lh * T + r0) * row_bytes;
-            for (int64_t b = 0; b < (r1 - r0) * row_bytes; ++b) hist[raw[b]]++;
-        }
-        uint8_t *len = aux + 256 * is_v;
-        ref_huff_lengths(hist, len);
-        for (int64_t ch = 0; ch < n; ++ch, ++idx) {
-            int64_t lh = ch / cph, cb = ch % cph;
-            int64_t r0 = cb * CHUNK_ROWS, r1 = r0 + CHUNK_ROWS > T ? T : r0 + CHUNK_ROWS;
-            put_u32(aux + 512 + 4 * idx, (uint32_t)(dir / 16));
-            dir += ref_huff_encode_chunk(codes[is_v] + (lh * T + r0) * row_bytes, (int)(r1 - r0),
-                                         row_bytes, len, out + dir);
+        int64_t start = dir;
+        for (int wi = 0; wi < 5; ++wi) {
+            int bits = wi < 4 ? WIDTHS[wi] : 16;                 /* (16 never occurs with the coder) */
+            int64_t heads_w = heads_of_width(c, is_v, bits, list);
+            if (heads_w == 0 || bits == 16) continue;
+            int row_bytes = c->head_dim * bits / 8;
+            int64_t n = heads_w * cph;
+            uint32_t hist[256];
+            int64_t last = -1;
+            memset(hist, 0, sizeof hist);
+            for (int i = 0; i < 16 && n > 0; ++i) {
+                int64_t ch = (int64_t)i * n / 16;
+                if (ch == last) continue;
+                last = ch;
+                int64_t lh = list[ch / cph], cb = ch % cph;
+                int64_t r0 = cb * CHUNK_ROWS, r1 = r0 + CHUNK_ROWS > T ? T : r0 + CHUNK_ROWS;
+                const uint8_t *raw = codes[is_v] + head_code_off(c, is_v, T, lh, NULL) + r0 * row_bytes;
+                for (int64_t b = 0; b < (r1 - r0) * row_bytes; ++b) hist[raw[b]]++;
+            }
+            uint8_t *len = aux + 256 * (has_tables(c) ? 4 * is_v + wi : is_v);
+            ref_huff_lengths(hist, len);
+            for (int64_t ch = 0; ch < n; ++ch, ++idx) {
+                int64_t lh = list[ch / cph], cb = ch % cph;
+                int64_t r0 = cb * CHUNK_ROWS, r1 = r0 + CHUNK_ROWS > T ? T : r0 + CHUNK_ROWS;
+                put_u32(aux + tab_bytes + 4 * idx, (uint32_t)(dir / 16));
+                dir += ref_huff_encode_chunk(codes[is_v] + head_code_off(c, is_v, T, lh, NULL) + r0 * row_bytes,
+                                             (int)(r1 - r0), row_bytes, len, out + dir);
+            }
         }
         bytes_codes[is_v] = dir - start;
         free(codes[is_v]);
     }
-    put_u32(aux + 512 + 4 * idx, (uint32_t)(dir / 16));
+    free(list);
+    put_u32(aux + tab_bytes + 4 * idx, (uint32_t)(dir / 16));
     int64_t total = g.off_codes_k + dir;
     write_header(payload, c, T, &g, bytes_codes[0], bytes_codes[1], total);
     if (out_bytes) *out_bytes = (uint64_t)total;
@@ -904,7 +944,7 @@ int ref_decompress(const uint8_t *payload, uint64_t bytes, void *k, void *v,
     {
         int64_t LH = (int64_t)c.layers * c.heads;
         uint64_t tables = (uint64_t)((c.head_bits_k ? LH : 0) + (c.head_bits_v ? LH : 0));
-        if (tables && (sec[4] + tables > total || c.codec)) return REF_ERR_FORMAT;
+        if (tables && sec[4] + sec[5] > total) return REF_ERR_FORMAT;
         if (ref_check_config(&c) != REF_OK) return REF_ERR_FORMAT;
         if (expect) {
             ref_config a = *expect, b = c;
@@ -927,29 +967,38 @@ int ref_decompress(const uint8_t *payload, uint64_t bytes, void *k, void *v,
         return REF_ERR_FORMAT;
 
     const uint8_t *aux = payload + g.off_aux;
+    const int64_t tab_bytes = code_table_bytes(&c), LHall = (int64_t)c.layers * c.heads;
     int64_t cph = ref_chunks_per_head(T);
+    int64_t *place = (int64_t *)malloc(sizeof(int64_t) * (size_t)(LHall + 1));    /* head -> rank in the chunk order */
+    int64_t *list = (int64_t *)malloc(sizeof(int64_t) * (size_t)(LHall + 1));
+    if (!place || !list) { free(place); free(list); return REF_ERR_ARG; }
     for (int is_v = 0; is_v < 2; ++is_v) {
-        int row_bytes = c.head_dim * (is_v ? c.bits_v : c.bits_k) / 8;
-        int64_t hb = head_code_bytes(&c, is_v, T), hm = head_meta_pairs(&c, is_v, T) * 4;
+        int64_t hm = head_meta_pairs(&c, is_v, T) * 4, at = 0;
+        for (int wi = 0; wi < 4; ++wi) {              /* chunk order: by width, then (layer, head) */
+            int64_t n = heads_of_width(&c, is_v, WIDTHS[wi], list);
+            for (int64_t i = 0; i < n; ++i) place[list[i]] = at++;
+        }
         const uint8_t *mbase = payload + (is_v ? g.off_meta_v : g.off_meta_k);
-        uint8_t *head = (uint8_t *)malloc((size_t)hb + 1);
-        if (!head) return REF_ERR_ARG;
+        uint8_t *head = (uint8_t *)malloc((size_t)(T * c.head_dim) + 1);              /* room for 8-bit codes */
+        if (!head) { free(place); free(list); return REF_ERR_ARG; }
         for (int l = 0; l < c.layers; ++l)
             for (int h = 0; h < c.heads; ++h) {
                 int64_t lh = (int64_t)l * c.heads + h;
                 const uint8_t *codes = payload + (is_v ? g.off_codes_v : g.off_codes_k) +
                                        head_code_off(&c, is_v, T, lh, NULL);
                 if (c.codec) {
+                    int bits = bits_at(&c, is_v, lh), wi = bits == 2 ? 0 : bits == 3 ? 1 : bits == 4 ? 2 : 3;
+                    int row_bytes = c.head_dim * bits / 8;
+                    const uint8_t *len = aux + 256 * (has_tables(&c) ? 4 * is_v + wi : is_v);
                     for (int64_t cb = 0; cb < cph; ++cb) {
-                        int64_t idx = (is_v ? g.chunks_k : 0) + lh * cph + cb;
-                        uint64_t a = 16ull * get_u32(aux + 512 + 4 * idx);
-                        uint64_t b = 16ull * get_u32(aux + 512 + 4 * (idx + 1));
+                        int64_t idx = (is_v ? g.chunks_k : 0) + place[lh] * cph + cb;
+                        uint64_t a = 16ull * get_u32(aux + tab_bytes + 4 * idx);
+                        uint64_t b = 16ull * get_u32(aux + tab_bytes + 4 * (idx + 1));
                         int64_t r0 = cb * CHUNK_ROWS, r1 = r0 + CHUNK_ROWS > T ? T : r0 + CHUNK_ROWS;
-                        if (b < a || (uint64_t)g.off_codes_k + b > total) { free(head); return REF_ERR_FORMAT; }
+                        if (b < a || (uint64_t)g.off_codes_k + b > total) { free(head); free(place); free(list); return REF_ERR_FORMAT; }
                         rc = ref_huff_decode_chunk(payload + g.off_codes_k + a, (int64_t)(b - a),
-                                                   (int)(r1 - r0), row_bytes, aux + 256 * is_v,
-                                                   head + r0 * row_bytes);
-                        if (rc) { free(head); return rc; }
+                                                   (int)(r1 - r0), row_bytes, len, head + r0 * row_bytes);
+                        if (rc) { free(head); free(place); free(list); return rc; }
                     }
                     codes = head;
                 }
@@ -957,9 +1006,11 @@ int ref_decompress(const uint8_t *payload, uint64_t bytes, void *k, void *v,
                                           lh * anchor_rows(&c, is_v, T) * c.head_dim;
                 rc = ref_decompress_head(&c, is_v, codes, (const uint16_t *)(mbase + lh * hm), anchors,
                                          T, l, h, is_v ? v : k, lay);
-                if (rc) { free(head); return rc; }
+                if (rc) { free(head); free(place); free(list); return rc; }
             }
         free(head);
     }
+    free(place);
+    free(list);
     return REF_OK;
 }

@@ -54,7 +54,8 @@ typedef struct {
                                    2 delta against an anchor token (ref_delta_row) */
     int32_t anchor_period;      /* transform 2: tokens per run, a power of two in 8..128; else 0 */
     /* optional per-head bit widths, index l*heads + h, values 2, 3, 4 or 8; when a table is
-     * given the uniform width of that tensor (bits_k / bits_v) must be 0.  Not with codec 1. */
+     * given the uniform width of that tensor (bits_k / bits_v) must be 0.  With codec 1 the chunks
+     * are ordered by width and every width has its own code table (see kvc_ref.c). */
     const uint8_t *head_bits_k, *head_bits_v;
 } ref_config;
 

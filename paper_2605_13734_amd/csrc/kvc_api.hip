@@ -118,8 +118,13 @@ static void geometry(const kvc_plan_t *p, long long T, Geometry *g)
     g->codes_k = sum_k * T * D / 8;
     g->codes_v = sum_v * T * D / 8;
     g->chunks_k = g->chunks_v = LH * chunks_per_head(T);
-    g->aux = p->strat.codec ? 512 + 4 * (g->chunks_k + g->chunks_v + 1) : 0;
-    g->aux += (p->has_table[0] + p->has_table[1]) * LH;
+    // with the coder: its tables (one per tensor, or one per tensor and width when there are width
+    // tables), then the directory; then the width tables
+    g->code_tables = p->strat.codec ? 256 * ((p->has_table[0] || p->has_table[1]) ? kTableSlots : 2) : 0;
+    g->aux = p->strat.codec ? g->code_tables + 4 * (g->chunks_k + g->chunks_v + 1) : 0;
+    g->widths = (p->has_table[0] + p->has_table[1]) * LH;
+    const long long widths_at = g->aux;
+    g->aux += g->widths;
     g->aux_base = g->aux;
     g->anchors_k = 2 * LH * anchor_rows(p, 0, T) * D;
     g->anchors_v = 2 * LH * anchor_rows(p, 1, T) * D;
@@ -127,6 +132,8 @@ static void geometry(const kvc_plan_t *p, long long T, Geometry *g)
     g->off_meta_k = kHeader;
     g->off_meta_v = g->off_meta_k + a16(g->meta_k);
     g->off_aux = g->off_meta_v + a16(g->meta_v);
+    g->off_dir = g->off_aux + g->code_tables;
+    g->off_widths = g->off_aux + widths_at;
     g->off_codes_k = g->off_aux + a16(g->aux);
     g->off_anchors_k = g->off_codes_k - g->anchors_v - g->anchors_k;
     g->off_anchors_v = g->off_codes_k - g->anchors_v;
@@ -214,7 +221,6 @@ static int check_pair(const kvc_model *m, const kvc_strategy *s)
         if (a < 8 || a > 128 || (a & (a - 1))) return KVC_ERR_ARG;
     } else if (s->anchor_period != 0) return KVC_ERR_ARG;
     if (s->transform == KVC_T_DELTA && s->anchor_period < kPassRows) return KVC_ERR_UNSUPPORTED;   // the kernels take one anchor per pass
-    if (s->codec && (s->head_bits_k || s->head_bits_v)) return KVC_ERR_UNSUPPORTED;
     if (s->codec && (s->bits_k == 16 || s->bits_v == 16)) return KVC_ERR_UNSUPPORTED;
     return KVC_OK;
 }
@@ -265,7 +271,7 @@ extern "C" int kvc_plan(const kvc_model *model, const kvc_strategy *strategy, in
         // histograms, encode tables, decode tables, ticket, then the scan state
         // one scan-state word per chunk of K and of V
         const long long chunks = (long long)model->layers * model->kv_heads * chunks_per_head(max_tokens);
-        p->ws_state_off = a256(2 * 256 * 4) + a256(2 * 256 * 4) + a256(2 * 4096 * 2) + 256;
+        p->ws_state_off = 2 * a256(kTableSlots * 256 * 4) + a256(kTableSlots * 4096 * 2) + 256;
         p->ws_request = p->ws_state_off + a256((size_t)(2 * chunks) * 8 + 8);
     }
     *out = p;
@@ -324,7 +330,6 @@ extern "C" int kvc_payload_inspect(const void *header128, kvc_model *model, kvc_
     if (flags & 2) { if (s.bits_v) return KVC_ERR_FORMAT; probe.bits_v = 4; }
     int rc = check_pair(&m, &probe);
     if (rc == KVC_ERR_ARG || T < 0 || T > kMaxTokens) return KVC_ERR_FORMAT;
-    if (flags && s.codec) return KVC_ERR_FORMAT;
     if (h[30] | h[31]) return KVC_ERR_FORMAT;
     // the fixed part of the section table must be the closed form of the fields above
     kvc_plan_t tmp;
@@ -341,12 +346,15 @@ extern "C" int kvc_payload_inspect(const void *header128, kvc_model *model, kvc_
     for (int i = 0; i < 7; ++i)
         if (get64(h + 48 + 8 * i) != want[i]) return KVC_ERR_FORMAT;
     const uint64_t total = get64(h + 40), ck = get64(h + 104), ov = get64(h + 112), cv = get64(h + 120);
-    if (flags) {
-        // code sizes follow from the width tables, which are not in the header: only their
-        // consistency and the bounds that hold for any table (2 to 8 bits per element) are checked
-        const uint64_t unit = (uint64_t)m.layers * m.kv_heads * (uint64_t)T * 16;      // bytes per bit of width
-        const uint64_t lo_k = (flags & 1) ? 2 * unit : (uint64_t)s.bits_k * unit, hi_k = (flags & 1) ? 8 * unit : lo_k;
-        const uint64_t lo_v = (flags & 2) ? 2 * unit : (uint64_t)s.bits_v * unit, hi_v = (flags & 2) ? 8 * unit : lo_v;
+    // with width tables the code sizes follow from the tables, which are not in the header: only the
+    // bounds that hold for any table (2 to 8 bits per element) are known here
+    const uint64_t unit = (uint64_t)m.layers * m.kv_heads * (uint64_t)T * 16;      // bytes per bit of width
+    const uint64_t lo_k = (flags & 1) ? 2 * unit : (uint64_t)s.bits_k * unit, hi_k = (flags & 1) ? 8 * unit : lo_k;
+    const uint64_t lo_v = (flags & 2) ? 2 * unit : (uint64_t)s.bits_v * unit, hi_v = (flags & 2) ? 8 * unit : lo_v;
+    if (flags && s.codec) {
+        if (ov != (uint64_t)g.off_codes_k + ck || total != ov + cv || (ck & 15) || (cv & 15) || ck > hi_k || cv > hi_v)
+            return KVC_ERR_FORMAT;
+    } else if (flags) {
         if (ck < lo_k || ck > hi_k || cv < lo_v || cv > hi_v || ov != (uint64_t)g.off_codes_k + (uint64_t)a16((long long)ck) ||
             total != ov + (uint64_t)a16((long long)cv))
             return KVC_ERR_FORMAT;
@@ -479,33 +487,75 @@ extern "C" int kvc_workspace_init(const kvc_plan_t *plan, void *workspace, void 
                ? KVC_OK : KVC_ERR_DEVICE;
 }
 
-static CoderArgs coder_args(const kvc_plan_t *p, const QuantArgs &q, int is_v, uint8_t *payload,
-                            const Geometry &g, uint8_t *ws, long long capacity, uint64_t *out_bytes)
+// The coder launches of one request, in chunk order: K before V; a tensor with a width table is one
+// launch per width present (2, 3, 4, 8) over the heads of that width, otherwise one launch.
+struct CoderLaunch {
+    CoderArgs a;
+    int bits, group;
+};
+
+
+static int coder_launches(const kvc_plan_t *p, const kvc_request *r, uint8_t *payload, const Geometry &g, uint8_t *ws,
+                          long long capacity, uint64_t *out_bytes, int *status, bool compress, const uint8_t *dev_tables,
+                          CoderLaunch out[kTableSlots])
 {
-    CoderArgs c;
-    memset(&c, 0, sizeof c);
-    c.q = q;
-    c.payload = payload;
-    c.off_aux = g.off_aux;
-    c.off_bodies = g.off_codes_k;
-    c.capacity = capacity;
-    c.chunks = is_v ? g.chunks_v : g.chunks_k;
-    c.chunk_base = is_v ? g.chunks_k : 0;
-    c.total_chunks = g.chunks_k + g.chunks_v;
-    // chunks per encode workgroup
-    const int nw_k = enc_waves(p->strat.bits_k, p->strat.group_k, p->model.dtype, q.dense != 0);
-    const int nw_v = enc_waves(p->strat.bits_v, p->strat.group_v, p->model.dtype, q.dense != 0);
-    const long long wg_k = (g.chunks_k + nw_k - 1) / nw_k, wg_v = (g.chunks_v + nw_v - 1) / nw_v;
-    c.wg_base = is_v ? wg_k : 0;
-    c.total_wgs = wg_k + wg_v;
-    c.is_v = is_v;
-    c.ws.hist = (uint32_t *)ws;
-    c.ws.enc = (uint32_t *)(ws + a256(2 * 256 * 4));
-    c.ws.lut = (uint16_t *)(ws + 2 * a256(2 * 256 * 4));
-    c.ws.ticket = (uint32_t *)(ws + 2 * a256(2 * 256 * 4) + a256(2 * 4096 * 2));
-    c.ws.state = (unsigned long long *)(ws + p->ws_state_off);
-    c.out_bytes = (unsigned long long *)out_bytes;
-    return c;
+    const bool any_table = p->has_table[0] || p->has_table[1];
+    const long long LH = (long long)p->model.layers * p->model.kv_heads, cph = chunks_per_head(r->tokens);
+    const TableLayout t = table_layout(LH, p->has_table[0] + p->has_table[1]);
+    CoderArgs base;
+    memset(&base, 0, sizeof base);
+    base.payload = payload;
+    base.off_aux = g.off_aux;
+    base.off_dir = g.off_dir;
+    base.off_bodies = g.off_codes_k;
+    base.capacity = capacity;
+    base.total_chunks = g.chunks_k + g.chunks_v;
+    base.slots = any_table ? kTableSlots : 2;
+    base.ws.hist = (uint32_t *)ws;
+    base.ws.enc = (uint32_t *)(ws + a256(kTableSlots * 256 * 4));
+    base.ws.lut = (uint16_t *)(ws + 2 * a256(kTableSlots * 256 * 4));
+    base.ws.ticket = (uint32_t *)(ws + 2 * a256(kTableSlots * 256 * 4) + a256(kTableSlots * 4096 * 2));
+    base.ws.state = (unsigned long long *)(ws + p->ws_state_off);
+    base.out_bytes = (unsigned long long *)out_bytes;
+    int n = 0, mask = 0;
+    long long chunk_at = 0, wg_at = 0, k_wgs = 0;
+    for (int is_v = 0; is_v < 2; ++is_v) {
+        const QuantArgs q = quant_args(p, r, is_v, payload, g, status, compress);
+        const int group = is_v ? p->strat.group_v : p->strat.group_k;
+        const int *list = p->has_table[is_v] ? (const int *)(dev_tables + t.head_list[is_v]) : nullptr;
+        for (int w = 0; w < 4; ++w) {
+            long long heads = 0;
+            if (p->has_table[is_v]) heads = p->width_count[is_v][w];
+            else if (kWidths[w] == (is_v ? p->strat.bits_v : p->strat.bits_k)) heads = LH;
+            if (heads == 0) continue;
+            CoderLaunch &L = out[n++];
+            L.a = base;
+            L.a.q = q;
+            L.a.q.head_list = list;                    // (null without a table: the heads in their own order)
+            if (list) {
+                L.a.q.bits_before = (const long long *)(dev_tables + t.bits_before[is_v]);
+                list += heads;
+            }
+            L.bits = kWidths[w];
+            L.group = group;
+            L.a.is_v = is_v;
+            L.a.tab = any_table ? 4 * is_v + w : is_v;
+            L.a.chunks = heads * cph;
+            L.a.chunk_base = chunk_at;
+            L.a.wg_base = wg_at;
+            const int nw = enc_waves(L.bits, group, p->model.dtype, q.dense != 0);
+            chunk_at += L.a.chunks;
+            wg_at += (L.a.chunks + nw - 1) / nw;
+            mask |= 1 << L.a.tab;
+        }
+        if (!is_v) k_wgs = wg_at;
+    }
+    for (int i = 0; i < n; ++i) {
+        out[i].a.k_wgs = k_wgs;
+        out[i].a.total_wgs = wg_at;
+        out[i].a.slot_mask = mask;
+    }
+    return n;
 }
 
 static int check_batch(const kvc_plan_t *p, const kvc_request *reqs, int32_t n, const void *payload,
@@ -559,11 +609,13 @@ static int compress_on(const kvc_plan_t *plan, const kvc_request *reqs, int32_t 
             it.pad_off[1] = g.off_aux + g.aux_base;
             it.pad_words[1] = (a16(g.aux_base) - g.aux_base) / 4;
             if (plan->blob_bytes) {
-                // the width tables and their padding: a copy of the image at the start of the workspace
+                // the width tables: a copy of the image at the start of the workspace (whole words; the
+                // image is zero behind the tables), then zero up to the next 16-byte boundary
                 it.aux_src = (const uint32_t *)workspace;
-                it.aux_off = g.off_aux;
-                it.aux_words = a16(g.aux_base) / 4;
-                it.pad_words[1] = 0;
+                it.aux_off = g.off_widths;
+                it.aux_words = (g.widths + 3) / 4;
+                it.pad_off[1] = g.off_widths + 4 * it.aux_words;
+                it.pad_words[1] = (g.off_aux + a16(g.aux_base) - it.pad_off[1]) / 4;
             }
             it.out_bytes = (unsigned long long *)(out_bytes + i);
             it.status = dev_status + i;
@@ -572,17 +624,21 @@ static int compress_on(const kvc_plan_t *plan, const kvc_request *reqs, int32_t 
                 it.write_total = 1;
             } else {
                 uint8_t *ws = (uint8_t *)workspace + plan->blob_bytes + (size_t)i * plan->ws_request;
-                CoderArgs c = coder_args(plan, quant_args(plan, &reqs[i], 0, pl, g, dev_status + i, true), 0, pl, g, ws, 0, nullptr);
+                CoderLaunch cl[kTableSlots];
+                const int launches = coder_launches(plan, &reqs[i], pl, g, ws, 0, nullptr, dev_status + i, true,
+                                                    (const uint8_t *)workspace, cl);
+                const CoderArgs &c = cl[0].a;              // (a request has at least one K and one V launch)
+                (void)launches;
                 // histograms, ticket and scan state start from zero
                 it.zero[0] = c.ws.hist;
-                it.zero_words[0] = 2 * 256;
+                it.zero_words[0] = kTableSlots * 256;
                 it.zero[1] = c.ws.ticket;
                 it.zero_words[1] = 64 + 2 * c.total_wgs + 2;
                 if (c.total_chunks == 0) {
                     // empty request: no workgroup runs that could close the directory and header
                     put64((uint8_t *)it.header.w + 40, (uint64_t)g.off_codes_k);
                     put64((uint8_t *)it.header.w + 112, (uint64_t)g.off_codes_k);
-                    it.dir0 = (uint32_t *)(pl + g.off_aux + 512);
+                    it.dir0 = (uint32_t *)(pl + g.off_dir);
                     it.total = (unsigned long long)g.off_codes_k;
                     it.write_total = 1;
                 }
@@ -607,13 +663,17 @@ static int compress_on(const kvc_plan_t *plan, const kvc_request *reqs, int32_t 
         } else {
             uint8_t *ws = (uint8_t *)workspace + plan->blob_bytes + (size_t)i * plan->ws_request;
             const long long cap = (long long)(payload_off[i + 1] - payload_off[i]);
-            CoderArgs ck = coder_args(plan, qk, 0, pl, g, ws, cap, out_bytes + i);
-            CoderArgs cv = coder_args(plan, qv, 1, pl, g, ws, cap, out_bytes + i);
-            KVC_TRY(launch_coder_tables(st.bits_k, st.bits_v, st.group_k, st.group_v, dt, ck, cv, s));
+            CoderLaunch cl[kTableSlots];
+            const int launches = coder_launches(plan, r, pl, g, ws, cap, out_bytes + i, dev_status + i, true,
+                                                (const uint8_t *)workspace, cl);
+            for (int j = 0; j < launches; ++j) KVC_TRY(launch_table_sample(cl[j].bits, cl[j].group, dt, cl[j].a, s));
+            KVC_TRY(launch_build_tables(cl[0].a, s));
             mark(plan, s);
-            KVC_TRY(launch_encode_section(st.bits_k, st.group_k, dt, ck, s));
+            for (int j = 0; j < launches; ++j)
+                if (!cl[j].a.is_v) KVC_TRY(launch_encode_section(cl[j].bits, cl[j].group, dt, cl[j].a, s));
             mark(plan, s);
-            KVC_TRY(launch_encode_section(st.bits_v, st.group_v, dt, cv, s));
+            for (int j = 0; j < launches; ++j)
+                if (cl[j].a.is_v) KVC_TRY(launch_encode_section(cl[j].bits, cl[j].group, dt, cl[j].a, s));
             mark(plan, s);
         }
     }
@@ -696,9 +756,9 @@ extern "C" int kvc_decompress(const kvc_plan_t *plan, const void *payload, const
             // words 10/11 (total), 26..31 (code sizes) depend on the data when the coder is on
             it.mask = st.codec ? 0x03fff3ffu : 0xffffffffu;
             if (plan->blob_bytes) {       // the payload's width tables must be the plan's
-                it.tables = pl + g.off_aux;
+                it.tables = pl + g.off_widths;
                 it.plan_tables = (const uint8_t *)workspace;
-                it.table_bytes = g.aux_base;
+                it.table_bytes = g.widths;
             }
             it.status = dev_status + i;
         }
@@ -721,13 +781,16 @@ extern "C" int kvc_decompress(const kvc_plan_t *plan, const void *payload, const
             mark(plan, s);
         } else {
             uint8_t *ws = (uint8_t *)workspace + plan->blob_bytes + (size_t)i * plan->ws_request;
-            CoderArgs ck = coder_args(plan, qk, 0, pl, g, ws, cap, nullptr);
-            CoderArgs cv = coder_args(plan, qv, 1, pl, g, ws, cap, nullptr);
-            KVC_TRY(launch_decode_prepare(ck, s));
+            CoderLaunch cl[kTableSlots];
+            const int launches = coder_launches(plan, r, pl, g, ws, cap, nullptr, dev_status + i, false,
+                                                (const uint8_t *)workspace, cl);
+            KVC_TRY(launch_decode_prepare(cl[0].a, s));
             mark(plan, s);
-            KVC_TRY(launch_decode_section(st.bits_k, st.group_k, dt, ck, s));
+            for (int j = 0; j < launches; ++j)
+                if (!cl[j].a.is_v) KVC_TRY(launch_decode_section(cl[j].bits, cl[j].group, dt, cl[j].a, s));
             mark(plan, s);
-            KVC_TRY(launch_decode_section(st.bits_v, st.group_v, dt, cv, s));
+            for (int j = 0; j < launches; ++j)
+                if (cl[j].a.is_v) KVC_TRY(launch_decode_section(cl[j].bits, cl[j].group, dt, cl[j].a, s));
             mark(plan, s);
         }
     }

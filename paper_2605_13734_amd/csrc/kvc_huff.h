@@ -72,8 +72,9 @@ __device__ __forceinline__ ChunkPos chunk_pos(const QuantArgs &a, long long chun
 {
     ChunkPos c;
     const long long cph = (a.tokens + kChunkRows - 1) / kChunkRows;
-    c.lh = chunk / cph;
-    c.cb = chunk - c.lh * cph;
+    const long long slot = chunk / cph;                 // with per-head widths: the slot-th head of this launch's width
+    c.lh = a.head_list ? a.head_list[slot] : slot;
+    c.cb = chunk - slot * cph;
     const long long l = c.lh / a.heads, h = c.lh - l * a.heads;
     c.head_off = l * a.x.stride_layer + h * a.x.stride_head;
     c.row0 = c.cb * kChunkRows;

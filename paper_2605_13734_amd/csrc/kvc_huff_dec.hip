@@ -137,7 +137,7 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
     unsigned long long d0 = 0, d1 = 0;
     int st = 0;
     if (live) {
-        const uint32_t *dir = (const uint32_t *)(a.payload + a.off_aux + 512) + a.chunk_base + chunk;
+        const uint32_t *dir = (const uint32_t *)(a.payload + a.off_dir) + a.chunk_base + chunk;
         d0 = dir[0];
         d1 = dir[1];
         st = *a.q.status;
@@ -145,7 +145,7 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
     constexpr int LUTN = 512 / (NW * 64);
     u32x4 lutv[LUTN];
     {
-        const u32x4 *src = (const u32x4 *)(a.ws.lut + (IS_V ? 4096 : 0));
+        const u32x4 *src = (const u32x4 *)(a.ws.lut + 4096 * a.tab);
 #pragma unroll
         for (int i = 0; i < LUTN; ++i) lutv[i] = src[tid + i * NW * 64];
     }

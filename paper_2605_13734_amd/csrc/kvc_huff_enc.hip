@@ -128,7 +128,7 @@ void encode_kernel(CoderArgs a)
     const int tid = threadIdx.x, wave = wave_id(), lane = lane_id();
     if (tid == 0) s_ticket = atomicAdd(a.ws.ticket, 1u);
     for (int k = tid; k < 256; k += NW * 64) {
-        const uint32_t e = a.ws.enc[(IS_V ? 256 : 0) + k];       // code | length << 16
+        const uint32_t e = a.ws.enc[256 * a.tab + k];             // code | length << 16
         enc.len[k] = (uint8_t)(e >> 16);
         enc.code[k] = (uint16_t)((e & 0xfffu) | ((e >> 16) << 12));
     }
@@ -245,13 +245,11 @@ void encode_kernel(CoderArgs a)
             if (ticket == a.total_wgs - 1 && !timeout) {
                 // the very last workgroup closes the directory and the header
                 const unsigned long long all = excl + agg;
-                uint32_t *dir = (uint32_t *)(a.payload + a.off_aux + 512);
+                uint32_t *dir = (uint32_t *)(a.payload + a.off_dir);
                 dir[a.total_chunks] = (uint32_t)all;
-                unsigned long long k_units = 0;
-                if (a.wg_base > 0)
-                    k_units = __hip_atomic_load(&a.ws.state[a.wg_base - 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kValueMask;
-                else if (!IS_V)
-                    k_units = all;
+                unsigned long long k_units = all;          // (this is the last K workgroup only if V has no chunks)
+                if (IS_V)
+                    k_units = a.k_wgs > 0 ? __hip_atomic_load(&a.ws.state[a.k_wgs - 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kValueMask : 0;
                 const unsigned long long total = (unsigned long long)a.off_bodies + all * 16;
                 unsigned long long *h = (unsigned long long *)a.payload;
                 h[5] = total;                                   // byte 40: total bytes
@@ -267,7 +265,7 @@ void encode_kernel(CoderArgs a)
     if (!live || excl == ~0ull) return;
     unsigned long long mine = excl;
     for (int w = 0; w < wave; ++w) mine += s_units[w];
-    if (lane == 0) ((uint32_t *)(a.payload + a.off_aux + 512))[a.chunk_base + chunk] = (uint32_t)mine;
+    if (lane == 0) ((uint32_t *)(a.payload + a.off_dir))[a.chunk_base + chunk] = (uint32_t)mine;
     uint8_t *dst = a.payload + a.off_bodies + mine * 16;
     if ((long long)(a.off_bodies + (mine + body_units) * 16) > a.capacity) return;      // cannot happen: bodies never exceed raw size
     if (coded) {

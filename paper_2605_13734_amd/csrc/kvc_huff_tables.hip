@@ -35,7 +35,7 @@ __global__ __launch_bounds__(64) void hist_kernel(CoderArgs a)
         for (int b = 0; b < 4; ++b) atomicAdd(&hist[(word >> (8 * b)) & 255u], 1u);
     }
     wave_sync();
-    uint32_t *g = a.ws.hist + (IS_V ? 256 : 0);
+    uint32_t *g = a.ws.hist + 256 * a.tab;
     for (int k = lane; k < 256; k += 64)
         if (hist[k]) atomicAdd(&g[k], hist[k]);
 }
@@ -119,9 +119,13 @@ __device__ __forceinline__ void build_lengths(BuildLds &s)
 
 constexpr int kTableWaves = 8;      // waves that fill a decode table
 
-// grid = 2 workgroups of 256 threads (one symbol each): 0 builds the K table, 1 the V table
+// grid = one workgroup of 256 threads (one symbol each) per table slot of the format
 __global__ __launch_bounds__(256) void build_tables_kernel(CoderArgs a)
 {
+    if (!((a.slot_mask >> blockIdx.x) & 1)) {          // a width the tensor does not use: an empty table
+        a.payload[a.off_aux + 256 * blockIdx.x + threadIdx.x] = 0;
+        return;
+    }
     __shared__ BuildLds s;
     __shared__ uint32_t block_count[4][16];            // symbols of each length in each block of 64 symbols
     const int sec = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
@@ -153,9 +157,10 @@ __global__ __launch_bounds__(256) void build_tables_kernel(CoderArgs a)
     a.ws.enc[256 * sec + tid] = (s.first[L] + rank) | ((uint32_t)L << 16);
 }
 
-// grid = 2 workgroups of kTableWaves waves: decode tables from the lengths stored in the payload
+// grid = one workgroup of kTableWaves waves per table slot: decode tables from the lengths stored in the payload
 __global__ __launch_bounds__(kTableWaves * 64) void decode_prepare_kernel(CoderArgs a)
 {
+    if (!((a.slot_mask >> blockIdx.x) & 1)) return;
     __shared__ BuildLds s;
     __shared__ uint32_t block_count[4][16];            // symbols of each length in each block of 64 symbols
     __shared__ int s_ok;
@@ -252,20 +257,20 @@ template <bool ISV> static int hist_b(int bits, int group, int dtype, const Code
     return KVC_ERR_UNSUPPORTED;
 }
 
-int launch_coder_tables(int bits_k, int bits_v, int group_k, int group_v, int dtype, const CoderArgs &k,
-                        const CoderArgs &v, hipStream_t s)
+int launch_table_sample(int bits, int group, int dtype, const CoderArgs &a, hipStream_t s)
 {
-    int rc = hist_b<false>(bits_k, group_k, dtype, k, s);
-    if (rc) return rc;
-    rc = hist_b<true>(bits_v, group_v, dtype, v, s);
-    if (rc) return rc;
-    hipLaunchKernelGGL(build_tables_kernel, dim3(2), dim3(256), 0, s, k);
+    return a.is_v ? hist_b<true>(bits, group, dtype, a, s) : hist_b<false>(bits, group, dtype, a, s);
+}
+
+int launch_build_tables(const CoderArgs &any, hipStream_t s)
+{
+    hipLaunchKernelGGL(build_tables_kernel, dim3(any.slots), dim3(256), 0, s, any);
     return launched();
 }
 
 int launch_decode_prepare(const CoderArgs &k, hipStream_t s)
 {
-    hipLaunchKernelGGL(decode_prepare_kernel, dim3(2), dim3(kTableWaves * 64), 0, s, k);
+    hipLaunchKernelGGL(decode_prepare_kernel, dim3(k.slots), dim3(kTableWaves * 64), 0, s, k);
     return launched();
 }
 

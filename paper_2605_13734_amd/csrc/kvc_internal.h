@@ -38,6 +38,9 @@ struct QuantArgs {
 struct Geometry {
     long long meta_k, meta_v, aux, codes_k, codes_v;
     long long aux_base;          // tables / directory part of the auxiliary section (before the anchors)
+    long long code_tables;       // bytes of the coder's tables at the start of the auxiliary section (0, 512 or 2048)
+    long long off_dir;           // the coder's directory
+    long long off_widths, widths;    // the per-head width tables
     long long anchors_k, anchors_v, off_anchors_k, off_anchors_v;
     long long off_meta_k, off_meta_v, off_aux, off_codes_k, off_codes_v, total;
     long long chunks_k, chunks_v;
@@ -95,12 +98,16 @@ int launch_fill_u32(uint32_t *dst, uint32_t value, long long n, hipStream_t s);
 
 // ---- lossless stage (codec 1) -----------------------------------------------------------
 
+// Code tables of a request: one per tensor, or with per-head widths one per tensor and width
+// (slot 4 * is_v + index of the width in 2, 3, 4, 8).
+constexpr int kTableSlots = 8;
+
 // Per-request scratch inside the caller's workspace (device memory).
 struct CoderScratch {
-    uint32_t *hist;             // [2][256] sample histograms (K, V)
-    uint32_t *enc;              // [2][256] code | length << 16
-    uint16_t *lut;              // [2][4096] decode table: symbol | length << 8
-    unsigned long long *state;  // scan state, one word per encode workgroup (K then V)
+    uint32_t *hist;             // [kTableSlots][256] sample histograms
+    uint32_t *enc;              // [kTableSlots][256] code | length << 16
+    uint16_t *lut;              // [kTableSlots][4096] decode table: symbol | length << 8
+    unsigned long long *state;  // scan state, one word per encode workgroup (in launch order)
     uint32_t *ticket;           // work-order counter
 };
 
@@ -112,24 +119,31 @@ constexpr int enc_waves(int bits, int group, int dtype, bool dense)
     return bits == 8 ? 2 : (group == 32 && dtype == DT_F16 && dense) ? 8 : 4;
 }
 
+// One launch of the coder: a tensor, or with per-head widths the heads of one width of a tensor
+// (q.head_list); the launches of a request follow each other in chunk order (K before V, widths
+// ascending) and share the ticket counter and the scan state.
 struct CoderArgs {
     QuantArgs q;                // tensor, meta, tokens, status ...
     uint8_t *payload;           // request payload base
-    long long off_aux;          // tables (2 x 256 length bytes) then directory
+    long long off_aux;          // the code tables (256 length bytes per slot)
+    long long off_dir;          // the directory
     long long off_bodies;       // first chunk body (= K codes offset)
     long long capacity;         // payload bytes available
-    long long chunks;           // chunks in this section
-    long long chunk_base;       // directory index of this section's first chunk
-    long long wg_base;          // scan-state index of this section's first workgroup
-    long long total_wgs;        // encode workgroups of K and V together
+    long long chunks;           // chunks of this launch
+    long long chunk_base;       // directory index of this launch's first chunk
+    long long wg_base;          // scan-state index of this launch's first workgroup
+    long long k_wgs;            // encode workgroups of all K launches
+    long long total_wgs;        // encode workgroups of all launches of the request
     long long total_chunks;     // K and V together
     int is_v;
+    int tab;                    // table slot of this launch
+    int slots, slot_mask;       // table slots of the request's format (2 or 8) and the ones in use
     CoderScratch ws;
     unsigned long long *out_bytes;   // device: true payload size (written by the last workgroup)
 };
 
-int launch_coder_tables(int bits_k, int bits_v, int group_k, int group_v, int dtype,
-                        const CoderArgs &k, const CoderArgs &v, hipStream_t s);
+int launch_table_sample(int bits, int group, int dtype, const CoderArgs &a, hipStream_t s);
+int launch_build_tables(const CoderArgs &any, hipStream_t s);
 int launch_encode_section(int bits, int group, int dtype, const CoderArgs &a, hipStream_t s);
 int launch_decode_prepare(const CoderArgs &k, hipStream_t s);
 int launch_decode_section(int bits, int group, int dtype, const CoderArgs &a, hipStream_t s);

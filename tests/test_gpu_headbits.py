@@ -16,19 +16,21 @@ def tables(seed, n):
     return rng.choice(WIDTHS, n).astype(np.uint8), rng.choice(WIDTHS, n).astype(np.uint8)
 
 
-def run(ref, x_cpu, tk, tv, gk, gv, transform=0, T=None, bits_k=4, bits_v=4):
+def run(ref, x_cpu, tk, tv, gk, gv, transform=0, T=None, bits_k=4, bits_v=4, codec=0, anchor_period=0):
     L, _, H, Tfull, D = x_cpu.shape
     T = Tfull if T is None else T
     dt = 1 if x_cpu.dtype == torch.float16 else 2
     xu = kvgen.as_u16(x_cpu)
     cfg = ref.config(dtype=dt, layers=L, heads=H, bits_k=bits_k, bits_v=bits_v, group_k=gk, group_v=gv,
-                     transform=transform, head_bits_k=tk, head_bits_v=tv)
+                     transform=transform, head_bits_k=tk, head_bits_v=tv, codec=codec, anchor_period=anchor_period)
     lay = ref.contiguous_layout(H, Tfull, D)
     want = ref.compress(cfg, xu[0, 0], xu[0, 1], lay, T)
     x = x_cpu.cuda()
-    plan = kvc.Plan(dt, L, H, D, bits_k, bits_v, gk, gv, 0, max_tokens=T, transform=transform,
-                    head_bits_k=tk, head_bits_v=tv)
-    assert plan.payload_size(T)[0] == want.size
+    plan = kvc.Plan(dt, L, H, D, bits_k, bits_v, gk, gv, codec, max_tokens=T, transform=transform,
+                    head_bits_k=tk, head_bits_v=tv, anchor_period=anchor_period)
+    assert plan.payload_size(T)[0] == ref.payload_size(cfg, T)[0]
+    if not codec:
+        assert plan.payload_size(T)[0] == want.size
     buf = kvc.Buffers(plan, [T])
     buf.payload.fill_(0xAB)
     st = torch.cuda.current_stream().cuda_stream
@@ -36,7 +38,7 @@ def run(ref, x_cpu, tk, tv, gk, gv, transform=0, T=None, bits_k=4, bits_v=4):
     torch.cuda.synchronize()
     assert int(buf.status[0]) == 0
     got = buf.payload_of(0)
-    assert got.size == want.size
+    assert got.size == want.size, (got.size, want.size)
     d = np.nonzero(got != want)[0]
     assert d.size == 0, "first differing byte %d of %d (%d differ)" % (d[0], want.size, d.size)
     y = torch.full_like(x, 7.0)
@@ -122,5 +124,35 @@ def test_payload_of_another_table_is_refused(ref):
 def test_plan_rejections():
     with pytest.raises(kvc.KvcError):
         kvc.Plan(1, 1, 4, 128, 4, 4, 32, 32, 0, max_tokens=64, head_bits_k=[2, 3, 5, 8])
-    with pytest.raises(kvc.KvcError):
-        kvc.Plan(1, 1, 4, 128, 4, 4, 32, 32, 1, max_tokens=64, head_bits_k=[2, 3, 4, 8])
+
+
+# ---- width tables together with the lossless stage: chunks by width, one code table per width ------------
+
+@pytest.mark.parametrize("dtype,group", [(torch.float16, 32), (torch.bfloat16, 64), (torch.float16, 128)])
+def test_both_tables_with_the_lossless_stage(ref, dtype, group):
+    L, H, T = 3, 4, 128 * 4 + 37
+    tk, tv = tables(11, L * H)
+    x = kvgen.make_kv(31, L, H, 128, T, dtype)
+    run(ref, x, tk, tv, group, group, codec=1)
+
+
+def test_one_table_with_the_lossless_stage_transforms_and_short_requests(ref):
+    L, H, T = 2, 4, 128 * 2 + 5
+    tk, tv = tables(12, L * H)
+    x = kvgen.make_kv(32, L, H, 128, T, torch.float16)
+    run(ref, x, tk, None, 32, 64, bits_v=4, codec=1)
+    run(ref, x, None, tv, 64, 32, bits_k=3, codec=1)
+    run(ref, x, tk, tv, 32, 32, codec=1, transform=1)
+    run(ref, x, tk, tv, 32, 32, codec=1, transform=2, anchor_period=32)
+    run(ref, x, tk, tv, 32, 32, codec=1, T=1)
+    only8 = np.full(L * H, 8, np.uint8)                       # one width only: seven empty table slots
+    run(ref, x, only8, only8, 32, 32, codec=1)
+
+
+def test_tables_with_the_lossless_stage_many_workgroups(ref):
+    """Enough chunks per width that every width's launch spans many workgroups and look-back windows,
+    in the dense fp16 layout that takes eight chunks per workgroup."""
+    L, H, T = 8, 8, 128 * 24 + 3
+    tk, tv = tables(13, L * H)
+    x = kvgen.make_kv(33, L, H, 128, T, torch.float16)
+    run(ref, x, tk, tv, 32, 32, codec=1)

@@ -114,8 +114,6 @@ def test_rejections(ref, data):
     bad[5] = 5
     with pytest.raises(ValueError):
         ref.compress(ref.config(layers=L, heads=H, head_bits_k=bad), data[0, 0], data[0, 1], lay, T)
-    with pytest.raises(ValueError):
-        ref.compress(ref.config(layers=L, heads=H, head_bits_k=tk, codec=1), data[0, 0], data[0, 1], lay, T)
     cfg = ref.config(layers=L, heads=H, head_bits_k=tk, head_bits_v=tv)
     p = ref.compress(cfg, data[0, 0], data[0, 1], lay, T)
     out = np.zeros_like(data)
@@ -126,3 +124,103 @@ def test_rejections(ref, data):
     q = p.copy()
     q[ref.inspect(p)[4][4] + 3] = 7                      # a width that does not exist
     assert ref.decompress(q, out[0, 0], out[0, 1], lay, None) == -4
+
+
+# ---- width tables together with the lossless stage ---------------------------------------------------
+# Reading: chunks ordered by width (2, 3, 4, 8), then (layer, head, chunk); one code table per tensor
+# and width, from a sample of that width's chunks; eight table slots, then the directory, then the
+# width tables.  Pinned against uniform payloads of sub-tensors that hold one width's heads only.
+
+TC = 128 * 3 + 41                    # several chunks per head and a ragged last one
+
+
+@pytest.fixture(scope="module")
+def long_data():
+    return kvgen.as_u16(kvgen.make_kv(22, L, H, D, TC, torch.float16))
+
+
+def heads_of(tab, b):
+    return [lh for lh in range(L * H) if tab[lh] == b]
+
+
+def test_lossless_stage_with_width_tables_round_trip_and_sizes(ref, long_data):
+    tk, tv = tables(5)
+    lay = ref.contiguous_layout(H, TC, D)
+    plain = ref.config(layers=L, heads=H, head_bits_k=tk, head_bits_v=tv)
+    coded = ref.config(layers=L, heads=H, head_bits_k=tk, head_bits_v=tv, codec=1)
+    p0 = ref.compress(plain, long_data[0, 0], long_data[0, 1], lay, TC)
+    p1 = ref.compress(coded, long_data[0, 0], long_data[0, 1], lay, TC)
+    a, b = np.zeros_like(long_data), np.zeros_like(long_data)
+    assert ref.decompress(p0, a[0, 0], a[0, 1], lay, plain) == 0
+    assert ref.decompress(p1, b[0, 0], b[0, 1], lay, coded) == 0
+    assert np.array_equal(a, b)                                   # the stage is lossless
+    rc, _, tokens, total, sec = ref.inspect(p1)
+    assert rc == 0 and tokens == TC and total == p1.size
+    cph = -(-TC // 128)
+    n = L * H * cph
+    assert sec[5] == 8 * 256 + 4 * (2 * n + 1) + 2 * L * H         # eight tables, directory, two width tables
+    d = p1[sec[4] + 2048: sec[4] + 2048 + 4 * (2 * n + 1)].view("<u4").astype(np.int64) * 16
+    assert d[0] == 0 and np.all(np.diff(d) > 0)
+    assert d[n] == sec[7] and d[2 * n] - d[n] == sec[9] and sec[8] == sec[6] + sec[7] and sec[6] + d[2 * n] == total
+    assert np.array_equal(p1[sec[4] + 2048 + 4 * (2 * n + 1): sec[4] + 2048 + 4 * (2 * n + 1) + L * H], tk)
+    assert np.array_equal(p1[sec[4] + 2048 + 4 * (2 * n + 1) + L * H: sec[4] + 2048 + 4 * (2 * n + 1) + 2 * L * H], tv)
+    # metadata is that of the codec-free payload; the bound of kvc_payload_size holds
+    assert np.array_equal(p1[sec[0]: sec[0] + sec[1]], p0[ref.inspect(p0)[4][0]: ref.inspect(p0)[4][0] + sec[1]])
+    assert total <= ref.payload_size(coded, TC)[0]
+    # every table slot is a complete prefix code or empty
+    for is_v, tab in ((0, tk), (1, tv)):
+        for wi, w in enumerate(WIDTHS):
+            lens = p1[sec[4] + 256 * (4 * is_v + wi): sec[4] + 256 * (4 * is_v + wi + 1)].astype(np.int64)
+            if heads_of(tab, w):
+                assert lens.min() >= 1 and lens.max() <= 12 and (2 ** (12 - lens)).sum() == 2 ** 12
+            else:
+                assert not lens.any()
+
+
+def test_every_width_is_coded_like_a_uniform_tensor_of_its_heads(ref, long_data):
+    """The heads of one width, taken out into a tensor of their own (one layer, as many heads) and
+    compressed with that uniform width and the lossless stage, give the table slot and, chunk after
+    chunk, the bodies that the mixed payload holds for this width."""
+    tk, tv = tables(6)
+    lay = ref.contiguous_layout(H, TC, D)
+    coded = ref.config(layers=L, heads=H, head_bits_k=tk, head_bits_v=tv, codec=1)
+    p1 = ref.compress(coded, long_data[0, 0], long_data[0, 1], lay, TC)
+    _, _, _, _, sec = ref.inspect(p1)
+    cph = -(-TC // 128)
+    n = L * H * cph
+    d = p1[sec[4] + 2048: sec[4] + 2048 + 4 * (2 * n + 1)].view("<u4").astype(np.int64) * 16
+    for is_v, tab in ((0, tk), (1, tv)):
+        at = is_v * n                                             # directory index of the width's first chunk
+        for wi, w in enumerate(WIDTHS):
+            hs = heads_of(tab, w)
+            if not hs:
+                continue
+            sub = np.zeros((1, 2, len(hs), TC, D), dtype=np.uint16)
+            for i, lh in enumerate(hs):
+                sub[0, :, i] = long_data[lh // H, :, lh % H]
+            c = ref.config(layers=1, heads=len(hs), bits_k=w, bits_v=w, codec=1)
+            q = ref.compress(c, sub[0, 0], sub[0, 1], ref.contiguous_layout(len(hs), TC, D), TC)
+            _, _, _, _, s = ref.inspect(q)
+            m = len(hs) * cph
+            dq = q[s[4] + 512: s[4] + 512 + 4 * (2 * m + 1)].view("<u4").astype(np.int64) * 16
+            assert np.array_equal(p1[sec[4] + 256 * (4 * is_v + wi): sec[4] + 256 * (4 * is_v + wi + 1)],
+                                  q[s[4] + 256 * is_v: s[4] + 256 * (is_v + 1)]), ("table", is_v, w)
+            sizes_mixed = np.diff(d[at: at + m + 1])
+            sizes_sub = np.diff(dq[is_v * m: is_v * m + m + 1])
+            assert np.array_equal(sizes_mixed, sizes_sub), ("sizes", is_v, w)
+            got = p1[sec[6] + d[at]: sec[6] + d[at + m]]
+            want = q[s[6] + dq[is_v * m]: s[6] + dq[is_v * m + m]]
+            assert np.array_equal(got, want), ("bodies", is_v, w)
+            at += m
+
+
+def test_one_table_and_one_uniform_tensor_with_the_lossless_stage(ref, long_data):
+    tk, _ = tables(7)
+    lay = ref.contiguous_layout(H, TC, D)
+    for kw in (dict(head_bits_k=tk, bits_v=4), dict(bits_k=3, head_bits_v=tk)):
+        plain = ref.config(layers=L, heads=H, **kw)
+        coded = ref.config(layers=L, heads=H, codec=1, **kw)
+        a, b = np.zeros_like(long_data), np.zeros_like(long_data)
+        assert ref.decompress(ref.compress(plain, long_data[0, 0], long_data[0, 1], lay, TC), a[0, 0], a[0, 1], lay, plain) == 0
+        assert ref.decompress(ref.compress(coded, long_data[0, 0], long_data[0, 1], lay, TC), b[0, 0], b[0, 1], lay, coded) == 0
+        assert np.array_equal(a, b)
