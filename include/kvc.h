@@ -76,8 +76,7 @@ enum { KVC_CODEC_NONE = 0, KVC_CODEC_HUFF8 = 1 };
  *                     its stored copy); a difference or sum is the exact value rounded once to
  *                     the tensor type and limited to its finite range.  A tensor stored unchanged
  *                     (16 bits) is not transformed by either
- *   anchor_period   : KVC_T_DELTA only: 32, 64 or 128 tokens (the format also allows 8 and 16, which
- *                     this build does not run: KVC_ERR_UNSUPPORTED); 0 otherwise
+ *   anchor_period   : KVC_T_DELTA only: 8, 16, 32, 64 or 128 tokens; 0 otherwise
  *   head_bits_k/v   : optional per-head bit widths (section 5.1: mixed precision at head
  *                     granularity; the mechanism behind MixHQ, which keeps the heads that matter
  *                     at a high precision and gives the others very few bits).  HOST arrays of

@@ -220,7 +220,6 @@ static int check_pair(const kvc_model *m, const kvc_strategy *s)
         const int a = s->anchor_period;
         if (a < 8 || a > 128 || (a & (a - 1))) return KVC_ERR_ARG;
     } else if (s->anchor_period != 0) return KVC_ERR_ARG;
-    if (s->transform == KVC_T_DELTA && s->anchor_period < kPassRows) return KVC_ERR_UNSUPPORTED;   // the kernels take one anchor per pass
     if (s->codec && (s->bits_k == 16 || s->bits_v == 16)) return KVC_ERR_UNSUPPORTED;
     return KVC_OK;
 }

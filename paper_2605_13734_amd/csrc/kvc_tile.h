@@ -488,29 +488,43 @@ template <int DT, bool ADD> __device__ __forceinline__ u32x4 delta_row(const u32
     return out;
 }
 
-// The rows of N/8 passes just loaded (see load_pass: rows past the end repeat the last row)
-// become differences from their anchors, which are read from the tensor again (they were
-// loaded moments ago by this or a neighbouring wave).  With `keep`, the lanes that hold an
-// anchor row also store it to `anchors`, the head's anchor rows in the payload.  Runs are 32
-// tokens or longer (shift >= 5).
-template <int DT, bool DENSE, int N>
-__device__ __forceinline__ void delta_rows(const TensorView &v, long long head_off, long long row0, long long tokens,
+// One pass of rows just loaded (see load_pass: rows past the end repeat the last row) becomes
+// differences from their anchors, which are read from the tensor again (they were loaded moments ago
+// by this or a neighbouring wave).  NA anchors per pass: 1 for runs of 32 tokens or more, 2 for runs
+// of 16, 4 for runs of 8 (the rows 4*i .. 4*i+3 that one load covers share a run).  A group of rows
+// past the end takes the anchor of the last row, whose copies they are.  With `keep`, the lanes that
+// hold an anchor row also store it to `anchors`, the head's anchor rows in the payload.
+template <int DT, bool DENSE, int NA>
+__device__ __forceinline__ void delta_pass(const TensorView &v, long long head_off, long long first, long long tokens,
                                            int shift, uint16_t *anchors, bool keep, u32x4 *raw, bool &bad)
 {
     const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
     const long long mask = (1ll << shift) - 1;
-    // a run (32 tokens or more) covers whole passes, whose first rows are multiples of 32: one anchor per pass
+    u32x4 anchor[NA];
+#pragma unroll
+    for (int k = 0; k < NA; ++k) {
+        const long long r = first + k * (kPassRows / NA);
+        const bool exists = r < tokens;
+        const long long arow = (exists ? r : tokens - 1) & ~mask;
+        const long long off = DENSE ? head_off + arow * kDim : row_offset(v, head_off, arow, bad);
+        anchor[k] = *(const u32x4 *)(v.base + off + col * 8);
+        if (keep && exists && r == arow && rsub == 0) *(u32x4 *)(anchors + (arow >> shift) * kDim + col * 8) = anchor[k];
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) raw[i] = delta_row<DT, false>(raw[i], anchor[(4 * i) / (kPassRows / NA)]);
+}
+
+// N/8 passes, runs of 2^shift tokens (8 or more)
+template <int DT, bool DENSE, int N>
+__device__ __forceinline__ void delta_rows(const TensorView &v, long long head_off, long long row0, long long tokens,
+                                           int shift, uint16_t *anchors, bool keep, u32x4 *raw, bool &bad)
+{
 #pragma unroll
     for (int p = 0; p < N / 8; ++p) {
-        long long first = row0 + p * kPassRows;
-        const bool exists = first < tokens;
-        first = exists ? first : tokens - 1;
-        const long long arow = first & ~mask;
-        const long long off = DENSE ? head_off + arow * kDim : row_offset(v, head_off, arow, bad);
-        const u32x4 anchor = *(const u32x4 *)(v.base + off + col * 8);
-        if (keep && exists && first == arow && rsub == 0) *(u32x4 *)(anchors + (arow >> shift) * kDim + col * 8) = anchor;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) raw[p * 8 + i] = delta_row<DT, false>(raw[p * 8 + i], anchor);
+        const long long first = row0 + p * kPassRows;
+        if (shift >= 5) delta_pass<DT, DENSE, 1>(v, head_off, first, tokens, shift, anchors, keep, raw + p * 8, bad);
+        else if (shift == 4) delta_pass<DT, DENSE, 2>(v, head_off, first, tokens, shift, anchors, keep, raw + p * 8, bad);
+        else delta_pass<DT, DENSE, 4>(v, head_off, first, tokens, shift, anchors, keep, raw + p * 8, bad);
     }
 }
 
@@ -541,10 +555,27 @@ __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float sc
                                                   const u32x4 *loaded_anchor)
 {
     const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
-    // delta transform: a run (32 tokens or more) covers the whole pass (row0 is a multiple of 32);
+    // delta transform: a run of 32 tokens or more covers the whole pass (row0 is a multiple of 32), and
     // the caller may have that one anchor in flight already
-    u32x4 pass_anchor = {0, 0, 0, 0};
-    if (TR == 2) pass_anchor = loaded_anchor ? *loaded_anchor : load_anchor(anchors, anchor_shift, row0);
+    // (runs of 16 or 8 tokens: two or four anchors per pass, one per 16 or 8 rows; an anchor past
+    // the end of the sequence is replaced by the last one, and no row uses it)
+    u32x4 pass_anchor[4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
+    if (TR == 2) {
+        if (anchor_shift >= 5) {
+            pass_anchor[0] = loaded_anchor ? *loaded_anchor : load_anchor(anchors, anchor_shift, row0);
+        } else {
+            const long long last = row0 + (rows < kPassRows ? rows : kPassRows) - 1;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const long long r = row0 + ((long long)k << anchor_shift);
+                if ((k << anchor_shift) < kPassRows) pass_anchor[k] = load_anchor(anchors, anchor_shift, r < last ? r : last);
+            }
+        }
+    }
+    // the anchor of the rows 4*i .. 4*i+3
+    auto anchor_of = [&](int i) -> const u32x4 & {
+        return anchor_shift >= 5 ? pass_anchor[0] : anchor_shift == 4 ? pass_anchor[i >> 2] : pass_anchor[i >> 1];
+    };
     // every load of the pass (packed codes, block-table entries) is issued before the first store: the
     // compiler cannot move a load across a store it cannot tell apart from it, and a pass that alternates
     // them pays one memory round trip per row
@@ -558,7 +589,7 @@ __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float sc
             u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w[i], scale[i], zero[i])
                              : dequant_row<BITS, DT, CLAMP>(w[i], scale, zero);
             if (TR == 1) out = hadamard_row<DT>(out, true);
-            if (TR == 2) out = add_anchor<DT>(out, pass_anchor, anchor_shift, row0 + 4 * i + rsub);
+            if (TR == 2) out = add_anchor<DT>(out, anchor_of(i), anchor_shift, row0 + 4 * i + rsub);
             __builtin_nontemporal_store(out, dst + i * 64);
         }
         return;
@@ -580,7 +611,7 @@ __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float sc
         u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w[i], scale[i], zero[i])
                          : dequant_row<BITS, DT, CLAMP>(w[i], scale, zero);
         if (TR == 1) out = hadamard_row<DT>(out, true);     // (all 16 lanes of a row take part)
-        if (TR == 2) out = add_anchor<DT>(out, pass_anchor, anchor_shift, row0 + (r < rows ? r : 0));
+        if (TR == 2) out = add_anchor<DT>(out, anchor_of(i), anchor_shift, row0 + (r < rows ? r : 0));
         if (r < rows && !b) __builtin_nontemporal_store(out, (u32x4 *)(x.base + off[i] + col * 8));
     }
 }

@@ -11,7 +11,8 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
-@pytest.mark.parametrize("bits,group,period", [(4, 32, 32), (2, 64, 64), (3, 128, 32), (8, 32, 128), (4, 128, 64)])
+@pytest.mark.parametrize("bits,group,period", [(4, 32, 32), (2, 64, 64), (3, 128, 32), (8, 32, 128), (4, 128, 64),
+                                               (4, 32, 8), (3, 64, 16), (2, 128, 8), (8, 32, 16)])
 def test_delta_contiguous(ref, dtype, bits, group, period):
     x = kvgen.make_kv(80 + bits, 2, 2, 128, 32 * 9 + 5, dtype)
     check_contiguous(ref, x, bits, bits, group, group, transform=2, anchor_period=period)
@@ -24,7 +25,7 @@ def test_delta_short_sequences(ref, T):
     check_contiguous(ref, x, 4, 4, 32, 32, transform=2, anchor_period=32)
 
 
-@pytest.mark.parametrize("period", [32, 64, 128])
+@pytest.mark.parametrize("period", [8, 16, 32, 64, 128])
 def test_delta_with_codec_and_ragged_tail(ref, period):
     x = kvgen.make_kv(82, 2, 4, 128, 128 * 5 + 37, torch.float16)
     check_contiguous(ref, x, 4, 4, 32, 32, codec=1, transform=2, anchor_period=period)
@@ -131,12 +132,16 @@ def test_delta_period_mismatch_is_reported(ref):
     assert not y.any()                                  # nothing was written
 
 
-def test_delta_short_runs_are_not_built():
-    """The format allows runs of 8 and 16 tokens; the kernels take one anchor per pass of 32 rows."""
-    for period in (8, 16):
-        with pytest.raises(kvc.KvcError) as e:
-            kvc.Plan(1, 1, 2, 128, 4, 4, 32, 32, 0, max_tokens=64, transform=2, anchor_period=period)
-        assert e.value.status == -2
+@pytest.mark.parametrize("period", [8, 16])
+def test_delta_short_runs(ref, period):
+    """Runs of 8 and 16 tokens (several anchors per pass of 32 rows): ragged ends inside and between
+    runs, paged pools, the lossless stage, and both types."""
+    for T in (1, 7, 8, 9, 15, 16, 17, 24, 25, 33, 40, 129):
+        x = kvgen.make_kv(84, 1, 2, 128, T, torch.float16)
+        check_contiguous(ref, x, 4, 4, 32, 32, transform=2, anchor_period=period)
+    x = kvgen.make_kv(85, 2, 2, 128, 128 * 2 + 21, torch.bfloat16)
+    check_contiguous(ref, x, 4, 2, 64, 64, codec=1, transform=2, anchor_period=period)
+    check_contiguous(ref, x, 8, 3, 128, 32, transform=2, anchor_period=period, T=100)
 
 
 @pytest.mark.parametrize("codec", [0, 1])

@@ -40,7 +40,7 @@ def test_plan_validation(lib):
         with pytest.raises(kvc.KvcError) as e:
             kvc.Plan(**{**ok, **kw})
         assert e.value.status == -1, kw
-    unsupported = [dict(head_dim=64), dict(transform=3), dict(transform=2, anchor_period=8), dict(transform=2, anchor_period=16), dict(bits_k=16, codec=1)]
+    unsupported = [dict(head_dim=64), dict(transform=3), dict(bits_k=16, codec=1)]
     for kw in unsupported:
         with pytest.raises(kvc.KvcError) as e:
             kvc.Plan(**{**ok, **kw})
