@@ -47,6 +47,10 @@ WORKLOADS = {
     "llama8b_8k_bf16_int4g32": (32, 8, 8192, "bf16", 4, 4, 32, 32, 0),
     "llama8b_8k_bf16_int2g64": (32, 8, 8192, "bf16", 2, 2, 64, 64, 0),
     "tiny_fp16_int4g32": (1, 8, 1024, "f16", 4, 4, 32, 32, 0),
+    # a twelfth field "paged": the KV lives in pages of 16 tokens behind a seeded random block table
+    "paged128k_fp16_int4g32": (32, 8, 131072, "f16", 4, 4, 32, 32, 0, 0, None, "paged"),
+    "paged128k_fp16_int4g32_huff8": (32, 8, 131072, "f16", 4, 4, 32, 32, 1, 0, None, "paged"),
+    "qwen3_32k_bf16_k4v2g64": (94, 4, 32768, "bf16", 4, 2, 64, 64, 0),
 }
 
 
@@ -325,12 +329,22 @@ def main():
         head_bits = [np.where(rng.permutation(L * H) < L * H // 2, mix[0], mix[1]).astype(np.uint8) for _ in range(2)]
     dtype, dt = (torch.float16, kvc.F16) if dtn == "f16" else (torch.bfloat16, kvc.BF16)
     dev = "cuda:0"
-    x = kvgen.make_kv(0, L, H, 128, T, dtype, dev)
-    y = torch.empty_like(x)
+    paged = len(WORKLOADS[args.workload]) > 11 and WORKLOADS[args.workload][11] == "paged"
     plan = kvc.Plan(dt, L, H, 128, bk, bv, gk, gv, codec, max_tokens=T, transform=transform, anchor_period=anchor_period,
                     head_bits_k=head_bits[0] if mix else None, head_bits_v=head_bits[1] if mix else None)
     buf = kvc.Buffers(plan, [T], dev)
-    src, dst = [kvc.contiguous_request(x)], [kvc.contiguous_request(y)]
+    if paged:
+        # x, y are pools [layer][kv][block][16][head][dim]; compression reads through one block table,
+        # decompression writes through another
+        x, table = kvgen.make_paged(0, L, H, 128, T, dtype, dev, 16)
+        table2 = kvgen.block_table(7, T // 16, T // 16, dev)
+        y = torch.empty_like(x)
+        src, dst = [kvc.paged_request(x, table, T)], [kvc.paged_request(y, table2, T)]
+        args.no_cpu_baseline = args.headline_only = True
+    else:
+        x = kvgen.make_kv(0, L, H, 128, T, dtype, dev)
+        y = torch.empty_like(x)
+        src, dst = [kvc.contiguous_request(x)], [kvc.contiguous_request(y)]
     stream = torch.cuda.current_stream().cuda_stream
     V = x.numel() * 2
 
@@ -340,7 +354,7 @@ def main():
     ref_layers = min(8, L)
     ref_plan = kvc.Plan(dt, ref_layers, H, 128, 16, 16, 32, 32, 0, max_tokens=T)
     ref_buf = kvc.Buffers(ref_plan, [T], dev)
-    ref_buf.compress([kvc.contiguous_request(x[:ref_layers])], stream)
+    ref_buf.compress([kvc.contiguous_request(x[:ref_layers].reshape(ref_layers, 2, H, T, 128))], stream)
     torch.cuda.synchronize()
     ref_bytes = ref_layers * H * T * 128 * 2
     del ref_buf
@@ -459,6 +473,7 @@ def main():
         "config": {"workload": args.workload, "layers": L, "kv_heads": H, "head_dim": 128, "tokens": T,
                    "kv_dtype": dtn, "bits_k": bk, "bits_v": bv, "group_k": gk, "group_v": gv,
                    "codec": "huff8" if codec else "none", "transform": ("none", "hadamard", "delta%d" % anchor_period)[transform],
+                   "layout": "paged, 16 tokens per block" if paged else "contiguous",
                    "kv_bytes": V, "payload_bytes": payload_bytes},
         "s_enc_GBps": round(s_enc, 1), "s_dec_GBps": round(s_dec, 1), "cr": round(cr, 4),
         "break_even_bandwidth_GBps": round((1 - 1 / cr) * s_p, 1),

@@ -77,11 +77,20 @@ __device__ __forceinline__ void pass_offsets(const TensorView &v, long long head
         return;
     }
     const int mask = (1 << v.bt_shift) - 1;
+    // all eight entries are requested before the first one is used: the empty statement below needs
+    // them all in registers, so the compiler cannot wait for them one by one (it does, when it
+    // sees eight loads that each feed one scalar)
+    int entry[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         long long first = row0 + 4 * i;
         first = first < tokens ? first : tokens - 1;
-        int blk = __builtin_amdgcn_readfirstlane(v.block_table[first >> v.bt_shift]);
+        entry[i] = v.block_table[first >> v.bt_shift];
+    }
+    __builtin_amdgcn_sched_group_barrier(0x020, 8, 0);     // (eight memory reads, then whatever follows)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        int blk = __builtin_amdgcn_readfirstlane(entry[i]);
         if ((unsigned)blk >= (unsigned)v.num_phys_blocks) { bad = true; blk = 0; }
         const long long base = head_off + (long long)blk * v.stride_block;
         long long row = row0 + 4 * i + rsub;

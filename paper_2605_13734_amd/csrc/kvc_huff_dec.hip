@@ -94,14 +94,19 @@ __device__ __forceinline__ void dequant_chunk(const CoderArgs &a, const ChunkPos
             else load_meta_v(a.q, c, (p + 1) * kPassRows, mv);
             if (one_anchor) anchor_next = load_anchor(anchors, a.q.anchor_shift, c.row0 + (p + 1) * kPassRows);
         }
-        dequant_pass<BITS, DT, IS_V, DENSE, Dec::kLayout, TR>(lds, scale, zero, clamp, a.q.x, c.head_off, c.row0 + p * kPassRows,
-                                                              c.rows - p * kPassRows, bad, p * kPassRows, anchors, a.q.anchor_shift,
-                                                              one_anchor ? &anchor : nullptr);
+        PassFetch f;
+        pass_fetch<BITS, DENSE, Dec::kLayout>(f, lds, a.q.x, c.head_off, c.row0 + p * kPassRows, c.rows - p * kPassRows, p * kPassRows);
+        dequant_pass<BITS, DT, IS_V, DENSE, TR>(f, scale, zero, clamp, a.q.x, c.head_off, c.row0 + p * kPassRows,
+                                                c.rows - p * kPassRows, bad, anchors, a.q.anchor_shift,
+                                                one_anchor ? &anchor : nullptr);
         anchor = anchor_next;
     }
 }
 
-template <int BITS, int DT, bool IS_V, bool DENSE>
+// XF = false leaves the inverses of stage T out (for launches without a transform): in one kernel
+// with them the plain path pays for their registers (the anchors of short runs, most of all) with
+// its fourth wave per SIMD.
+template <int BITS, int DT, bool IS_V, bool DENSE, bool XF>
 __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel(CoderArgs a)
 {
     using Geo = ChunkGeom<BITS>;
@@ -173,7 +178,7 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
         }
         if (!IS_V) load_meta_k(a.q, c, 0, meta0, meta1);
         else load_meta_v(a.q, c, 0, metav);
-        if (a.q.anchors)
+        if (XF && a.q.anchors)
             anchor0 = load_anchor(head_anchors(a.q.anchors, c.lh, a.q.tokens, a.q.anchor_shift), a.q.anchor_shift, c.row0);
     }
 #pragma unroll
@@ -239,8 +244,8 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
 
     // dequantize the rows from LDS (one copy of the loop per transform; a launch runs one of them)
     bool bad = false;
-    if (a.q.rotate) dequant_chunk<BITS, DT, IS_V, DENSE, 1>(a, c, lds, meta0, meta1, metav, anchor0, bad);
-    else if (a.q.anchors) dequant_chunk<BITS, DT, IS_V, DENSE, 2>(a, c, lds, meta0, meta1, metav, anchor0, bad);
+    if (XF && a.q.rotate) dequant_chunk<BITS, DT, IS_V, DENSE, 1>(a, c, lds, meta0, meta1, metav, anchor0, bad);
+    else if (XF && a.q.anchors) dequant_chunk<BITS, DT, IS_V, DENSE, 2>(a, c, lds, meta0, meta1, metav, anchor0, bad);
     else dequant_chunk<BITS, DT, IS_V, DENSE, 0>(a, c, lds, meta0, meta1, metav, anchor0, bad);
     if (bad) atomicOr(a.q.status, KVC_DEV_BAD_BLOCK);
 }
@@ -252,8 +257,15 @@ template <int BITS, int DT, bool IS_V> static int decode_launch(const CoderArgs 
     constexpr int NW = ChunkGeom<BITS>::kDecWaves;
     const long long need = (a.chunks + NW - 1) / NW;
     if (need <= 0) return KVC_OK;
-    if (a.q.dense) hipLaunchKernelGGL((decode_kernel<BITS, DT, IS_V, true>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
-    else hipLaunchKernelGGL((decode_kernel<BITS, DT, IS_V, false>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
+    const dim3 grid((unsigned)need), block(NW * 64);
+    const bool xf = a.q.rotate || a.q.anchors;
+    if (a.q.dense) {
+        if (xf) hipLaunchKernelGGL((decode_kernel<BITS, DT, IS_V, true, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((decode_kernel<BITS, DT, IS_V, true, false>), grid, block, 0, s, a);
+    } else {
+        if (xf) hipLaunchKernelGGL((decode_kernel<BITS, DT, IS_V, false, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((decode_kernel<BITS, DT, IS_V, false, false>), grid, block, 0, s, a);
+    }
     return launched();
 }
 

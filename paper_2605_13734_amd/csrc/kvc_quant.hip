@@ -54,15 +54,17 @@ __global__ __launch_bounds__(256) void decompress_k_kernel(QuantArgs a)
     const long long tb = row0 / a.group, nb = (a.tokens + a.group - 1) / a.group;
     const u32x4 *m = (const u32x4 *)(a.meta + ((u.lh * nb + tb) * kDim + col * 8) * 4);
     const u32x4 m0 = m[0], m1 = m[1];
-    float scale[8], zero[8];
-    const bool clamp = k_meta_floats<BITS, DT>(m0, m1, scale, zero);
     uint8_t *codes = head_codes<BITS>(a, u.lh) + row0 * (16 * BITS);
     const long long left = a.tokens - row0;
+    const int rows = left < kPassRows ? (int)left : kPassRows;
+    PassFetch f;
+    pass_fetch<BITS, DENSE, 0>(f, codes, a.x, u.head_off, row0, rows);
+    float scale[8], zero[8];
+    const bool clamp = k_meta_floats<BITS, DT>(m0, m1, scale, zero);
     bool bad = false;
-    dequant_pass_any<BITS, DT, false, DENSE, 0>(codes, scale, zero, clamp, a.x, u.head_off, row0,
-                                                left < kPassRows ? (int)left : kPassRows, bad, a.rotate != 0,
-                                                a.anchors ? head_anchors(a.anchors, u.lh, a.tokens, a.anchor_shift) : nullptr,
-                                                a.anchor_shift);
+    dequant_pass_any<BITS, DT, false, DENSE>(f, scale, zero, clamp, a.x, u.head_off, row0, rows, bad, a.rotate != 0,
+                                             a.anchors ? head_anchors(a.anchors, u.lh, a.tokens, a.anchor_shift) : nullptr,
+                                             a.anchor_shift);
     report(a.status, bad);
 }
 
@@ -106,13 +108,15 @@ __global__ __launch_bounds__(256) void decompress_v_kernel(QuantArgs a)
     uint32_t mw[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) mw[i] = meta[(4 * i + rsub < rows ? 4 * i + rsub : 0) * ng];
+    uint8_t *codes = head_codes<BITS>(a, u.lh) + row0 * (16 * BITS);
+    PassFetch f;
+    pass_fetch<BITS, DENSE, 0>(f, codes, a.x, u.head_off, row0, rows);
     float scale[8], zero[8];
     const bool clamp = v_meta_floats<BITS, DT>(mw, scale, zero);
-    uint8_t *codes = head_codes<BITS>(a, u.lh) + row0 * (16 * BITS);
     bool bad = false;
-    dequant_pass_any<BITS, DT, true, DENSE, 0>(codes, scale, zero, clamp, a.x, u.head_off, row0, rows, bad, a.rotate != 0,
-                                               a.anchors ? head_anchors(a.anchors, u.lh, a.tokens, a.anchor_shift) : nullptr,
-                                               a.anchor_shift);
+    dequant_pass_any<BITS, DT, true, DENSE>(f, scale, zero, clamp, a.x, u.head_off, row0, rows, bad, a.rotate != 0,
+                                            a.anchors ? head_anchors(a.anchors, u.lh, a.tokens, a.anchor_shift) : nullptr,
+                                            a.anchor_shift);
     report(a.status, bad);
 }
 

@@ -547,12 +547,42 @@ __device__ __forceinline__ u32x4 load_anchor(const uint16_t *anchors, int shift,
     return *(const u32x4 *)(anchors + (row >> shift) * kDim + (lane_id() & 15) * 8);
 }
 
+// What a pass reads before it can store: the packed codes of the lane's 8 rows and, unless the rows
+// are whole and dense, where each row goes.  Fetched ahead of everything that has to wait for the
+// group parameters (the choice of the clamping variant does), so that codes, block-table entries and
+// parameters travel together instead of one round trip after the other.
+struct PassFetch {
+    u32x2 w[8];
+    long long off[8];
+    bool bad;           // a block-table entry out of range: nothing of the pass is stored
+};
+
+template <int BITS, bool DENSE, int LAYOUT>
+__device__ __forceinline__ void pass_fetch(PassFetch &f, uint8_t *codes, const TensorView &x, long long head_off,
+                                           long long row0, int rows, int row_base = 0)
+{
+    const int rsub = lane_id() >> 4;
+    f.bad = false;
+    if (DENSE && rows >= kPassRows) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f.w[i] = fetch_codes<BITS, LAYOUT>(codes, row_base + 4 * i + rsub);
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = 4 * i + rsub;
+        const bool ok = r < rows;                       // uniform over each quad of lanes
+        f.w[i] = fetch_codes<BITS, LAYOUT>(codes, row_base + (ok ? r : 0));
+        if (DENSE) f.off[i] = head_off + (row0 + (ok ? r : 0)) * kDim;
+    }
+    if (!DENSE) pass_offsets(x, head_off, row0, row0 + rows, f.off, f.bad);
+}
+
 // TR: the inverse of stage T applied to every row (0 none, 1 Hadamard, 2 plus the anchor of the row's run)
-template <int BITS, int DT, bool IS_V, bool DENSE, int LAYOUT, bool CLAMP, int TR>
-__device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float scale[8], const float zero[8],
+template <int BITS, int DT, bool IS_V, bool DENSE, bool CLAMP, int TR>
+__device__ __forceinline__ void dequant_pass_rows(const PassFetch &f, const float scale[8], const float zero[8],
                                                   const TensorView &x, long long head_off, long long row0, int rows,
-                                                  bool &bad, int row_base, const uint16_t *anchors, int anchor_shift,
-                                                  const u32x4 *loaded_anchor)
+                                                  const uint16_t *anchors, int anchor_shift, const u32x4 *loaded_anchor)
 {
     const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
     // delta transform: a run of 32 tokens or more covers the whole pass (row0 is a multiple of 32), and
@@ -576,70 +606,56 @@ __device__ __forceinline__ void dequant_pass_rows(uint8_t *codes, const float sc
     auto anchor_of = [&](int i) -> const u32x4 & {
         return anchor_shift >= 5 ? pass_anchor[0] : anchor_shift == 4 ? pass_anchor[i >> 2] : pass_anchor[i >> 1];
     };
-    // every load of the pass (packed codes, block-table entries) is issued before the first store: the
-    // compiler cannot move a load across a store it cannot tell apart from it, and a pass that alternates
-    // them pays one memory round trip per row
-    u32x2 w[8];
+    // (every load of the pass was issued before the first store: the compiler cannot move a load across
+    // a store it cannot tell apart from it, and a pass that alternates them pays one memory round
+    // trip per row)
     if (DENSE && rows >= kPassRows) {
         u32x4 *dst = (u32x4 *)(x.base + head_off + (row0 + rsub) * kDim + col * 8);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) w[i] = fetch_codes<BITS, LAYOUT>(codes, row_base + 4 * i + rsub);
-#pragma unroll
         for (int i = 0; i < 8; ++i) {
-            u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w[i], scale[i], zero[i])
-                             : dequant_row<BITS, DT, CLAMP>(w[i], scale, zero);
+            u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(f.w[i], scale[i], zero[i])
+                             : dequant_row<BITS, DT, CLAMP>(f.w[i], scale, zero);
             if (TR == 1) out = hadamard_row<DT>(out, true);
             if (TR == 2) out = add_anchor<DT>(out, anchor_of(i), anchor_shift, row0 + 4 * i + rsub);
             __builtin_nontemporal_store(out, dst + i * 64);
         }
         return;
     }
-    long long off[8];
-    bool b = false;
-    if (!DENSE) pass_offsets(x, head_off, row0, row0 + rows, off, b);       // a bad block makes the whole pass suspect:
-    bad |= b;                                                             // nothing of it is stored
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int r = 4 * i + rsub;
-        const bool ok = r < rows;                       // uniform over each quad of lanes
-        w[i] = fetch_codes<BITS, LAYOUT>(codes, row_base + (ok ? r : 0));
-        if (DENSE) off[i] = head_off + (row0 + (ok ? r : 0)) * kDim;
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int r = 4 * i + rsub;
-        u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(w[i], scale[i], zero[i])
-                         : dequant_row<BITS, DT, CLAMP>(w[i], scale, zero);
+        u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(f.w[i], scale[i], zero[i])
+                         : dequant_row<BITS, DT, CLAMP>(f.w[i], scale, zero);
         if (TR == 1) out = hadamard_row<DT>(out, true);     // (all 16 lanes of a row take part)
         if (TR == 2) out = add_anchor<DT>(out, anchor_of(i), anchor_shift, row0 + (r < rows ? r : 0));
-        if (r < rows && !b) __builtin_nontemporal_store(out, (u32x4 *)(x.base + off[i] + col * 8));
+        if (r < rows && !f.bad) __builtin_nontemporal_store(out, (u32x4 *)(x.base + f.off[i] + col * 8));
     }
 }
 
-// Dequantize the pass whose packed rows are rows row_base... of `codes` (see fetch_codes for
-// LAYOUT) and store its `rows` existing rows at token rows row0... of head `head_off`, after the
-// inverse of stage T (rotate: Hadamard; anchors: the head's anchor rows of the delta transform).
-// K: scale / zero per channel of the lane; V: per row of the lane.
-template <int BITS, int DT, bool IS_V, bool DENSE, int LAYOUT, int TR = 0>
-__device__ __forceinline__ void dequant_pass(uint8_t *codes, const float scale[8], const float zero[8], bool clamp,
+// Dequantize the fetched pass and store its `rows` existing rows at token rows row0... of head
+// `head_off`, after the inverse of stage T (TR 1: Hadamard; 2: the head's anchor rows of the delta
+// transform).  K: scale / zero per channel of the lane; V: per row of the lane.
+template <int BITS, int DT, bool IS_V, bool DENSE, int TR = 0>
+__device__ __forceinline__ void dequant_pass(const PassFetch &f, const float scale[8], const float zero[8], bool clamp,
                                              const TensorView &x, long long head_off, long long row0, int rows, bool &bad,
-                                             int row_base = 0, const uint16_t *anchors = nullptr, int anchor_shift = 0,
+                                             const uint16_t *anchors = nullptr, int anchor_shift = 0,
                                              const u32x4 *loaded_anchor = nullptr)
 {
-    if (clamp) dequant_pass_rows<BITS, DT, IS_V, DENSE, LAYOUT, true, TR>(codes, scale, zero, x, head_off, row0, rows, bad, row_base, anchors, anchor_shift, loaded_anchor);
-    else dequant_pass_rows<BITS, DT, IS_V, DENSE, LAYOUT, false, TR>(codes, scale, zero, x, head_off, row0, rows, bad, row_base, anchors, anchor_shift, loaded_anchor);
+    bad |= f.bad;
+    if (clamp) dequant_pass_rows<BITS, DT, IS_V, DENSE, true, TR>(f, scale, zero, x, head_off, row0, rows, anchors, anchor_shift, loaded_anchor);
+    else dequant_pass_rows<BITS, DT, IS_V, DENSE, false, TR>(f, scale, zero, x, head_off, row0, rows, anchors, anchor_shift, loaded_anchor);
 }
 
 // the same with the transform chosen at run time (one copy of the pass per transform; a launch
 // only ever runs one of them)
-template <int BITS, int DT, bool IS_V, bool DENSE, int LAYOUT>
-__device__ __forceinline__ void dequant_pass_any(uint8_t *codes, const float scale[8], const float zero[8], bool clamp,
+template <int BITS, int DT, bool IS_V, bool DENSE>
+__device__ __forceinline__ void dequant_pass_any(const PassFetch &f, const float scale[8], const float zero[8], bool clamp,
                                                  const TensorView &x, long long head_off, long long row0, int rows, bool &bad,
                                                  bool rotate, const uint16_t *anchors, int anchor_shift)
 {
-    if (rotate) dequant_pass<BITS, DT, IS_V, DENSE, LAYOUT, 1>(codes, scale, zero, clamp, x, head_off, row0, rows, bad);
-    else if (anchors) dequant_pass<BITS, DT, IS_V, DENSE, LAYOUT, 2>(codes, scale, zero, clamp, x, head_off, row0, rows, bad, 0, anchors, anchor_shift);
-    else dequant_pass<BITS, DT, IS_V, DENSE, LAYOUT, 0>(codes, scale, zero, clamp, x, head_off, row0, rows, bad);
+    if (rotate) dequant_pass<BITS, DT, IS_V, DENSE, 1>(f, scale, zero, clamp, x, head_off, row0, rows, bad);
+    else if (anchors) dequant_pass<BITS, DT, IS_V, DENSE, 2>(f, scale, zero, clamp, x, head_off, row0, rows, bad, anchors, anchor_shift);
+    else dequant_pass<BITS, DT, IS_V, DENSE, 0>(f, scale, zero, clamp, x, head_off, row0, rows, bad);
 }
 
 // Stage T on the rows just loaded (see hadamard_row).
