@@ -77,7 +77,7 @@ __device__ __forceinline__ void dequant_chunk(const CoderArgs &a, const ChunkPos
                                               const u32x4 &meta1, const uint32_t metav[8], const u32x4 &first_anchor, bool &bad)
 {
     using Dec = DecGeom<BITS>;
-    const uint16_t *anchors = TR == 2 ? head_anchors(a.q.anchors, c.lh, a.q.tokens, a.q.anchor_shift) : nullptr;
+    const uint16_t *anchors = TR >= 2 ? head_anchors(a.q.anchors, c.lh, a.q.tokens, a.q.anchor_shift) : nullptr;
     constexpr bool one_anchor = TR == 2;
     u32x4 anchor = first_anchor, anchor_next = first_anchor;
     u32x4 mk0 = meta0, mk1 = meta1;
@@ -103,10 +103,10 @@ __device__ __forceinline__ void dequant_chunk(const CoderArgs &a, const ChunkPos
     }
 }
 
-// XF = false leaves the inverses of stage T out (for launches without a transform): in one kernel
-// with them the plain path pays for their registers (the anchors of short runs, most of all) with
-// its fourth wave per SIMD.
-template <int BITS, int DT, bool IS_V, bool DENSE, bool XF>
+// TR: the inverse of stage T that the launch applies (see dequant_pass_rows).  One kernel per
+// transform: in one kernel, every path pays for the registers of the most expensive one (the anchors
+// of short runs, the rotation) with its fourth wave per SIMD.
+template <int BITS, int DT, bool IS_V, bool DENSE, int TR>
 __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel(CoderArgs a)
 {
     using Geo = ChunkGeom<BITS>;
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
         }
         if (!IS_V) load_meta_k(a.q, c, 0, meta0, meta1);
         else load_meta_v(a.q, c, 0, metav);
-        if (XF && a.q.anchors)
+        if (TR == 2)
             anchor0 = load_anchor(head_anchors(a.q.anchors, c.lh, a.q.tokens, a.q.anchor_shift), a.q.anchor_shift, c.row0);
     }
 #pragma unroll
@@ -242,11 +242,9 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
         wave_sync();
     }
 
-    // dequantize the rows from LDS (one copy of the loop per transform; a launch runs one of them)
+    // dequantize the rows from LDS
     bool bad = false;
-    if (XF && a.q.rotate) dequant_chunk<BITS, DT, IS_V, DENSE, 1>(a, c, lds, meta0, meta1, metav, anchor0, bad);
-    else if (XF && a.q.anchors) dequant_chunk<BITS, DT, IS_V, DENSE, 2>(a, c, lds, meta0, meta1, metav, anchor0, bad);
-    else dequant_chunk<BITS, DT, IS_V, DENSE, 0>(a, c, lds, meta0, meta1, metav, anchor0, bad);
+    dequant_chunk<BITS, DT, IS_V, DENSE, TR>(a, c, lds, meta0, meta1, metav, anchor0, bad);
     if (bad) atomicOr(a.q.status, KVC_DEV_BAD_BLOCK);
 }
 
@@ -258,14 +256,14 @@ template <int BITS, int DT, bool IS_V> static int decode_launch(const CoderArgs 
     const long long need = (a.chunks + NW - 1) / NW;
     if (need <= 0) return KVC_OK;
     const dim3 grid((unsigned)need), block(NW * 64);
-    const bool xf = a.q.rotate || a.q.anchors;
+    const int tr = a.q.rotate ? 1 : !a.q.anchors ? 0 : a.q.anchor_shift >= 5 ? 2 : 3;
+#define KVC_DECODE(D, T) hipLaunchKernelGGL((decode_kernel<BITS, DT, IS_V, D, T>), grid, block, 0, s, a)
     if (a.q.dense) {
-        if (xf) hipLaunchKernelGGL((decode_kernel<BITS, DT, IS_V, true, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((decode_kernel<BITS, DT, IS_V, true, false>), grid, block, 0, s, a);
+        if (tr == 0) KVC_DECODE(true, 0); else if (tr == 1) KVC_DECODE(true, 1); else if (tr == 2) KVC_DECODE(true, 2); else KVC_DECODE(true, 3);
     } else {
-        if (xf) hipLaunchKernelGGL((decode_kernel<BITS, DT, IS_V, false, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((decode_kernel<BITS, DT, IS_V, false, false>), grid, block, 0, s, a);
+        if (tr == 0) KVC_DECODE(false, 0); else if (tr == 1) KVC_DECODE(false, 1); else if (tr == 2) KVC_DECODE(false, 2); else KVC_DECODE(false, 3);
     }
+#undef KVC_DECODE
     return launched();
 }
 

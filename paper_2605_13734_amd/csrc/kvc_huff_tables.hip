@@ -60,81 +60,124 @@ struct BuildLds {
     int longest;
 };
 
-// Code lengths from the weights s.w[], by a workgroup of 256 threads (one symbol each): Huffman's
-// algorithm with two queues, a leaf before a joined node of the same weight and the lower symbol
-// first among equal leaves; while the longest code exceeds kMaxLen all weights are halved (rounded
-// up) and the construction is repeated.  Sorting, depths and halving are spread over the threads;
-// the 255 joins are one thread's work.
-__device__ __forceinline__ void build_lengths(BuildLds &s)
+// One construction of code lengths from the weights s.w[], by a workgroup of 256 threads (one symbol
+// each): Huffman's algorithm with two queues, a leaf before a joined node of the same weight and the
+// lower symbol first among equal leaves.  Sorting and depths are spread over the threads; the 255
+// joins are one thread's work.  Leaves s.len[] and s.longest; ends with a barrier.
+__device__ __forceinline__ void build_once(BuildLds &s)
 {
     constexpr uint32_t kNone = 0xffffffffu;
     const int tid = threadIdx.x;
-    for (;;) {
-        // position of the thread's leaf among all leaves
-        const uint32_t wk = s.w[tid];
-        int pos = 0;
-        for (int t = 0; t < 256; ++t) {
-            const uint32_t wt = s.w[t];
-            pos += (wt < wk || (wt == wk && t < tid)) ? 1 : 0;
-        }
-        s.sw[pos] = wk;
-        s.wi[tid] = kNone;                             // a joined node that does not exist yet never wins
-        if (tid < 2) s.sw[256 + tid] = kNone;
-        if (tid == 0) s.longest = 0;
-        __syncthreads();
-        if (tid == 0) {
-            // Every join reads the two front entries of both queues in one go (one LDS round trip) and
-            // decides in registers; the entries it writes are read by later joins only.
-            int lq = 0, jq = 0;
-            for (int made = 0; made < 255; ++made) {
-                const uint32_t a0 = s.sw[lq], a1 = s.sw[lq + 1], b0 = s.wi[jq], b1 = s.wi[jq + 1];
-                const bool first_leaf = a0 <= b0;      // a leaf wins a tie: its id is lower
-                const uint32_t la = first_leaf ? a1 : a0, jb = first_leaf ? b0 : b1;     // the fronts after the first pick
-                const bool second_leaf = la <= jb;
-                const uint32_t sum = (first_leaf ? a0 : b0) + (second_leaf ? la : jb);
-                uint16_t *p0 = first_leaf ? &s.parent_leaf[lq] : &s.parent_int[jq];
-                lq += first_leaf ? 1 : 0;
-                jq += first_leaf ? 0 : 1;
-                uint16_t *p1 = second_leaf ? &s.parent_leaf[lq] : &s.parent_int[jq];
-                lq += second_leaf ? 1 : 0;
-                jq += second_leaf ? 0 : 1;
-                *p0 = (uint16_t)made;
-                *p1 = (uint16_t)made;
-                s.wi[made] = sum;
-            }
-        }
-        __syncthreads();
-        int d = 1;
-        for (int i = s.parent_leaf[pos]; i != 254 && d < 256; i = s.parent_int[i]) ++d;
-        s.len[tid] = (uint8_t)d;
-        atomicMax(&s.longest, d);
-        __syncthreads();
-        if (s.longest <= kMaxLen) return;
-        const uint32_t v = (wk + 1) >> 1;
-        __syncthreads();                               // everyone has seen `longest` before it is cleared
-        s.w[tid] = v < 1 ? 1 : v;
-        __syncthreads();
+    // position of the thread's leaf among all leaves
+    const uint32_t wk = s.w[tid];
+    int pos = 0;
+    for (int t = 0; t < 256; ++t) {
+        const uint32_t wt = s.w[t];
+        pos += (wt < wk || (wt == wk && t < tid)) ? 1 : 0;
     }
+    s.sw[pos] = wk;
+    s.wi[tid] = kNone;                             // a joined node that does not exist yet never wins
+    if (tid < 2) s.sw[256 + tid] = kNone;
+    if (tid == 0) s.longest = 0;
+    __syncthreads();
+    if (tid == 0) {
+        // Every join reads the two front entries of both queues in one go (one LDS round trip) and
+        // decides in registers; the entries it writes are read by later joins only.
+        int lq = 0, jq = 0;
+        for (int made = 0; made < 255; ++made) {
+            const uint32_t a0 = s.sw[lq], a1 = s.sw[lq + 1], b0 = s.wi[jq], b1 = s.wi[jq + 1];
+            const bool first_leaf = a0 <= b0;      // a leaf wins a tie: its id is lower
+            const uint32_t la = first_leaf ? a1 : a0, jb = first_leaf ? b0 : b1;     // the fronts after the first pick
+            const bool second_leaf = la <= jb;
+            const uint32_t sum = (first_leaf ? a0 : b0) + (second_leaf ? la : jb);
+            uint16_t *p0 = first_leaf ? &s.parent_leaf[lq] : &s.parent_int[jq];
+            lq += first_leaf ? 1 : 0;
+            jq += first_leaf ? 0 : 1;
+            uint16_t *p1 = second_leaf ? &s.parent_leaf[lq] : &s.parent_int[jq];
+            lq += second_leaf ? 1 : 0;
+            jq += second_leaf ? 0 : 1;
+            *p0 = (uint16_t)made;
+            *p1 = (uint16_t)made;
+            s.wi[made] = sum;
+        }
+    }
+    __syncthreads();
+    int d = 1;
+    for (int i = s.parent_leaf[pos]; i != 254 && d < 256; i = s.parent_int[i]) ++d;
+    s.len[tid] = (uint8_t)d;
+    atomicMax(&s.longest, d);
+    __syncthreads();
 }
+
+// The format's length limit: while the longest code exceeds kMaxLen all weights are halved (rounded
+// up) and the construction is repeated.  k halvings turn a weight w into ceil(w / 2^k), so the
+// constructions do not depend on each other: the first kCandidates of them run side by side, one
+// workgroup each, and the one with the fewest halvings that meets the limit is the table.  (Groups
+// along 128 tokens or channels give strongly peaked codes that need five or six halvings; one
+// after the other they took 0.25 ms per call.)
+constexpr int kCandidates = 8;
+
+__device__ __forceinline__ uint32_t halved(uint32_t w, int k) { return (w + ((1u << k) - 1u)) >> k; }
 
 constexpr int kTableWaves = 8;      // waves that fill a decode table
 
-// grid = one workgroup of 256 threads (one symbol each) per table slot of the format
+// grid = kCandidates workgroups of 256 threads (one symbol each) per table slot of the format.
+// A candidate leaves its lengths in the slot's decode-table space of the workspace (unused while
+// compressing); the last one to finish picks and writes the table.
 __global__ __launch_bounds__(256) void build_tables_kernel(CoderArgs a)
 {
-    if (!((a.slot_mask >> blockIdx.x) & 1)) {          // a width the tensor does not use: an empty table
-        a.payload[a.off_aux + 256 * blockIdx.x + threadIdx.x] = 0;
+    const int sec = blockIdx.x / kCandidates, k = blockIdx.x - sec * kCandidates;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
+    if (!((a.slot_mask >> sec) & 1)) {                 // a width the tensor does not use: an empty table
+        if (k == 0) a.payload[a.off_aux + 256 * sec + tid] = 0;
         return;
     }
     __shared__ BuildLds s;
     __shared__ uint32_t block_count[4][16];            // symbols of each length in each block of 64 symbols
-    const int sec = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
-    s.w[tid] = a.ws.hist[256 * sec + tid] + 1;
+    __shared__ int s_pick;
+    const uint32_t w0 = a.ws.hist[256 * sec + tid] + 1;
+    s.w[tid] = halved(w0, k);
     __syncthreads();
-    build_lengths(s);
+    build_once(s);
+    uint32_t *cand = (uint32_t *)(a.ws.lut + 4096 * sec);      // [kCandidates][64] words of lengths, then the longest of each
+    if ((tid & 3) == 0) {
+        const uint32_t word = (uint32_t)s.len[tid] | ((uint32_t)s.len[tid + 1] << 8) | ((uint32_t)s.len[tid + 2] << 16) |
+                              ((uint32_t)s.len[tid + 3] << 24);
+        __hip_atomic_store(cand + 64 * k + (tid >> 2), word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (tid == 0) __hip_atomic_store(cand + 64 * kCandidates + k, (uint32_t)s.longest, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        // (the counters sit behind the ticket, in words that every call clears)
+        const uint32_t done = __hip_atomic_fetch_add(a.ws.ticket + 8 + sec, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        int pick = -2;                                 // not the last candidate: nothing more to do
+        if (done == kCandidates - 1) {
+            pick = -1;                                 // none meets the limit: go on halving
+            for (int j = kCandidates - 1; j >= 0; --j)
+                if (__hip_atomic_load(cand + 64 * kCandidates + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) <= (uint32_t)kMaxLen) pick = j;
+        }
+        s_pick = pick;
+    }
+    __syncthreads();
+    const int pick = s_pick;
+    if (pick == -2) return;
+    int L;
+    if (pick >= 0) {
+        const uint32_t word = __hip_atomic_load(cand + 64 * pick + (tid >> 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        L = (int)((word >> (8 * (tid & 3))) & 255u);
+    } else {
+        for (int j = kCandidates;; ++j) {
+            s.w[tid] = halved(w0, j);
+            __syncthreads();
+            build_once(s);
+            if (s.longest <= kMaxLen) break;
+            __syncthreads();                           // everyone has seen `longest` before it is cleared
+        }
+        L = s.len[tid];
+    }
     // canonical codes: first code of every length, and the symbol's place among the symbols of
     // its length (those of lower blocks, then the lower lanes of its own block)
-    const int L = s.len[tid];
     int within = 0;
 #pragma unroll
     for (int l = 1; l <= kMaxLen; ++l) {
@@ -264,7 +307,7 @@ int launch_table_sample(int bits, int group, int dtype, const CoderArgs &a, hipS
 
 int launch_build_tables(const CoderArgs &any, hipStream_t s)
 {
-    hipLaunchKernelGGL(build_tables_kernel, dim3(any.slots), dim3(256), 0, s, any);
+    hipLaunchKernelGGL(build_tables_kernel, dim3(any.slots * kCandidates), dim3(256), 0, s, any);
     return launched();
 }
 

@@ -578,7 +578,8 @@ __device__ __forceinline__ void pass_fetch(PassFetch &f, uint8_t *codes, const T
     if (!DENSE) pass_offsets(x, head_off, row0, row0 + rows, f.off, f.bad);
 }
 
-// TR: the inverse of stage T applied to every row (0 none, 1 Hadamard, 2 plus the anchor of the row's run)
+// TR: the inverse of stage T applied to every row (0 none, 1 Hadamard, 2 plus the anchor of the row's
+// run, runs of 32 tokens or more, 3 the same for runs of 8 or 16 tokens)
 template <int BITS, int DT, bool IS_V, bool DENSE, bool CLAMP, int TR>
 __device__ __forceinline__ void dequant_pass_rows(const PassFetch &f, const float scale[8], const float zero[8],
                                                   const TensorView &x, long long head_off, long long row0, int rows,
@@ -586,25 +587,25 @@ __device__ __forceinline__ void dequant_pass_rows(const PassFetch &f, const floa
 {
     const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
     // delta transform: a run of 32 tokens or more covers the whole pass (row0 is a multiple of 32), and
-    // the caller may have that one anchor in flight already
-    // (runs of 16 or 8 tokens: two or four anchors per pass, one per 16 or 8 rows; an anchor past
-    // the end of the sequence is replaced by the last one, and no row uses it)
-    u32x4 pass_anchor[4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
-    if (TR == 2) {
-        if (anchor_shift >= 5) {
-            pass_anchor[0] = loaded_anchor ? *loaded_anchor : load_anchor(anchors, anchor_shift, row0);
-        } else {
-            const long long last = row0 + (rows < kPassRows ? rows : kPassRows) - 1;
+    // the caller may have that one anchor in flight already; runs of 16 or 8 tokens take two or four
+    // anchors per pass, one per 16 or 8 rows (an anchor past the end of the sequence is replaced by
+    // the last one, and no row uses it)
+    constexpr int NA = TR == 3 ? 4 : 1;
+    u32x4 pass_anchor[NA];
+    pass_anchor[0] = u32x4{0, 0, 0, 0};
+    if (TR == 2) pass_anchor[0] = loaded_anchor ? *loaded_anchor : load_anchor(anchors, anchor_shift, row0);
+    if (TR == 3) {
+        const long long last = row0 + (rows < kPassRows ? rows : kPassRows) - 1;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const long long r = row0 + ((long long)k << anchor_shift);
-                if ((k << anchor_shift) < kPassRows) pass_anchor[k] = load_anchor(anchors, anchor_shift, r < last ? r : last);
-            }
+        for (int k = 0; k < NA; ++k) {
+            const long long r = row0 + ((long long)k << anchor_shift);
+            pass_anchor[k] = pass_anchor[0];
+            if ((k << anchor_shift) < kPassRows) pass_anchor[k] = load_anchor(anchors, anchor_shift, r < last ? r : last);
         }
     }
     // the anchor of the rows 4*i .. 4*i+3
     auto anchor_of = [&](int i) -> const u32x4 & {
-        return anchor_shift >= 5 ? pass_anchor[0] : anchor_shift == 4 ? pass_anchor[i >> 2] : pass_anchor[i >> 1];
+        return TR != 3 ? pass_anchor[0] : anchor_shift == 4 ? pass_anchor[(i >> 2) % NA] : pass_anchor[(i >> 1) % NA];
     };
     // (every load of the pass was issued before the first store: the compiler cannot move a load across
     // a store it cannot tell apart from it, and a pass that alternates them pays one memory round
@@ -616,7 +617,7 @@ __device__ __forceinline__ void dequant_pass_rows(const PassFetch &f, const floa
             u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(f.w[i], scale[i], zero[i])
                              : dequant_row<BITS, DT, CLAMP>(f.w[i], scale, zero);
             if (TR == 1) out = hadamard_row<DT>(out, true);
-            if (TR == 2) out = add_anchor<DT>(out, anchor_of(i), anchor_shift, row0 + 4 * i + rsub);
+            if (TR >= 2) out = add_anchor<DT>(out, anchor_of(i), anchor_shift, row0 + 4 * i + rsub);
             __builtin_nontemporal_store(out, dst + i * 64);
         }
         return;
@@ -627,7 +628,7 @@ __device__ __forceinline__ void dequant_pass_rows(const PassFetch &f, const floa
         u32x4 out = IS_V ? dequant_row_uniform<BITS, DT, CLAMP>(f.w[i], scale[i], zero[i])
                          : dequant_row<BITS, DT, CLAMP>(f.w[i], scale, zero);
         if (TR == 1) out = hadamard_row<DT>(out, true);     // (all 16 lanes of a row take part)
-        if (TR == 2) out = add_anchor<DT>(out, anchor_of(i), anchor_shift, row0 + (r < rows ? r : 0));
+        if (TR >= 2) out = add_anchor<DT>(out, anchor_of(i), anchor_shift, row0 + (r < rows ? r : 0));
         if (r < rows && !f.bad) __builtin_nontemporal_store(out, (u32x4 *)(x.base + f.off[i] + col * 8));
     }
 }
@@ -654,7 +655,8 @@ __device__ __forceinline__ void dequant_pass_any(const PassFetch &f, const float
                                                  bool rotate, const uint16_t *anchors, int anchor_shift)
 {
     if (rotate) dequant_pass<BITS, DT, IS_V, DENSE, 1>(f, scale, zero, clamp, x, head_off, row0, rows, bad);
-    else if (anchors) dequant_pass<BITS, DT, IS_V, DENSE, 2>(f, scale, zero, clamp, x, head_off, row0, rows, bad, anchors, anchor_shift);
+    else if (anchors && anchor_shift >= 5) dequant_pass<BITS, DT, IS_V, DENSE, 2>(f, scale, zero, clamp, x, head_off, row0, rows, bad, anchors, anchor_shift);
+    else if (anchors) dequant_pass<BITS, DT, IS_V, DENSE, 3>(f, scale, zero, clamp, x, head_off, row0, rows, bad, anchors, anchor_shift);
     else dequant_pass<BITS, DT, IS_V, DENSE, 0>(f, scale, zero, clamp, x, head_off, row0, rows, bad);
 }
 

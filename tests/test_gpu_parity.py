@@ -282,6 +282,30 @@ def test_codec_incompressible_chunks_stored_raw(ref):
     assert got.size == plan.payload_size(256)[0]           # the all-raw bound is reached
 
 
+def peaked_codes(seed, n, ratio, symbols):
+    """n byte values in 2 .. 2+symbols-1 whose frequencies grow by `ratio` from one value to the next."""
+    p = float(ratio) ** np.arange(symbols)
+    return np.random.default_rng(seed).choice(np.arange(2, 2 + symbols), size=n, p=p / p.sum())
+
+
+@pytest.mark.parametrize("ratio_k,ratio_v,symbols", [(2.0, 1.618, 18), (1.3, 3.0, 12), (1.0, 2.0, 6)])
+def test_codec_length_limit(ref, ratio_k, ratio_v, symbols):
+    """Strongly peaked byte frequencies: the plain Huffman code is longer than 12 bits and the table is
+    the one after several halvings of the weights (up to seven here).  Every group holds a 0 and a
+    255, so an 8-bit code is the value itself and the frequencies are the ones chosen here."""
+    L, H, T, D = 1, 2, 128 * 8, 128
+    k = peaked_codes(7, L * H * T * D, ratio_k, symbols).reshape(L, H, T, D)
+    v = peaked_codes(8, L * H * T * D, ratio_v, symbols).reshape(L, H, T, D)
+    k[:, :, 0::32] = 0
+    k[:, :, 1::32] = 255                                # K groups: 32 tokens of a channel
+    v[..., 0::32] = 0
+    v[..., 1::32] = 255                                 # V groups: 32 channels of a token
+    x = torch.from_numpy(np.stack([k, v], axis=1)).to(torch.float16)
+    pay = check_contiguous(ref, x, 8, 8, 32, 32, codec=1)
+    lens_k = pay[int.from_bytes(pay[80:88].tobytes(), "little"):][:256]
+    assert lens_k.max() == 12                          # the limit was reached
+
+
 def test_codec_many_workgroups_scan(ref):
     """Enough chunks that the chunk-offset scan spans many workgroups and look-back windows."""
     x = kvgen.make_kv(31, 4, 8, 128, 128 * 40 + 17, torch.float16)        # 1312 chunks per section
