@@ -111,11 +111,13 @@ __device__ __forceinline__ void build_once(BuildLds &s)
 
 // The format's length limit: while the longest code exceeds kMaxLen all weights are halved (rounded
 // up) and the construction is repeated.  k halvings turn a weight w into ceil(w / 2^k), so the
-// constructions do not depend on each other: the first kCandidates of them run side by side, one
-// workgroup each, and the one with the fewest halvings that meets the limit is the table.  (Groups
-// along 128 tokens or channels give strongly peaked codes that need five or six halvings; one
-// after the other they took 0.25 ms per call.)
-constexpr int kCandidates = 8;
+// constructions do not depend on each other: all of them run side by side, one workgroup each, and
+// the one with the fewest halvings that meets the limit is the table.  (Groups along 128 tokens or
+// channels give strongly peaked codes that need five or six halvings; one after the other they
+// took 0.25 ms per call.)  A table sample is at most 16 chunks of 16 KB, so a weight is at most
+// 2^18 + 1 and 19 halvings leave nothing but ones, whose code has 8 bits everywhere: the last
+// candidate always meets the limit.
+constexpr int kCandidates = 20;
 
 __device__ __forceinline__ uint32_t halved(uint32_t w, int k) { return (w + ((1u << k) - 1u)) >> k; }
 
@@ -151,31 +153,19 @@ __global__ __launch_bounds__(256) void build_tables_kernel(CoderArgs a)
     if (tid == 0) {
         // (the counters sit behind the ticket, in words that every call clears)
         const uint32_t done = __hip_atomic_fetch_add(a.ws.ticket + 8 + sec, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        int pick = -2;                                 // not the last candidate: nothing more to do
+        int pick = -1;                                 // not the last candidate: nothing more to do
         if (done == kCandidates - 1) {
-            pick = -1;                                 // none meets the limit: go on halving
-            for (int j = kCandidates - 1; j >= 0; --j)
+            pick = kCandidates - 1;
+            for (int j = kCandidates - 2; j >= 0; --j)
                 if (__hip_atomic_load(cand + 64 * kCandidates + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) <= (uint32_t)kMaxLen) pick = j;
         }
         s_pick = pick;
     }
     __syncthreads();
     const int pick = s_pick;
-    if (pick == -2) return;
-    int L;
-    if (pick >= 0) {
-        const uint32_t word = __hip_atomic_load(cand + 64 * pick + (tid >> 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        L = (int)((word >> (8 * (tid & 3))) & 255u);
-    } else {
-        for (int j = kCandidates;; ++j) {
-            s.w[tid] = halved(w0, j);
-            __syncthreads();
-            build_once(s);
-            if (s.longest <= kMaxLen) break;
-            __syncthreads();                           // everyone has seen `longest` before it is cleared
-        }
-        L = s.len[tid];
-    }
+    if (pick < 0) return;
+    const uint32_t picked = __hip_atomic_load(cand + 64 * pick + (tid >> 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int L = (int)((picked >> (8 * (tid & 3))) & 255u);
     // canonical codes: first code of every length, and the symbol's place among the symbols of
     // its length (those of lower blocks, then the lower lanes of its own block)
     int within = 0;
