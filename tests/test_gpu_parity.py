@@ -282,6 +282,17 @@ def test_codec_incompressible_chunks_stored_raw(ref):
     assert got.size == plan.payload_size(256)[0]           # the all-raw bound is reached
 
 
+def test_generator_is_the_same_on_the_gpu():
+    """The benchmark draws its inputs on the GPU, the parity tests on the CPU: same seed, same tensor."""
+    for dtype in (torch.float16, torch.bfloat16):
+        a = kvgen.make_kv(3, 2, 4, 128, 257, dtype)
+        b = kvgen.make_kv(3, 2, 4, 128, 257, dtype, device="cuda:0")
+        assert torch.equal(a, b.cpu())
+    pool_c, tab_c = kvgen.make_paged(4, 2, 2, 128, 16 * 5 + 3, torch.float16)
+    pool_g, tab_g = kvgen.make_paged(4, 2, 2, 128, 16 * 5 + 3, torch.float16, device="cuda:0")
+    assert torch.equal(tab_c, tab_g.cpu()) and torch.equal(pool_c, pool_g.cpu())
+
+
 def peaked_codes(seed, n, ratio, symbols):
     """n byte values in 2 .. 2+symbols-1 whose frequencies grow by `ratio` from one value to the next."""
     p = float(ratio) ** np.arange(symbols)

@@ -277,6 +277,10 @@ def test_generator_recipe():
     again = kvgen.make_kv(0, 1, 8, 128, 1024)
     assert torch.equal(again, kvgen.make_kv(0, 1, 8, 128, 1024))
     assert not torch.equal(again, kvgen.make_kv(1, 1, 8, 128, 1024))
+    # counter-based: an element depends on its coordinates and the seed alone
+    assert torch.equal(kvgen.make_kv(0, 1, 8, 128, 300), again[:, :, :, :300])
+    two = kvgen.make_kv(0, 2, 8, 128, 64)
+    assert torch.equal(two[0], again[0, :, :, :64]) and not torch.equal(two[1], two[0])
     tab = kvgen.block_table(3, 64, 64)
     assert sorted(tab.tolist()) == list(range(64))
     lens = kvgen.request_lengths(0, 4, 16384, 32768)
