@@ -266,16 +266,38 @@ template <int DT> __device__ __forceinline__ u32x4 hadamard_row(const u32x4 &in,
                 x[j] = a + b;
                 x[j + h] = a - b;
             }
+    // x[e] += c * (x[e] of lane ^ m): for m = 1, 2 and 8 the lane exchange is a DPP pattern (two quad
+    // permutations, a rotation of the row of 16 by 8) that the multiply-add itself can carry
+    // (v_fmac_f32 with a DPP source: one instruction, the same single rounding); the compiler does not
+    // form it and keeps a separate move, so the eight of a stage are written out.  A DPP source must
+    // not have been written by the two instructions before it (five, if that was a vector write of
+    // EXEC): inside a block the writer of x[e] is eight instructions back, and the block opens with five
+    // wait states.
+#define KVC_FMAC_DPP8(CTRL)                                                                                          \
+    asm("s_nop 4\n\t"                                                                                                \
+        "v_fmac_f32_dpp %0, %0, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                                          \
+        "v_fmac_f32_dpp %1, %1, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                                          \
+        "v_fmac_f32_dpp %2, %2, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                                          \
+        "v_fmac_f32_dpp %3, %3, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                                          \
+        "v_fmac_f32_dpp %4, %4, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                                          \
+        "v_fmac_f32_dpp %5, %5, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                                          \
+        "v_fmac_f32_dpp %6, %6, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                                          \
+        "v_fmac_f32_dpp %7, %7, %8 " CTRL " row_mask:0xf bank_mask:0xf"                                               \
+        : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7])             \
+        : "v"(c))
 #pragma unroll
     for (int m = 1; m < 16; m <<= 1) {
         const float c = (col & m) ? 1.0f : -1.0f;
+        if (m == 1) KVC_FMAC_DPP8("quad_perm:[1,0,3,2]");
+        else if (m == 2) KVC_FMAC_DPP8("quad_perm:[2,3,0,1]");
+        else if (m == 8) KVC_FMAC_DPP8("row_ror:8");
+        else {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float other = m == 1 ? xor_lane_f32<1>(x[e]) : m == 2 ? xor_lane_f32<2>(x[e])
-                              : m == 4 ? xor_lane_f32<4>(x[e]) : xor_lane_f32<8>(x[e]);
-            x[e] = __builtin_fmaf(other, c, x[e]);             // exact product, one rounded sum
+            for (int e = 0; e < 8; ++e)
+                x[e] = __builtin_fmaf(xor_lane_f32<4>(x[e]), c, x[e]);         // exact product, one rounded sum
         }
     }
+#undef KVC_FMAC_DPP8
     constexpr float top = DT == DT_F16 ? 65504.0f : 3.3895313892515355e38f;
     u32x4 out;
 #pragma unroll
