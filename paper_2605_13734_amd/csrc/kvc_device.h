@@ -63,8 +63,18 @@ __device__ __forceinline__ long long row_offset(const TensorView &v, long long h
 // replaced by the last one.  With a block table whose blocks hold 4 tokens or more, the four rows
 // 4*i .. 4*i+3 share a block: its entry is read and turned into a base once per wave, and a lane
 // adds its row's place inside the block with a 24-bit multiply.
+// The block-table entries of the rows row0 + 4*i, i = 0..7, of a pass (rows past `tokens` repeat the
+// last one), one load: lane l brings entry l & 7.  row0 and tokens are the same in all lanes.
+__device__ __forceinline__ int pass_blocks(const TensorView &v, long long row0, long long tokens)
+{
+    long long first = row0 + 4 * (lane_id() & 7);
+    first = first < tokens ? first : tokens - 1;
+    return v.block_table[first >> v.bt_shift];
+}
+
+// `ahead`: the pass's entries from pass_blocks, when the caller had them in flight already.
 __device__ __forceinline__ void pass_offsets(const TensorView &v, long long head_off, long long row0, long long tokens,
-                                             long long off[8], bool &bad)
+                                             long long off[8], bool &bad, const int *ahead = nullptr)
 {
     const int rsub = lane_id() >> 4;
     if (v.block_table == nullptr || !v.bt_wave) {
@@ -77,20 +87,10 @@ __device__ __forceinline__ void pass_offsets(const TensorView &v, long long head
         return;
     }
     const int mask = (1 << v.bt_shift) - 1;
-    // all eight entries are requested before the first one is used: the empty statement below needs
-    // them all in registers, so the compiler cannot wait for them one by one (it does, when it
-    // sees eight loads that each feed one scalar)
-    int entry[8];
+    const int entries = ahead ? *ahead : pass_blocks(v, row0, tokens);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        long long first = row0 + 4 * i;
-        first = first < tokens ? first : tokens - 1;
-        entry[i] = v.block_table[first >> v.bt_shift];
-    }
-    __builtin_amdgcn_sched_group_barrier(0x020, 8, 0);     // (eight memory reads, then whatever follows)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        int blk = __builtin_amdgcn_readfirstlane(entry[i]);
+        int blk = __builtin_amdgcn_readlane(entries, i);
         if ((unsigned)blk >= (unsigned)v.num_phys_blocks) { bad = true; blk = 0; }
         const long long base = head_off + (long long)blk * v.stride_block;
         long long row = row0 + 4 * i + rsub;

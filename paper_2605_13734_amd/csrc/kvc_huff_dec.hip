@@ -74,7 +74,8 @@ __device__ __forceinline__ void load_meta_v(const QuantArgs &q, const ChunkPos &
 // first_anchor (delta transform): the first pass's anchor row.
 template <int BITS, int DT, bool IS_V, bool DENSE, int TR>
 __device__ __forceinline__ void dequant_chunk(const CoderArgs &a, const ChunkPos &c, uint8_t *lds, const u32x4 &meta0,
-                                              const u32x4 &meta1, const uint32_t metav[8], const u32x4 &first_anchor, bool &bad)
+                                              const u32x4 &meta1, const uint32_t metav[8], const u32x4 &first_anchor,
+                                              int first_blocks, bool &bad)
 {
     using Dec = DecGeom<BITS>;
     const uint16_t *anchors = TR >= 2 ? head_anchors(a.q.anchors, c.lh, a.q.tokens, a.q.anchor_shift) : nullptr;
@@ -84,6 +85,9 @@ __device__ __forceinline__ void dequant_chunk(const CoderArgs &a, const ChunkPos
     uint32_t mv[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) mv[i] = metav[i];
+    // paged destination: the block-table entries of a pass are in flight one pass ahead as well
+    const bool paged = !DENSE && a.q.x.block_table != nullptr && a.q.x.bt_wave;
+    int blocks = first_blocks, blocks_next = first_blocks;
 #pragma unroll 1
     for (int p = 0; p < kChunkRows / kPassRows; ++p) {
         if (p * kPassRows >= c.rows) break;
@@ -93,13 +97,16 @@ __device__ __forceinline__ void dequant_chunk(const CoderArgs &a, const ChunkPos
             if (!IS_V) load_meta_k(a.q, c, (p + 1) * kPassRows, mk0, mk1);
             else load_meta_v(a.q, c, (p + 1) * kPassRows, mv);
             if (one_anchor) anchor_next = load_anchor(anchors, a.q.anchor_shift, c.row0 + (p + 1) * kPassRows);
+            if (paged) blocks_next = pass_blocks(a.q.x, c.row0 + (p + 1) * kPassRows, c.row0 + c.rows);
         }
         PassFetch f;
-        pass_fetch<BITS, DENSE, Dec::kLayout>(f, lds, a.q.x, c.head_off, c.row0 + p * kPassRows, c.rows - p * kPassRows, p * kPassRows);
+        pass_fetch<BITS, DENSE, Dec::kLayout>(f, lds, a.q.x, c.head_off, c.row0 + p * kPassRows, c.rows - p * kPassRows, p * kPassRows,
+                                              paged ? &blocks : nullptr);
         dequant_pass<BITS, DT, IS_V, DENSE, TR>(f, scale, zero, clamp, a.q.x, c.head_off, c.row0 + p * kPassRows,
                                                 c.rows - p * kPassRows, bad, anchors, a.q.anchor_shift,
                                                 one_anchor ? &anchor : nullptr);
         anchor = anchor_next;
+        blocks = blocks_next;
     }
 }
 
@@ -169,6 +176,7 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
     u32x4 meta0 = {0, 0, 0, 0}, meta1 = {0, 0, 0, 0};
     uint32_t metav[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     u32x4 anchor0 = {0, 0, 0, 0};                      // delta transform: the first pass's anchor row
+    int blocks0 = 0;                                   // paged destination: the first pass's block-table entries (pass_blocks)
     if (ok) {
         const uint8_t *body = a.payload + a.off_bodies + d0 * 16;
 #pragma unroll
@@ -178,6 +186,7 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
         }
         if (!IS_V) load_meta_k(a.q, c, 0, meta0, meta1);
         else load_meta_v(a.q, c, 0, metav);
+        if (!DENSE && a.q.x.block_table != nullptr && a.q.x.bt_wave) blocks0 = pass_blocks(a.q.x, c.row0, c.row0 + c.rows);
         if (TR == 2)
             anchor0 = load_anchor(head_anchors(a.q.anchors, c.lh, a.q.tokens, a.q.anchor_shift), a.q.anchor_shift, c.row0);
     }
@@ -244,7 +253,7 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
 
     // dequantize the rows from LDS
     bool bad = false;
-    dequant_chunk<BITS, DT, IS_V, DENSE, TR>(a, c, lds, meta0, meta1, metav, anchor0, bad);
+    dequant_chunk<BITS, DT, IS_V, DENSE, TR>(a, c, lds, meta0, meta1, metav, anchor0, blocks0, bad);
     if (bad) atomicOr(a.q.status, KVC_DEV_BAD_BLOCK);
 }
 

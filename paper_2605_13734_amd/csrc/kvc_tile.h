@@ -559,7 +559,7 @@ struct PassFetch {
 
 template <int BITS, bool DENSE, int LAYOUT>
 __device__ __forceinline__ void pass_fetch(PassFetch &f, uint8_t *codes, const TensorView &x, long long head_off,
-                                           long long row0, int rows, int row_base = 0)
+                                           long long row0, int rows, int row_base = 0, const int *blocks = nullptr)
 {
     const int rsub = lane_id() >> 4;
     f.bad = false;
@@ -575,7 +575,7 @@ __device__ __forceinline__ void pass_fetch(PassFetch &f, uint8_t *codes, const T
         f.w[i] = fetch_codes<BITS, LAYOUT>(codes, row_base + (ok ? r : 0));
         if (DENSE) f.off[i] = head_off + (row0 + (ok ? r : 0)) * kDim;
     }
-    if (!DENSE) pass_offsets(x, head_off, row0, row0 + rows, f.off, f.bad);
+    if (!DENSE) pass_offsets(x, head_off, row0, row0 + rows, f.off, f.bad, blocks);
 }
 
 // TR: the inverse of stage T applied to every row (0 none, 1 Hadamard, 2 plus the anchor of the row's
