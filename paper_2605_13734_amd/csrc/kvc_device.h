@@ -72,9 +72,9 @@ __device__ __forceinline__ int pass_blocks(const TensorView &v, long long row0, 
     return v.block_table[first >> v.bt_shift];
 }
 
-// `ahead`: the pass's entries from pass_blocks, when the caller had them in flight already.
+// `ahead` (with have_ahead): the pass's entries from pass_blocks, when the caller had them in flight already.
 __device__ __forceinline__ void pass_offsets(const TensorView &v, long long head_off, long long row0, long long tokens,
-                                             long long off[8], bool &bad, const int *ahead = nullptr)
+                                             long long off[8], bool &bad, bool have_ahead = false, int ahead = 0)
 {
     const int rsub = lane_id() >> 4;
     if (v.block_table == nullptr || !v.bt_wave) {
@@ -87,7 +87,7 @@ __device__ __forceinline__ void pass_offsets(const TensorView &v, long long head
         return;
     }
     const int mask = (1 << v.bt_shift) - 1;
-    const int entries = ahead ? *ahead : pass_blocks(v, row0, tokens);
+    const int entries = have_ahead ? ahead : pass_blocks(v, row0, tokens);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         int blk = __builtin_amdgcn_readlane(entries, i);

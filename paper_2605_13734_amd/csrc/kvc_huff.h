@@ -98,13 +98,14 @@ template <int BITS, int G, int DT, bool IS_V> struct UnitGeom {
 // packed; their codes go to the rows lds_row0 ... of the LDS region.
 template <int BITS, int G, int DT, bool IS_V, bool DENSE, bool XF = true>
 __device__ __forceinline__ void quantize_unit(const QuantArgs &a, const ChunkPos &c, int u, uint8_t *lds, int lds_row0,
-                                              bool write_meta, bool &bad)
+                                              bool write_meta, bool &bad, bool have_blocks = false, const int *blocks = nullptr)
 {
     constexpr int RU = UnitGeom<BITS, G, DT, IS_V>::kRows, PU = UnitGeom<BITS, G, DT, IS_V>::kPasses;
     const long long row0 = c.row0 + u * RU;
     u32x4 raw[PU * 8];
 #pragma unroll
-    for (int p = 0; p < PU; ++p) load_pass<DENSE>(a.x, c.head_off, row0 + p * kPassRows, a.tokens, raw + p * 8, bad);
+    for (int p = 0; p < PU; ++p)
+        load_pass<DENSE>(a.x, c.head_off, row0 + p * kPassRows, a.tokens, raw + p * 8, bad, have_blocks, have_blocks ? blocks[p] : 0);
     if (XF && a.rotate) rotate_rows<DT, PU * 8>(raw);
     if (XF && a.anchors)
         delta_rows<DT, DENSE, PU * 8>(a.x, c.head_off, row0, a.tokens, a.anchor_shift,
@@ -129,10 +130,22 @@ __device__ __forceinline__ void quantize_chunk(const QuantArgs &a, const ChunkPo
                                                bool &bad)
 {
     constexpr int RU = UnitGeom<BITS, G, DT, IS_V>::kRows, NU = UnitGeom<BITS, G, DT, IS_V>::kUnits;
+    constexpr int PU = UnitGeom<BITS, G, DT, IS_V>::kPasses;
+    // paged source: the block-table entries of a unit's passes are requested one unit ahead
+    const bool paged = !DENSE && a.x.block_table != nullptr && a.x.bt_wave;
+    int blocks[PU], blocks_next[PU];
+#pragma unroll
+    for (int p = 0; p < PU; ++p) blocks[p] = blocks_next[p] = paged ? pass_blocks(a.x, c.row0 + p * kPassRows, a.tokens) : 0;
 #pragma unroll 1
     for (int u = 0; u < NU; ++u) {
         if (u * RU >= c.rows) break;
-        quantize_unit<BITS, G, DT, IS_V, DENSE, XF>(a, c, u, lds, u * RU, write_meta, bad);
+        if (paged && (u + 1) * RU < c.rows) {
+#pragma unroll
+            for (int p = 0; p < PU; ++p) blocks_next[p] = pass_blocks(a.x, c.row0 + (u + 1) * RU + p * kPassRows, a.tokens);
+        }
+        quantize_unit<BITS, G, DT, IS_V, DENSE, XF>(a, c, u, lds, u * RU, write_meta, bad, paged, blocks);
+#pragma unroll
+        for (int p = 0; p < PU; ++p) blocks[p] = blocks_next[p];
     }
 }
 

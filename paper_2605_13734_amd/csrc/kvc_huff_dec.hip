@@ -101,7 +101,7 @@ __device__ __forceinline__ void dequant_chunk(const CoderArgs &a, const ChunkPos
         }
         PassFetch f;
         pass_fetch<BITS, DENSE, Dec::kLayout>(f, lds, a.q.x, c.head_off, c.row0 + p * kPassRows, c.rows - p * kPassRows, p * kPassRows,
-                                              paged ? &blocks : nullptr);
+                                              paged, blocks);
         dequant_pass<BITS, DT, IS_V, DENSE, TR>(f, scale, zero, clamp, a.q.x, c.head_off, c.row0 + p * kPassRows,
                                                 c.rows - p * kPassRows, bad, anchors, a.q.anchor_shift,
                                                 one_anchor ? &anchor : nullptr);

@@ -22,7 +22,7 @@ __device__ __forceinline__ void wave_sync()
 // full pass is eight loads at constant offsets from one address.
 template <bool DENSE>
 __device__ __forceinline__ void load_pass(const TensorView &v, long long head_off, long long row0,
-                                          long long tokens, u32x4 raw[8], bool &bad)
+                                          long long tokens, u32x4 raw[8], bool &bad, bool have_blocks = false, int blocks = 0)
 {
     const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
     if (DENSE && row0 + kPassRows <= tokens) {
@@ -40,7 +40,7 @@ __device__ __forceinline__ void load_pass(const TensorView &v, long long head_of
             off[i] = head_off + row * kDim;
         }
     } else {
-        pass_offsets(v, head_off, row0, tokens, off, bad);
+        pass_offsets(v, head_off, row0, tokens, off, bad, have_blocks, blocks);      // (blocks: entries the caller had in flight)
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) raw[i] = __builtin_nontemporal_load((const u32x4 *)(v.base + off[i] + col * 8));
@@ -559,7 +559,7 @@ struct PassFetch {
 
 template <int BITS, bool DENSE, int LAYOUT>
 __device__ __forceinline__ void pass_fetch(PassFetch &f, uint8_t *codes, const TensorView &x, long long head_off,
-                                           long long row0, int rows, int row_base = 0, const int *blocks = nullptr)
+                                           long long row0, int rows, int row_base = 0, bool have_blocks = false, int blocks = 0)
 {
     const int rsub = lane_id() >> 4;
     f.bad = false;
@@ -575,7 +575,7 @@ __device__ __forceinline__ void pass_fetch(PassFetch &f, uint8_t *codes, const T
         f.w[i] = fetch_codes<BITS, LAYOUT>(codes, row_base + (ok ? r : 0));
         if (DENSE) f.off[i] = head_off + (row0 + (ok ? r : 0)) * kDim;
     }
-    if (!DENSE) pass_offsets(x, head_off, row0, row0 + rows, f.off, f.bad, blocks);
+    if (!DENSE) pass_offsets(x, head_off, row0, row0 + rows, f.off, f.bad, have_blocks, blocks);
 }
 
 // TR: the inverse of stage T applied to every row (0 none, 1 Hadamard, 2 plus the anchor of the row's
