@@ -50,6 +50,8 @@ WORKLOADS = {
     # a twelfth field "paged": the KV lives in pages of 16 tokens behind a seeded random block table
     "paged128k_fp16_int4g32": (32, 8, 131072, "f16", 4, 4, 32, 32, 0, 0, None, "paged"),
     "paged128k_fp16_int4g32_huff8": (32, 8, 131072, "f16", 4, 4, 32, 32, 1, 0, None, "paged"),
+    "paged128k_fp16_int2g128": (32, 8, 131072, "f16", 2, 2, 128, 128, 0, 0, None, "paged"),
+    "paged128k_fp16_int8g32": (32, 8, 131072, "f16", 8, 8, 32, 32, 0, 0, None, "paged"),
     "qwen3_32k_bf16_k4v2g64": (94, 4, 32768, "bf16", 4, 2, 64, 64, 0),
 }
 
