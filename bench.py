@@ -34,6 +34,8 @@ WORKLOADS = {
     # transform: 0 none, 1 Hadamard, (2, anchor period) delta
     "llama70b_32k_fp16_int4g32_huff8": (80, 8, 32768, "f16", 4, 4, 32, 32, 1),
     "llama70b_32k_fp16_int4g32": (80, 8, 32768, "f16", 4, 4, 32, 32, 0),
+    "llama70b_32k_bf16_int4g32_huff8": (80, 8, 32768, "bf16", 4, 4, 32, 32, 1),
+    "llama70b_32k_bf16_int4g32": (80, 8, 32768, "bf16", 4, 4, 32, 32, 0),
     "llama70b_32k_fp16_hadamard_int4g32_huff8": (80, 8, 32768, "f16", 4, 4, 32, 32, 1, 1),
     "llama70b_32k_fp16_hadamard_int4g32": (80, 8, 32768, "f16", 4, 4, 32, 32, 0, 1),
     "llama70b_32k_fp16_delta32_int4g32_huff8": (80, 8, 32768, "f16", 4, 4, 32, 32, 1, (2, 32)),

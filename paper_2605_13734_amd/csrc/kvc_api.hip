@@ -542,7 +542,7 @@ static int coder_launches(const kvc_plan_t *p, const kvc_request *r, uint8_t *pa
             L.a.chunks = heads * cph;
             L.a.chunk_base = chunk_at;
             L.a.wg_base = wg_at;
-            const int nw = enc_waves(L.bits, group, p->model.dtype, q.dense != 0);
+            const int nw = enc_waves(L.bits, group, p->model.dtype, q.dense != 0, is_v != 0, q.rotate || q.anchors != nullptr);
             chunk_at += L.a.chunks;
             wg_at += (L.a.chunks + nw - 1) / nw;
             mask |= 1 << L.a.tab;

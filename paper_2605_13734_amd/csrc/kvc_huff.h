@@ -115,11 +115,13 @@ __device__ __forceinline__ void quantize_unit(const QuantArgs &a, const ChunkPos
         KParams kp;
         uint8_t *meta_block = write_meta ? a.meta + (c.lh * nb + row0 / G) * (kDim * 4) : nullptr;
         k_group_params<BITS, DT, PU * 8, ChunkGeom<BITS>::kSubStride>(raw, lds + ChunkGeom<BITS>::kSubBytes, meta_block, kp);
+        forget_unpacked<DT, PU * 8>(raw);
         k_emit<BITS, DT, PU, true>(raw, kp, code_row<BITS, true>(lds, lds_row0), c.rows - u * RU);
     } else {
         constexpr int NG = kDim / G;
         VParams vp;
         v_pass_params<BITS, G, DT>(raw, vp);
+        forget_unpacked<DT, PU * 8>(raw);
         uint32_t *meta = write_meta ? (uint32_t *)a.meta + (c.lh * a.tokens + row0) * NG : nullptr;
         v_emit<BITS, G, DT, true>(raw, vp, code_row<BITS, true>(lds, lds_row0), c.rows - u * RU, meta);
     }

@@ -102,23 +102,20 @@ template <int W> __device__ __forceinline__ void encode_two(const uint32_t *sym,
 // back over earlier tickets until it meets one that knows its inclusive prefix, and publishes
 // its own.  Ticket order guarantees that every predecessor is already running, so the wait
 // always ends; it is bounded by kSpinLimit all the same.
-// Waves per SIMD the register allocation must leave room for: four workgroups of the 2- to 4-bit
-// group-32 encoders fit a compute unit's LDS, and for fp16 rows in the dense layout they fit its
-// registers too without spilling (the other variants would spill, so they keep what they need).
-template <int BITS, int G, int DT, bool DENSE> constexpr int enc_min_waves()
+// Waves per SIMD the register allocation must leave room for: four where the workgroup has 512
+// threads (see enc_waves); the other variants would spill, so they keep what they need.
+template <int BITS, int G, int DT, bool IS_V, bool DENSE, bool XF> constexpr int enc_min_waves()
 {
-#ifdef KVC_EXP_AHEAD
-    return (BITS <= 4 && G == 32 && DT == DT_F16 && DENSE) ? KVC_EXP_AHEAD : 1;
-#endif
-    return (BITS <= 4 && G == 32 && DT == DT_F16 && DENSE) ? 4 : 1;
+    return enc_waves(BITS, G, DT, DENSE, IS_V, XF) == 8 ? 4 : 1;
 }
 
 template <int BITS, int G, int DT, bool IS_V, bool DENSE, bool XF>
-__global__ __launch_bounds__(enc_waves(BITS, G, DT, DENSE) * 64) __attribute__((amdgpu_waves_per_eu(enc_min_waves<BITS, G, DT, DENSE>())))
+__global__ __launch_bounds__(enc_waves(BITS, G, DT, DENSE, IS_V, XF) * 64)
+__attribute__((amdgpu_waves_per_eu(enc_min_waves<BITS, G, DT, IS_V, DENSE, XF>())))
 void encode_kernel(CoderArgs a)
 {
     using Geo = ChunkGeom<BITS>;
-    constexpr int W = Geo::kWords, NW = enc_waves(BITS, G, DT, DENSE);
+    constexpr int W = Geo::kWords, NW = enc_waves(BITS, G, DT, DENSE, IS_V, XF);
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * Geo::kLds];
     __shared__ EncTables enc;
     __shared__ uint32_t s_units[NW];
@@ -146,10 +143,6 @@ void encode_kernel(CoderArgs a)
         ChunkPos c = chunk_pos(a.q, chunk);
         rows = c.rows;
         bool bad = false;
-#ifdef KVC_EXP_AHEAD
-        if (DENSE && c.rows == kChunkRows && !(XF && (a.q.rotate || a.q.anchors))) quantize_chunk_ahead<BITS, G, DT, IS_V, KVC_EXP_UNITS>(a.q, c, lds);
-        else
-#endif
         quantize_chunk<BITS, G, DT, IS_V, DENSE, XF>(a.q, c, lds, true, bad);
         if (bad) atomicOr(a.q.status, KVC_DEV_BAD_BLOCK);
         wave_sync();
@@ -288,7 +281,7 @@ void encode_kernel(CoderArgs a)
 
 template <int BITS, int G, int DT, bool IS_V> static int encode_launch(const CoderArgs &a, hipStream_t s)
 {
-    const int NW = enc_waves(BITS, G, DT, a.q.dense != 0);
+    const int NW = enc_waves(BITS, G, DT, a.q.dense != 0, IS_V, a.q.rotate || a.q.anchors != nullptr);
     const long long need = (a.chunks + NW - 1) / NW;
     if (need <= 0) return KVC_OK;
     // K token blocks of 64 and 128 rows, and V groups of 32 channels (the variant that is short of

@@ -112,11 +112,12 @@ struct CoderScratch {
 };
 
 // Chunks (= waves) per encoder workgroup.  One look-back per workgroup is the encoder's serial part,
-// so the variants whose registers allow 512 threads (2- to 4-bit codes, groups of 32, fp16 rows in
-// the dense layout) take eight chunks per workgroup; 8-bit chunks need twice the LDS and take two.
-constexpr int enc_waves(int bits, int group, int dtype, bool dense)
+// so the variants whose registers allow 512 threads (2- to 4-bit codes, groups of 32, the dense
+// layout; not the V kernels with the transforms for bf16 rows or 3-bit codes) take eight chunks per workgroup; 8-bit
+// chunks need twice the LDS and take two.  `transform`: the launch applies stage T.
+constexpr int enc_waves(int bits, int group, int dtype, bool dense, bool is_v, bool transform)
 {
-    return bits == 8 ? 2 : (group == 32 && dtype == DT_F16 && dense) ? 8 : 4;
+    return bits == 8 ? 2 : (group == 32 && dense && !(is_v && transform && (dtype == DT_BF16 || bits == 3))) ? 8 : 4;
 }
 
 // One launch of the coder: a tensor, or with per-head widths the heads of one width of a tensor

@@ -37,6 +37,7 @@ __global__ __launch_bounds__(256) void compress_k_kernel(QuantArgs a)
     KParams kp;
     uint8_t *meta_block = a.meta + (u.lh * a.units_per_head + u.blk) * (kDim * 4);
     k_group_params<BITS, DT, P * 8, 16>(raw, (uint8_t *)(xch_all + wave_id() * kXchFloats), meta_block, kp);
+    forget_unpacked<DT, P * 8>(raw);
     uint8_t *codes = head_codes<BITS>(a, u.lh) + row0 * (16 * BITS);
     const long long left = a.tokens - row0;
     k_emit<BITS, DT, P, false>(raw, kp, codes, left < G ? (int)left : G);
@@ -86,6 +87,7 @@ __global__ __launch_bounds__(256) void compress_v_kernel(QuantArgs a)
                                  head_anchors(a.anchors, u.lh, a.tokens, a.anchor_shift), true, raw, bad);
     VParams vp;
     v_pass_params<BITS, GV, DT>(raw, vp);
+    forget_unpacked<DT, 8>(raw);
     uint8_t *codes = head_codes<BITS>(a, u.lh) + row0 * (16 * BITS);
     uint32_t *meta = (uint32_t *)a.meta + (u.lh * a.tokens + row0) * NG;
     const long long left = a.tokens - row0;

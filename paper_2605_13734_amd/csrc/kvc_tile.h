@@ -660,6 +660,17 @@ __device__ __forceinline__ void dequant_pass_any(const PassFetch &f, const float
     else dequant_pass<BITS, DT, IS_V, DENSE, 0>(f, scale, zero, clamp, x, head_off, row0, rows, bad);
 }
 
+// bf16 rows are widened to fp32 once for the statistics and once for the quantizer.  Left alone, the
+// compiler keeps the widened copy of the whole unit alive from one to the other (64 registers per
+// pass, against 32 for the rows themselves); after this statement it no longer knows that the rows
+// are the ones it widened, and widens again (one shift or mask per element).
+template <int DT, int N> __device__ __forceinline__ void forget_unpacked(u32x4 *raw)
+{
+    if (DT != DT_BF16) return;
+#pragma unroll
+    for (int i = 0; i < N; ++i) asm volatile("" : "+v"(raw[i][0]), "+v"(raw[i][1]), "+v"(raw[i][2]), "+v"(raw[i][3]));
+}
+
 // Stage T on the rows just loaded (see hadamard_row).
 template <int DT, int N> __device__ __forceinline__ void rotate_rows(u32x4 *raw)
 {
