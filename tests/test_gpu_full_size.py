@@ -232,3 +232,54 @@ def test_paged_128k_sweep(ref):
             check_sampled_heads(ref, buf, 0, lambda l, kv, h: logical(pool, idx1, l, kv, h),
                                 lambda l, kv, h: logical(out, idx2, l, kv, h), L, H, T, 1, bits, bits, g, g, samples)
             del buf
+
+
+def test_paged_128k_with_lossless_stage(ref):
+    """The paged tensor of the sweep through the coder kernels (4-bit, group 32): code tables rebuilt
+    by the oracle, sampled chunk bodies byte for byte, and the reconstruction into other pages equal
+    to the one of the codec-free payload, bit for bit, for every page."""
+    L, H, T, bt = 32, 8, 131072, 16
+    pool, table = kvgen.make_paged(0, L, H, 128, T, torch.float16, "cuda", bt)
+    table2 = kvgen.block_table(7, T // bt, T // bt, "cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    idx1 = table.to(torch.int64)
+
+    def logical(p, idx, l, kv, h):
+        return p[l, kv, idx][:, :, h, :].reshape(T, 128).cpu()
+
+    outs = []
+    for codec in (0, 1):
+        plan = kvc.Plan(1, L, H, 128, 4, 4, 32, 32, codec, max_tokens=T)
+        buf = kvc.Buffers(plan, [T])
+        buf.compress([kvc.paged_request(pool, table, T)], stream)
+        out = torch.zeros_like(pool)
+        buf.decompress([kvc.paged_request(out, table2, T)], stream)
+        torch.cuda.synchronize()
+        assert int(buf.status[0]) == 0
+        outs.append(out)
+        if codec:
+            cph = T // 128
+            n = L * H * cph
+            hdr = dev_bytes(buf.payload, 0, 128)
+            rc, _, _, tokens, total, sec = kvc.payload_inspect(hdr)
+            assert rc == 0 and tokens == T and total == int(buf.out_bytes[0])
+            d = dev_bytes(buf.payload, sec[4] + 512, 4 * (2 * n + 1)).view("<u4").astype(np.int64)
+            assert d[0] == 0 and (np.diff(d) > 0).all() and (np.diff(d) * 16 <= 128 * 64).all()
+            assert sec[6] + 16 * int(d[-1]) == total
+            # the tables are the ones the oracle builds from the 16 sampled chunks of each section
+            tabs = dev_bytes(buf.payload, sec[4], 512)
+            cfg1 = head_cfg(ref, 1, 4, 4, 32, 32, 1)
+            for kv in (0, 1):
+                hist = np.zeros(256, dtype=np.uint32)
+                for ch in sorted({i * n // 16 for i in range(16)}):
+                    lh, cb = divmod(ch, cph)
+                    l, h = divmod(lh, H)
+                    xh = kvgen.as_u16(logical(pool, idx1, l, kv, h)[cb * 128: cb * 128 + 128].contiguous())
+                    codes, _ = ref.compress_head(cfg1, kv, xh, ref.contiguous_layout(1, 128, 128), 128, 0, 0)
+                    hist += np.bincount(codes, minlength=256).astype(np.uint32)
+                assert np.array_equal(ref.huff_lengths(hist), tabs[256 * kv: 256 * kv + 256]), kv
+            rng = np.random.default_rng(2)
+            picks = [(kv, int(rng.integers(0, n))) for kv in (0, 1) for _ in range(4)] + [(0, 0), (1, n - 1)]
+            check_sampled_bodies(ref, buf, lambda l, kv, h: logical(pool, idx1, l, kv, h), L, H, T, 1, 4, 4, 32, 32, picks)
+        del buf
+    assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
