@@ -42,6 +42,8 @@ WORKLOADS = {
     "llama70b_32k_fp16_delta32_int4g32": (80, 8, 32768, "f16", 4, 4, 32, 32, 0, (2, 32)),
     "llama70b_32k_fp16_int4g128_huff8": (80, 8, 32768, "f16", 4, 4, 128, 128, 1),
     "llama70b_32k_fp16_int2g64": (80, 8, 32768, "f16", 2, 2, 64, 64, 0),
+    "llama70b_32k_fp16_int2g32_huff8": (80, 8, 32768, "f16", 2, 2, 32, 32, 1),
+    "llama70b_32k_fp16_int8g32_huff8": (80, 8, 32768, "f16", 8, 8, 32, 32, 1),
     # per-head widths: a seeded random half of the heads at 8 bits, the other half at 2 (the paper's
     # MixHQ takes the split from trained head masks, which are not available here)
     "llama70b_32k_fp16_mixhq_8_2_g32": (80, 8, 32768, "f16", 4, 4, 32, 32, 0, 0, (8, 2)),
