@@ -124,6 +124,42 @@ def test_host_errors_before_launch(lib):
     assert e.value.status == -2                                   # block size not a power of two
 
 
+def test_newer_entry_points_refuse_on_the_host(lib):
+    """kvc_stream_probe, kvc_workspace_init, kvc_table_bytes and kvc_compress_static: what the host can
+    see is refused before a device is touched (there is none here)."""
+    def status(fn, *a):
+        with pytest.raises(kvc.KvcError) as e:
+            fn(*a)
+        return e.value.status
+
+    assert status(kvc.stream_probe, 2, 0x1000, 0x2000, 128, 80) == -1       # no such mode
+    assert status(kvc.stream_probe, 0, 0x1000, 0x2000, 100, 80) == -1       # rows not whole chunks
+    assert status(kvc.stream_probe, 0, 0x1000, 0x2000, 128, 72) == -1       # payload rows not whole 16 bytes
+    assert status(kvc.stream_probe, 1, 0x1000, 0x2000, 128, 272) == -1      # payload rows wider than the tensor's
+    assert status(kvc.stream_probe, 0, 0x1004, 0x2000, 128, 80) == -1       # misaligned
+    assert status(kvc.stream_probe, 0, None, 0x2000, 128, 80) == -1
+    kvc.stream_probe(0, 0x1000, 0x2000, 0, 80)                              # nothing to do is not an error
+    plain = kvc.Plan(1, 2, 2, max_tokens=64)
+    assert lib.kvc_table_bytes(plain._h) == 0
+    kvc.workspace_init(plain, None)                                         # no tables: nothing to bring over
+    tk = np.array([2, 8, 4, 3], dtype=np.uint8)
+    mixed = kvc.Plan(1, 2, 2, 128, 0, 4, 32, 32, 0, max_tokens=64, head_bits_k=tk)
+    assert lib.kvc_table_bytes(mixed._h) > 0
+    assert status(kvc.workspace_init, mixed, None) == -1                    # tables need a workspace
+    assert status(kvc.workspace_init, mixed, 0x1004) == -1
+    r = kvc.request(0x1000, 0x2000, 64, 128 * 64 * 2, 128 * 64, 128)
+    assert status(kvc.compress_static, mixed, [r], 0x10000, [0, 1 << 20], 0x100, 0x200) == -2    # width tables
+    huge = kvc.Plan(1, 80, 8, 128, 4, 4, 32, 32, 1, max_tokens=1 << 20)
+    assert huge.workspace_size() > lib_static_bytes()
+    assert status(kvc.compress_static, huge, [r], 0x10000, [0, 1 << 20], 0x100, 0x200) == -3    # larger than the static array
+
+
+def lib_static_bytes():
+    text = open(os.path.join(ROOT, "include", "kvc.h")).read()
+    m = re.search(r"#define KVC_STATIC_WORKSPACE_BYTES \((\d+)u << (\d+)\)", text)
+    return int(m.group(1)) << int(m.group(2))
+
+
 def test_inspect_accepts_payloads_with_width_tables(ref):
     """kvc_payload_inspect on oracle payloads whose tensors carry per-head width tables."""
     import torch
