@@ -64,12 +64,26 @@ static int width_at(const kvc_plan_t *p, int is_v, long long lh)
     return t ? t[lh] : (is_v ? p->strat.bits_v : p->strat.bits_k);
 }
 
-// Optional measurement hook (kvc_trace): events recorded between the stages of a call.
-static void mark(const kvc_plan_t *plan, hipStream_t s)
-{
-    kvc_plan_t *p = const_cast<kvc_plan_t *>(plan);
-    if (p->trace && p->trace_n < p->trace_cap && hipEventRecord(p->trace[p->trace_n], s) == hipSuccess) ++p->trace_n;
-}
+// Optional measurement hook (kvc_trace): events recorded between the stages of a call, four per
+// request: before anything of the request is enqueued, after its set-up, after K, after V.  Requests
+// that share their launches (see request_window) share the moments.
+struct Marks {
+    kvc_plan_t *p;
+    hipStream_t s;
+    int base;
+    Marks(const kvc_plan_t *plan, hipStream_t stream) : p(const_cast<kvc_plan_t *>(plan)), s(stream), base(p->trace_n) {}
+    void at(int request, int stage) const
+    {
+        const int idx = base + 4 * request + stage;
+        if (p->trace && idx < p->trace_cap && hipEventRecord(p->trace[idx], s) == hipSuccess && p->trace_n < idx + 1) p->trace_n = idx + 1;
+    }
+    void window(int first, int end, int stage) const
+    {
+        if (!p->trace) return;
+        for (int i = first; i < end; ++i)
+            if (!(stage == 0 && i == 0)) at(i, stage);      // (the first request's first mark opens the call)
+    }
+};
 
 extern "C" int kvc_trace(kvc_plan_t *plan, void **hip_events, int32_t capacity)
 {
@@ -448,31 +462,70 @@ static QuantArgs quant_args(const kvc_plan_t *p, const kvc_request *r, int is_v,
     return a;
 }
 
-// One tensor without the coder: one launch, or one per width present in the head table.
-static int launch_tensor(const kvc_plan_t *p, int is_v, bool compress, QuantArgs a, const uint8_t *dev_tables, hipStream_t s)
+// One tensor of the requests of a window without the coder: one launch, or one per width present in
+// the head table.
+static int launch_tensor(const kvc_plan_t *p, int is_v, bool compress, QuantBatch b, const uint8_t *dev_tables, hipStream_t s)
 {
     const int dt = p->model.dtype;
     const int group = is_v ? p->strat.group_v : p->strat.group_k;
     if (!p->has_table[is_v]) {
         const int bits = is_v ? p->strat.bits_v : p->strat.bits_k;
-        return compress ? launch_compress_tensor(is_v, bits, group, dt, a, s) : launch_decompress_tensor(is_v, bits, group, dt, a, s);
+        return compress ? launch_compress_tensor(is_v, bits, group, dt, b, s) : launch_decompress_tensor(is_v, bits, group, dt, b, s);
     }
     const long long LH = (long long)p->model.layers * p->model.kv_heads;
     const TableLayout t = table_layout(LH, p->has_table[0] + p->has_table[1]);
-    a.bits_before = (const long long *)(dev_tables + t.bits_before[is_v]);
     const int *list = (const int *)(dev_tables + t.head_list[is_v]);
     for (int w = 0; w < 4; ++w) {
         const int n = p->width_count[is_v][w];
         if (n > 0) {
-            a.head_list = list;
-            a.total_units = a.units_per_head * n;
-            const int rc = compress ? launch_compress_tensor(is_v, kWidths[w], group, dt, a, s)
-                                    : launch_decompress_tensor(is_v, kWidths[w], group, dt, a, s);
+            for (int i = 0; i < b.n; ++i) {
+                b.item[i].bits_before = (const long long *)(dev_tables + t.bits_before[is_v]);
+                b.item[i].head_list = list;
+                b.item[i].total_units = b.item[i].units_per_head * n;
+            }
+            const int rc = compress ? launch_compress_tensor(is_v, kWidths[w], group, dt, b, s)
+                                    : launch_decompress_tensor(is_v, kWidths[w], group, dt, b, s);
             if (rc) return rc;
         }
         list += n;
     }
     return KVC_OK;
+}
+
+// The requests [first, end) that can share their launches: at most `limit`, and of one layout class
+// (the kernels for rows that are contiguous per head are not the ones for strided or paged rows).
+// Empty requests have no work in any launch and fit every window.
+static bool dense_layout(const kvc_request *r) { return !r->block_table && r->stride_token == kDim; }
+
+static int request_window(const kvc_request *reqs, int n, int first, int limit, int *lead)
+{
+    int end = first, leader = -1;
+    while (end < n && end - first < limit) {
+        if (reqs[end].tokens > 0) {
+            if (leader < 0) leader = end;
+            else if (dense_layout(&reqs[end]) != dense_layout(&reqs[leader])) break;
+        }
+        ++end;
+    }
+    *lead = leader < 0 ? first : leader;
+    return end;
+}
+
+// the window's tensor as one batch, the leader (a request that has rows) in front: the launchers
+// read the kernel variant off the first item
+static QuantBatch quant_batch(const kvc_plan_t *plan, const kvc_request *reqs, int first, int end, int lead, int is_v,
+                              void *payload, const uint64_t *payload_off, int32_t *dev_status, bool compress)
+{
+    QuantBatch b;
+    memset(&b, 0, sizeof b);
+    for (int k = 0; k <= end - first; ++k) {
+        const int i = k == 0 ? lead : (first + k - 1);
+        if (k > 0 && i == lead) continue;
+        Geometry g;
+        geometry(plan, reqs[i].tokens, &g);
+        b.item[b.n++] = quant_args(plan, &reqs[i], is_v, (uint8_t *)payload + payload_off[i], g, dev_status + i, compress);
+    }
+    return b;
 }
 
 extern "C" size_t kvc_table_bytes(const kvc_plan_t *plan) { return plan ? plan->blob_bytes : 0; }
@@ -589,7 +642,8 @@ static int compress_on(const kvc_plan_t *plan, const kvc_request *reqs, int32_t 
     }
     const kvc_strategy &st = plan->strat;
     const int dt = plan->model.dtype;
-    mark(plan, s);
+    const Marks marks(plan, s);
+    marks.at(0, 0);
     for (int first = 0; first < n; first += kPrologueBatch) {
         PrologueArgs pa;
         memset(&pa, 0, sizeof pa);
@@ -645,21 +699,24 @@ static int compress_on(const kvc_plan_t *plan, const kvc_request *reqs, int32_t 
         }
         KVC_TRY(launch_compress_prologue(pa, s));
     }
-    for (int i = 0; i < n; ++i) {
-        const kvc_request *r = &reqs[i];
-        Geometry g;
-        geometry(plan, r->tokens, &g);
-        uint8_t *pl = (uint8_t *)payload + payload_off[i];
-        QuantArgs qk = quant_args(plan, r, 0, pl, g, dev_status + i, true);
-        QuantArgs qv = quant_args(plan, r, 1, pl, g, dev_status + i, true);
-        if (i > 0) mark(plan, s);
+    for (int first = 0; first < n;) {
+        int lead;
+        const int end = request_window(reqs, n, first, st.codec ? 1 : kQuantBatch, &lead);
+        marks.window(first, end, 0);
         if (!st.codec) {
-            mark(plan, s);
-            KVC_TRY(launch_tensor(plan, 0, true, qk, (const uint8_t *)workspace, s));
-            mark(plan, s);
-            KVC_TRY(launch_tensor(plan, 1, true, qv, (const uint8_t *)workspace, s));
-            mark(plan, s);
+            marks.window(first, end, 1);
+            KVC_TRY(launch_tensor(plan, 0, true, quant_batch(plan, reqs, first, end, lead, 0, payload, payload_off, dev_status, true),
+                                  (const uint8_t *)workspace, s));
+            marks.window(first, end, 2);
+            KVC_TRY(launch_tensor(plan, 1, true, quant_batch(plan, reqs, first, end, lead, 1, payload, payload_off, dev_status, true),
+                                  (const uint8_t *)workspace, s));
+            marks.window(first, end, 3);
         } else {
+            const int i = first;
+            const kvc_request *r = &reqs[i];
+            Geometry g;
+            geometry(plan, r->tokens, &g);
+            uint8_t *pl = (uint8_t *)payload + payload_off[i];
             uint8_t *ws = (uint8_t *)workspace + plan->blob_bytes + (size_t)i * plan->ws_request;
             const long long cap = (long long)(payload_off[i + 1] - payload_off[i]);
             CoderLaunch cl[kTableSlots];
@@ -667,14 +724,15 @@ static int compress_on(const kvc_plan_t *plan, const kvc_request *reqs, int32_t 
                                                 (const uint8_t *)workspace, cl);
             for (int j = 0; j < launches; ++j) KVC_TRY(launch_table_sample(cl[j].bits, cl[j].group, dt, cl[j].a, s));
             KVC_TRY(launch_build_tables(cl[0].a, s));
-            mark(plan, s);
+            marks.at(i, 1);
             for (int j = 0; j < launches; ++j)
                 if (!cl[j].a.is_v) KVC_TRY(launch_encode_section(cl[j].bits, cl[j].group, dt, cl[j].a, s));
-            mark(plan, s);
+            marks.at(i, 2);
             for (int j = 0; j < launches; ++j)
                 if (cl[j].a.is_v) KVC_TRY(launch_encode_section(cl[j].bits, cl[j].group, dt, cl[j].a, s));
-            mark(plan, s);
+            marks.at(i, 3);
         }
+        first = end;
     }
     return KVC_OK;
 }
@@ -739,7 +797,8 @@ extern "C" int kvc_decompress(const kvc_plan_t *plan, const void *payload, const
     }
     hipStream_t s = (hipStream_t)hip_stream;
     const int dt = plan->model.dtype;
-    mark(plan, s);
+    const Marks marks(plan, s);
+    marks.at(0, 0);
     for (int first = 0; first < n; first += kCheckBatch) {
         CheckArgs ca;
         memset(&ca, 0, sizeof ca);
@@ -763,35 +822,39 @@ extern "C" int kvc_decompress(const kvc_plan_t *plan, const void *payload, const
         }
         KVC_TRY(launch_decompress_prologue(ca, s));
     }
-    for (int i = 0; i < n; ++i) {
-        const kvc_request *r = &dst[i];
-        Geometry g;
-        geometry(plan, r->tokens, &g);
-        uint8_t *pl = (uint8_t *)payload + payload_off[i];
-        const long long cap = (long long)(payload_off[i + 1] - payload_off[i]);
-        QuantArgs qk = quant_args(plan, r, 0, pl, g, dev_status + i, false);
-        QuantArgs qv = quant_args(plan, r, 1, pl, g, dev_status + i, false);
-        if (i > 0) mark(plan, s);
+    for (int first = 0; first < n;) {
+        int lead;
+        const int end = request_window(dst, n, first, st.codec ? 1 : kQuantBatch, &lead);
+        marks.window(first, end, 0);
         if (!st.codec) {
-            mark(plan, s);
-            KVC_TRY(launch_tensor(plan, 0, false, qk, (const uint8_t *)workspace, s));
-            mark(plan, s);
-            KVC_TRY(launch_tensor(plan, 1, false, qv, (const uint8_t *)workspace, s));
-            mark(plan, s);
+            marks.window(first, end, 1);
+            KVC_TRY(launch_tensor(plan, 0, false, quant_batch(plan, dst, first, end, lead, 0, const_cast<void *>(payload), payload_off, dev_status, false),
+                                  (const uint8_t *)workspace, s));
+            marks.window(first, end, 2);
+            KVC_TRY(launch_tensor(plan, 1, false, quant_batch(plan, dst, first, end, lead, 1, const_cast<void *>(payload), payload_off, dev_status, false),
+                                  (const uint8_t *)workspace, s));
+            marks.window(first, end, 3);
         } else {
+            const int i = first;
+            const kvc_request *r = &dst[i];
+            Geometry g;
+            geometry(plan, r->tokens, &g);
+            uint8_t *pl = (uint8_t *)payload + payload_off[i];
+            const long long cap = (long long)(payload_off[i + 1] - payload_off[i]);
             uint8_t *ws = (uint8_t *)workspace + plan->blob_bytes + (size_t)i * plan->ws_request;
             CoderLaunch cl[kTableSlots];
             const int launches = coder_launches(plan, r, pl, g, ws, cap, nullptr, dev_status + i, false,
                                                 (const uint8_t *)workspace, cl);
             KVC_TRY(launch_decode_prepare(cl[0].a, s));
-            mark(plan, s);
+            marks.at(i, 1);
             for (int j = 0; j < launches; ++j)
                 if (!cl[j].a.is_v) KVC_TRY(launch_decode_section(cl[j].bits, cl[j].group, dt, cl[j].a, s));
-            mark(plan, s);
+            marks.at(i, 2);
             for (int j = 0; j < launches; ++j)
                 if (cl[j].a.is_v) KVC_TRY(launch_decode_section(cl[j].bits, cl[j].group, dt, cl[j].a, s));
-            mark(plan, s);
+            marks.at(i, 3);
         }
+        first = end;
     }
     return KVC_OK;
 }

@@ -34,6 +34,14 @@ struct QuantArgs {
     int *status;                // device status word of the request
 };
 
+// The same tensor (K or V) of several requests of a call in one launch: blockIdx.y picks the request.
+// All items take the same kernel (same plan; same layout class, see QuantArgs::dense).
+constexpr int kQuantBatch = 12;     // (the argument block stays below 4 KB)
+struct QuantBatch {
+    QuantArgs item[kQuantBatch];
+    int n;
+};
+
 // Geometry of one payload (all byte counts), shared by host code of compress / decompress.
 struct Geometry {
     long long meta_k, meta_v, aux, codes_k, codes_v;
@@ -48,12 +56,12 @@ struct Geometry {
 
 struct HeaderBytes { uint32_t w[32]; };
 
-int launch_compress_tensor(int is_v, int bits, int group, int dtype, const QuantArgs &a, hipStream_t s);
-int launch_decompress_tensor(int is_v, int bits, int group, int dtype, const QuantArgs &a, hipStream_t s);
+int launch_compress_tensor(int is_v, int bits, int group, int dtype, const QuantBatch &b, hipStream_t s);
+int launch_decompress_tensor(int is_v, int bits, int group, int dtype, const QuantBatch &b, hipStream_t s);
 // one translation unit per code width (kvc_quant.hip compiled with -DKVC_BITS=...)
 #define KVC_DECLARE_QUANT(B)                                                                              \
-    int launch_compress_bits##B(int is_v, int group, int dtype, const QuantArgs &a, hipStream_t s);      \
-    int launch_decompress_bits##B(int is_v, int dtype, const QuantArgs &a, hipStream_t s);
+    int launch_compress_bits##B(int is_v, int group, int dtype, const QuantBatch &b, hipStream_t s);     \
+    int launch_decompress_bits##B(int is_v, int dtype, const QuantBatch &b, hipStream_t s);
 KVC_DECLARE_QUANT(2) KVC_DECLARE_QUANT(3) KVC_DECLARE_QUANT(4) KVC_DECLARE_QUANT(8)
 #undef KVC_DECLARE_QUANT
 // Service work of one request before its tensors are compressed (see compress_prologue_kernel).

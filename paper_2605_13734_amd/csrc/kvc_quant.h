@@ -47,12 +47,19 @@ __device__ __forceinline__ void report(int *status, bool bad)
     if (bad) atomicOr(status, KVC_DEV_BAD_BLOCK);
 }
 
-static inline dim3 grid_for(long long units) { return dim3((unsigned)((units + 3) / 4)); }
+// grid: x = workgroups of four units for the largest item, y = items
+static inline dim3 grid_for(const QuantBatch &b)
+{
+    long long most = 0;
+    for (int i = 0; i < b.n; ++i) most = b.item[i].total_units > most ? b.item[i].total_units : most;
+    return dim3((unsigned)((most + 3) / 4), (unsigned)b.n);
+}
 
-#define KVC_LAUNCH(kernel, a, s)                                                        \
+#define KVC_LAUNCH(kernel, b, s)                                                        \
     do {                                                                                \
-        if ((a).total_units > 0)                                                        \
-            hipLaunchKernelGGL(kernel, grid_for((a).total_units), dim3(256), 0, s, a);  \
+        const dim3 grid_ = grid_for(b);                                                 \
+        if (grid_.x > 0 && grid_.y > 0)                                                 \
+            hipLaunchKernelGGL(kernel, grid_, dim3(256), 0, s, b);                      \
         return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_DEVICE;               \
     } while (0)
 

@@ -19,8 +19,9 @@ namespace kvc {
 // XF = false leaves the code of stage T out (for launches without a transform): sharing a kernel
 // with it doubles the registers of the plain path for token blocks of 64 and 128 rows.
 template <int BITS, int G, int DT, bool DENSE, bool XF>
-__global__ __launch_bounds__(256) void compress_k_kernel(QuantArgs a)
+__global__ __launch_bounds__(256) void compress_k_kernel(QuantBatch b)
 {
+    const QuantArgs &a = b.item[blockIdx.y];
     __shared__ __attribute__((aligned(16))) float xch_all[4 * kXchFloats];
     UnitPos u;
     if (!unit_pos(a, u)) return;
@@ -45,8 +46,9 @@ __global__ __launch_bounds__(256) void compress_k_kernel(QuantArgs a)
 }
 
 template <int BITS, int DT, bool DENSE>
-__global__ __launch_bounds__(256) void decompress_k_kernel(QuantArgs a)
+__global__ __launch_bounds__(256) void decompress_k_kernel(QuantBatch b)
 {
+    const QuantArgs &a = b.item[blockIdx.y];
     UnitPos u;
     if (!unit_pos(a, u)) return;
     if (*a.status & KVC_DEV_BAD_HEADER) return;
@@ -72,8 +74,9 @@ __global__ __launch_bounds__(256) void decompress_k_kernel(QuantArgs a)
 // ---- V: groups along channels, one set per token -----------------------------------------------
 
 template <int BITS, int GV, int DT, bool DENSE>
-__global__ __launch_bounds__(256) void compress_v_kernel(QuantArgs a)
+__global__ __launch_bounds__(256) void compress_v_kernel(QuantBatch b)
 {
+    const QuantArgs &a = b.item[blockIdx.y];
     UnitPos u;
     if (!unit_pos(a, u)) return;
     constexpr int NG = kDim / GV;
@@ -96,8 +99,9 @@ __global__ __launch_bounds__(256) void compress_v_kernel(QuantArgs a)
 }
 
 template <int BITS, int DT, bool DENSE>
-__global__ __launch_bounds__(256) void decompress_v_kernel(QuantArgs a)
+__global__ __launch_bounds__(256) void decompress_v_kernel(QuantBatch b)
 {
+    const QuantArgs &a = b.item[blockIdx.y];
     UnitPos u;
     if (!unit_pos(a, u)) return;
     if (*a.status & KVC_DEV_BAD_HEADER) return;
@@ -124,54 +128,55 @@ __global__ __launch_bounds__(256) void decompress_v_kernel(QuantArgs a)
 
 // ---- launchers ----------------------------------------------------------------------------------
 
-template <int BITS, int DT, bool DENSE> static int compress_bits_dt(int is_v, int group, const QuantArgs &a, hipStream_t s)
+template <int BITS, int DT, bool DENSE> static int compress_bits_dt(int is_v, int group, const QuantBatch &b, hipStream_t s)
 {
+    const QuantArgs &a = b.item[0];
     if (!is_v) {
         const bool xf = a.rotate || a.anchors;
         switch (group) {
-        case 32: KVC_LAUNCH((compress_k_kernel<BITS, 32, DT, DENSE, true>), a, s);
+        case 32: KVC_LAUNCH((compress_k_kernel<BITS, 32, DT, DENSE, true>), b, s);
         case 64:
-            if (xf) KVC_LAUNCH((compress_k_kernel<BITS, 64, DT, DENSE, true>), a, s);
-            KVC_LAUNCH((compress_k_kernel<BITS, 64, DT, DENSE, false>), a, s);
+            if (xf) KVC_LAUNCH((compress_k_kernel<BITS, 64, DT, DENSE, true>), b, s);
+            KVC_LAUNCH((compress_k_kernel<BITS, 64, DT, DENSE, false>), b, s);
         case 128:
-            if (xf) KVC_LAUNCH((compress_k_kernel<BITS, 128, DT, DENSE, true>), a, s);
-            KVC_LAUNCH((compress_k_kernel<BITS, 128, DT, DENSE, false>), a, s);
+            if (xf) KVC_LAUNCH((compress_k_kernel<BITS, 128, DT, DENSE, true>), b, s);
+            KVC_LAUNCH((compress_k_kernel<BITS, 128, DT, DENSE, false>), b, s);
         }
     } else {
         switch (group) {
-        case 32: KVC_LAUNCH((compress_v_kernel<BITS, 32, DT, DENSE>), a, s);
-        case 64: KVC_LAUNCH((compress_v_kernel<BITS, 64, DT, DENSE>), a, s);
-        case 128: KVC_LAUNCH((compress_v_kernel<BITS, 128, DT, DENSE>), a, s);
+        case 32: KVC_LAUNCH((compress_v_kernel<BITS, 32, DT, DENSE>), b, s);
+        case 64: KVC_LAUNCH((compress_v_kernel<BITS, 64, DT, DENSE>), b, s);
+        case 128: KVC_LAUNCH((compress_v_kernel<BITS, 128, DT, DENSE>), b, s);
         }
     }
     return KVC_ERR_UNSUPPORTED;
 }
 
-template <int BITS, bool DENSE> static int decompress_bits_dense(int is_v, int dtype, const QuantArgs &a, hipStream_t s)
+template <int BITS, bool DENSE> static int decompress_bits_dense(int is_v, int dtype, const QuantBatch &b, hipStream_t s)
 {
     if (!is_v) {
-        if (dtype == DT_F16) KVC_LAUNCH((decompress_k_kernel<BITS, DT_F16, DENSE>), a, s);
-        KVC_LAUNCH((decompress_k_kernel<BITS, DT_BF16, DENSE>), a, s);
+        if (dtype == DT_F16) KVC_LAUNCH((decompress_k_kernel<BITS, DT_F16, DENSE>), b, s);
+        KVC_LAUNCH((decompress_k_kernel<BITS, DT_BF16, DENSE>), b, s);
     }
-    if (dtype == DT_F16) KVC_LAUNCH((decompress_v_kernel<BITS, DT_F16, DENSE>), a, s);
-    KVC_LAUNCH((decompress_v_kernel<BITS, DT_BF16, DENSE>), a, s);
+    if (dtype == DT_F16) KVC_LAUNCH((decompress_v_kernel<BITS, DT_F16, DENSE>), b, s);
+    KVC_LAUNCH((decompress_v_kernel<BITS, DT_BF16, DENSE>), b, s);
 }
 
 #define KVC_PASTE2(a, b) a##b
 #define KVC_PASTE(a, b) KVC_PASTE2(a, b)
 
-int KVC_PASTE(launch_compress_bits, KVC_BITS)(int is_v, int group, int dtype, const QuantArgs &a, hipStream_t s)
+int KVC_PASTE(launch_compress_bits, KVC_BITS)(int is_v, int group, int dtype, const QuantBatch &b, hipStream_t s)
 {
-    if (a.dense)
-        return dtype == DT_F16 ? compress_bits_dt<KVC_BITS, DT_F16, true>(is_v, group, a, s)
-                               : compress_bits_dt<KVC_BITS, DT_BF16, true>(is_v, group, a, s);
-    return dtype == DT_F16 ? compress_bits_dt<KVC_BITS, DT_F16, false>(is_v, group, a, s)
-                           : compress_bits_dt<KVC_BITS, DT_BF16, false>(is_v, group, a, s);
+    if (b.item[0].dense)
+        return dtype == DT_F16 ? compress_bits_dt<KVC_BITS, DT_F16, true>(is_v, group, b, s)
+                               : compress_bits_dt<KVC_BITS, DT_BF16, true>(is_v, group, b, s);
+    return dtype == DT_F16 ? compress_bits_dt<KVC_BITS, DT_F16, false>(is_v, group, b, s)
+                           : compress_bits_dt<KVC_BITS, DT_BF16, false>(is_v, group, b, s);
 }
 
-int KVC_PASTE(launch_decompress_bits, KVC_BITS)(int is_v, int dtype, const QuantArgs &a, hipStream_t s)
+int KVC_PASTE(launch_decompress_bits, KVC_BITS)(int is_v, int dtype, const QuantBatch &b, hipStream_t s)
 {
-    return a.dense ? decompress_bits_dense<KVC_BITS, true>(is_v, dtype, a, s) : decompress_bits_dense<KVC_BITS, false>(is_v, dtype, a, s);
+    return b.item[0].dense ? decompress_bits_dense<KVC_BITS, true>(is_v, dtype, b, s) : decompress_bits_dense<KVC_BITS, false>(is_v, dtype, b, s);
 }
 
 }  // namespace kvc

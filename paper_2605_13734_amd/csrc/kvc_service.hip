@@ -8,8 +8,9 @@ namespace kvc {
 // ---- 16 bits: the tensor travels unchanged ----------------------------------------------------
 
 template <bool TO_PAYLOAD>
-__global__ __launch_bounds__(256) void copy_rows_kernel(QuantArgs a)
+__global__ __launch_bounds__(256) void copy_rows_kernel(QuantBatch batch)
 {
+    const QuantArgs &a = batch.item[blockIdx.y];
     UnitPos u;
     if (!unit_pos(a, u)) return;
     if (!TO_PAYLOAD && (*a.status & KVC_DEV_BAD_HEADER)) return;
@@ -77,27 +78,27 @@ __global__ void fill_u32_kernel(uint32_t *dst, uint32_t value, long long n)
 
 // ---- launchers ----------------------------------------------------------------------------------
 
-int launch_compress_tensor(int is_v, int bits, int group, int dtype, const QuantArgs &a, hipStream_t s)
+int launch_compress_tensor(int is_v, int bits, int group, int dtype, const QuantBatch &b, hipStream_t s)
 {
     switch (bits) {
-    case 2: return launch_compress_bits2(is_v, group, dtype, a, s);
-    case 3: return launch_compress_bits3(is_v, group, dtype, a, s);
-    case 4: return launch_compress_bits4(is_v, group, dtype, a, s);
-    case 8: return launch_compress_bits8(is_v, group, dtype, a, s);
-    case 16: KVC_LAUNCH(copy_rows_kernel<true>, a, s);
+    case 2: return launch_compress_bits2(is_v, group, dtype, b, s);
+    case 3: return launch_compress_bits3(is_v, group, dtype, b, s);
+    case 4: return launch_compress_bits4(is_v, group, dtype, b, s);
+    case 8: return launch_compress_bits8(is_v, group, dtype, b, s);
+    case 16: KVC_LAUNCH(copy_rows_kernel<true>, b, s);
     }
     return KVC_ERR_UNSUPPORTED;
 }
 
-int launch_decompress_tensor(int is_v, int bits, int group, int dtype, const QuantArgs &a, hipStream_t s)
+int launch_decompress_tensor(int is_v, int bits, int group, int dtype, const QuantBatch &b, hipStream_t s)
 {
     (void)group;
     switch (bits) {
-    case 2: return launch_decompress_bits2(is_v, dtype, a, s);
-    case 3: return launch_decompress_bits3(is_v, dtype, a, s);
-    case 4: return launch_decompress_bits4(is_v, dtype, a, s);
-    case 8: return launch_decompress_bits8(is_v, dtype, a, s);
-    case 16: KVC_LAUNCH(copy_rows_kernel<false>, a, s);
+    case 2: return launch_decompress_bits2(is_v, dtype, b, s);
+    case 3: return launch_decompress_bits3(is_v, dtype, b, s);
+    case 4: return launch_decompress_bits4(is_v, dtype, b, s);
+    case 8: return launch_decompress_bits8(is_v, dtype, b, s);
+    case 16: KVC_LAUNCH(copy_rows_kernel<false>, b, s);
     }
     return KVC_ERR_UNSUPPORTED;
 }
