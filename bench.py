@@ -245,6 +245,23 @@ def other_configs(steps):
     del xs, ys, buf, plan
     torch.cuda.empty_cache()
 
+    # many short requests in one call (Llama-3.1-8B shape, 32 requests of 512 to 2048 tokens): the requests
+    # of a call share their launches, so this is not 32 times the latency of a small call
+    L, H = 32, 8
+    lens = kvgen.request_lengths(1, 32, 512, 2048)
+    xs = [kvgen.make_kv(200 + i, L, H, 128, T, torch.float16, dev) for i, T in enumerate(lens)]
+    ys = [torch.empty_like(x) for x in xs]
+    V = sum(x.numel() * 2 for x in xs)
+    for codec in (0, 1):
+        plan = kvc.Plan(kvc.F16, L, H, 128, 4, 4, 32, 32, codec, max_tokens=max(lens), max_batch=len(lens))
+        buf = kvc.Buffers(plan, lens, dev)
+        t_enc, t_dec = time_directions(buf, [kvc.contiguous_request(x) for x in xs], [kvc.contiguous_request(y) for y in ys], steps)
+        out.append(direction_report("llama8b_32_short_requests_fp16_int4g32" + ("_huff8" if codec else ""), V,
+                                    int(buf.out_bytes.sum()), t_enc, t_dec, {"requests": len(lens), "tokens_total": sum(lens)}))
+        del buf, plan
+    del xs, ys
+    torch.cuda.empty_cache()
+
     # paged 128K: Llama-3.1-8B shape, 131072 tokens in pages of 16 tokens through a random block table,
     # compressing from the pages and decompressing into pages under another table
     L, H, T, bt = 32, 8, 131072, 16

@@ -250,8 +250,9 @@ int kvc_check_block_table(const int32_t *table, int64_t entries, int32_t num_phy
  * array, owned by the caller) is installed in a plan, every kvc_compress / kvc_decompress with
  * that plan records, per request and on the call's stream, four events: before the set-up work
  * (for the first request of a call: before anything the call enqueues), before the K pass,
- * between the K and V passes, and after the V pass.  Returns the number of events recorded
- * since the previous call; NULL uninstalls.  The state lives in the plan.
+ * between the K and V passes, and after the V pass (short requests of one call share their launches
+ * and then share these moments).  Returns the number of events recorded since the previous call;
+ * NULL uninstalls.  The state lives in the plan.
  */
 int kvc_trace(kvc_plan_t *plan, void **hip_events, int32_t capacity);
 

@@ -114,16 +114,18 @@ __device__ __forceinline__ void dequant_chunk(const CoderArgs &a, const ChunkPos
 // transform: in one kernel, every path pays for the registers of the most expensive one (the anchors
 // of short runs, the rotation) with its fourth wave per SIMD.
 template <int BITS, int DT, bool IS_V, bool DENSE, int TR>
-__global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel(CoderArgs a)
+__global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel(CoderBatch batch)
 {
     using Geo = ChunkGeom<BITS>;
     using Dec = DecGeom<BITS>;
     constexpr int W = Geo::kWords, NW = Geo::kDecWaves;
+    unsigned wg;
+    const CoderArgs &a = batch.item[batch_item(batch, wg)];
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * Dec::kLds];
     __shared__ uint16_t lut[4096];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id();      // (kept per lane: as a scalar it costs this kernel its fourth wave per SIMD)
-    long long chunk = (long long)blockIdx.x * NW + wave;
+    long long chunk = (long long)wg * NW + wave;
     const bool live = chunk < a.chunks;
     if (!DENSE && live && a.q.head_minor) {
         // destination with the heads of a token next to each other: neighbouring waves take the same
@@ -259,14 +261,21 @@ __global__ __launch_bounds__(ChunkGeom<BITS>::kDecWaves * 64) void decode_kernel
 
 // ---- launchers ----------------------------------------------------------------------------------
 
-template <int BITS, int DT, bool IS_V> static int decode_launch(const CoderArgs &a, hipStream_t s)
+template <int BITS, int DT, bool IS_V> static int decode_launch(const CoderBatch &b, hipStream_t s)
 {
     constexpr int NW = ChunkGeom<BITS>::kDecWaves;
-    const long long need = (a.chunks + NW - 1) / NW;
-    if (need <= 0) return KVC_OK;
-    const dim3 grid((unsigned)need), block(NW * 64);
+    const CoderArgs &a = b.item[0];
+    CoderBatch placed = b;
+    unsigned need = 0;
+    for (int i = 0; i < b.n; ++i) {
+        placed.start[i] = need;
+        need += (unsigned)((b.item[i].chunks + NW - 1) / NW);
+    }
+    placed.start[b.n] = need;
+    if (need == 0) return KVC_OK;
+    const dim3 grid(need), block(NW * 64);
     const int tr = a.q.rotate ? 1 : !a.q.anchors ? 0 : a.q.anchor_shift >= 5 ? 2 : 3;
-#define KVC_DECODE(D, T) hipLaunchKernelGGL((decode_kernel<BITS, DT, IS_V, D, T>), grid, block, 0, s, a)
+#define KVC_DECODE(D, T) hipLaunchKernelGGL((decode_kernel<BITS, DT, IS_V, D, T>), grid, block, 0, s, placed)
     if (a.q.dense) {
         if (tr == 0) KVC_DECODE(true, 0); else if (tr == 1) KVC_DECODE(true, 1); else if (tr == 2) KVC_DECODE(true, 2); else KVC_DECODE(true, 3);
     } else {
@@ -279,9 +288,9 @@ template <int BITS, int DT, bool IS_V> static int decode_launch(const CoderArgs 
 #define KVC_PASTE2(a, b) a##b
 #define KVC_PASTE(a, b) KVC_PASTE2(a, b)
 
-int KVC_PASTE(launch_decode_bits, KVC_BITS)(int dtype, const CoderArgs &a, hipStream_t s)
+int KVC_PASTE(launch_decode_bits, KVC_BITS)(int dtype, const CoderBatch &a, hipStream_t s)
 {
-    if (a.is_v) return dtype == DT_F16 ? decode_launch<KVC_BITS, DT_F16, true>(a, s) : decode_launch<KVC_BITS, DT_BF16, true>(a, s);
+    if (a.item[0].is_v) return dtype == DT_F16 ? decode_launch<KVC_BITS, DT_F16, true>(a, s) : decode_launch<KVC_BITS, DT_BF16, true>(a, s);
     return dtype == DT_F16 ? decode_launch<KVC_BITS, DT_F16, false>(a, s) : decode_launch<KVC_BITS, DT_BF16, false>(a, s);
 }
 

@@ -112,10 +112,13 @@ template <int BITS, int G, int DT, bool IS_V, bool DENSE, bool XF> constexpr int
 template <int BITS, int G, int DT, bool IS_V, bool DENSE, bool XF>
 __global__ __launch_bounds__(enc_waves(BITS, G, DT, DENSE, IS_V, XF) * 64)
 __attribute__((amdgpu_waves_per_eu(enc_min_waves<BITS, G, DT, IS_V, DENSE, XF>())))
-void encode_kernel(CoderArgs a)
+void encode_kernel(CoderBatch batch)
 {
     using Geo = ChunkGeom<BITS>;
     constexpr int W = Geo::kWords, NW = enc_waves(BITS, G, DT, DENSE, IS_V, XF);
+    unsigned wg;
+    const CoderArgs &a = batch.item[batch_item(batch, wg)];      // (which of them it is among the item's workgroups does not matter: the chunk comes from the ticket)
+    (void)wg;
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * Geo::kLds];
     __shared__ EncTables enc;
     __shared__ uint32_t s_units[NW];
@@ -279,25 +282,33 @@ void encode_kernel(CoderArgs a)
 
 // ---- launchers ----------------------------------------------------------------------------------
 
-template <int BITS, int G, int DT, bool IS_V> static int encode_launch(const CoderArgs &a, hipStream_t s)
+template <int BITS, int G, int DT, bool IS_V> static int encode_launch(const CoderBatch &b, hipStream_t s)
 {
+    const CoderArgs &a = b.item[0];
     const int NW = enc_waves(BITS, G, DT, a.q.dense != 0, IS_V, a.q.rotate || a.q.anchors != nullptr);
-    const long long need = (a.chunks + NW - 1) / NW;
-    if (need <= 0) return KVC_OK;
+    CoderBatch placed = b;
+    unsigned need = 0;
+    for (int i = 0; i < b.n; ++i) {
+        placed.start[i] = need;
+        need += (unsigned)((b.item[i].chunks + NW - 1) / NW);
+    }
+    placed.start[b.n] = need;
+    if (need == 0) return KVC_OK;
+    const dim3 grid(need), block(NW * 64);
     // K token blocks of 64 and 128 rows, and V groups of 32 channels (the variant that is short of
     // registers), have a kernel of their own for launches without a transform
     constexpr bool kSplit = IS_V ? G == 32 : G >= 64;
     if (kSplit && !a.q.rotate && !a.q.anchors) {
-        if (a.q.dense) hipLaunchKernelGGL((encode_kernel<BITS, G, DT, IS_V, true, !kSplit>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
-        else hipLaunchKernelGGL((encode_kernel<BITS, G, DT, IS_V, false, !kSplit>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
+        if (a.q.dense) hipLaunchKernelGGL((encode_kernel<BITS, G, DT, IS_V, true, !kSplit>), grid, block, 0, s, placed);
+        else hipLaunchKernelGGL((encode_kernel<BITS, G, DT, IS_V, false, !kSplit>), grid, block, 0, s, placed);
         return launched();
     }
-    if (a.q.dense) hipLaunchKernelGGL((encode_kernel<BITS, G, DT, IS_V, true, true>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
-    else hipLaunchKernelGGL((encode_kernel<BITS, G, DT, IS_V, false, true>), dim3((unsigned)need), dim3(NW * 64), 0, s, a);
+    if (a.q.dense) hipLaunchKernelGGL((encode_kernel<BITS, G, DT, IS_V, true, true>), grid, block, 0, s, placed);
+    else hipLaunchKernelGGL((encode_kernel<BITS, G, DT, IS_V, false, true>), grid, block, 0, s, placed);
     return launched();
 }
 
-template <int DT, bool ISV> static int encode_g(int group, const CoderArgs &a, hipStream_t s)
+template <int DT, bool ISV> static int encode_g(int group, const CoderBatch &a, hipStream_t s)
 {
     switch (group) {
     case 32: return encode_launch<KVC_BITS, 32, DT, ISV>(a, s);
@@ -310,9 +321,9 @@ template <int DT, bool ISV> static int encode_g(int group, const CoderArgs &a, h
 #define KVC_PASTE2(a, b) a##b
 #define KVC_PASTE(a, b) KVC_PASTE2(a, b)
 
-int KVC_PASTE(launch_encode_bits, KVC_BITS)(int group, int dtype, const CoderArgs &a, hipStream_t s)
+int KVC_PASTE(launch_encode_bits, KVC_BITS)(int group, int dtype, const CoderBatch &a, hipStream_t s)
 {
-    if (a.is_v) return dtype == DT_F16 ? encode_g<DT_F16, true>(group, a, s) : encode_g<DT_BF16, true>(group, a, s);
+    if (a.item[0].is_v) return dtype == DT_F16 ? encode_g<DT_F16, true>(group, a, s) : encode_g<DT_BF16, true>(group, a, s);
     return dtype == DT_F16 ? encode_g<DT_F16, false>(group, a, s) : encode_g<DT_BF16, false>(group, a, s);
 }
 

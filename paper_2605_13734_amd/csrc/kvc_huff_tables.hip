@@ -10,8 +10,10 @@ namespace kvc {
 // grid = 16 sample chunks x the units of a chunk, one wave each: the wave quantizes its unit (one
 // load round trip) and counts the byte values of the packed rows.
 template <int BITS, int G, int DT, bool IS_V>
-__global__ __launch_bounds__(64) void hist_kernel(CoderArgs a)
+__global__ __launch_bounds__(64) void hist_kernel(CoderBatch batch)
 {
+    const CoderArgs &a = batch.item[blockIdx.y];
+    if (a.chunks <= 0) return;
     using Unit = UnitGeom<BITS, G, DT, IS_V>;
     constexpr int RW = 4 * BITS;                         // words of a packed row
     // (a whole chunk's region: the K group parameters travel through the padding of all 64 sub-blocks)
@@ -126,8 +128,9 @@ constexpr int kTableWaves = 8;      // waves that fill a decode table
 // grid = kCandidates workgroups of 256 threads (one symbol each) per table slot of the format.
 // A candidate leaves its lengths in the slot's decode-table space of the workspace (unused while
 // compressing); the last one to finish picks and writes the table.
-__global__ __launch_bounds__(256) void build_tables_kernel(CoderArgs a)
+__global__ __launch_bounds__(256) void build_tables_kernel(CoderBatch batch)
 {
+    const CoderArgs &a = batch.item[blockIdx.y];
     const int sec = blockIdx.x / kCandidates, k = blockIdx.x - sec * kCandidates;
     const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
     if (!((a.slot_mask >> sec) & 1)) {                 // a width the tensor does not use: an empty table
@@ -191,8 +194,9 @@ __global__ __launch_bounds__(256) void build_tables_kernel(CoderArgs a)
 }
 
 // grid = one workgroup of kTableWaves waves per table slot: decode tables from the lengths stored in the payload
-__global__ __launch_bounds__(kTableWaves * 64) void decode_prepare_kernel(CoderArgs a)
+__global__ __launch_bounds__(kTableWaves * 64) void decode_prepare_kernel(CoderBatch batch)
 {
+    const CoderArgs &a = batch.item[blockIdx.y];
     if (!((a.slot_mask >> blockIdx.x) & 1)) return;
     __shared__ BuildLds s;
     __shared__ uint32_t block_count[4][16];            // symbols of each length in each block of 64 symbols
@@ -257,14 +261,16 @@ __global__ __launch_bounds__(kTableWaves * 64) void decode_prepare_kernel(CoderA
 
 // ---- launchers ----------------------------------------------------------------------------------
 
-template <int BITS, int G, int DT, bool IS_V> static int hist_launch(const CoderArgs &a, hipStream_t s)
+template <int BITS, int G, int DT, bool IS_V> static int hist_launch(const CoderBatch &b, hipStream_t s)
 {
-    if (a.chunks <= 0) return KVC_OK;
-    hipLaunchKernelGGL((hist_kernel<BITS, G, DT, IS_V>), dim3(16 * UnitGeom<BITS, G, DT, IS_V>::kUnits), dim3(64), 0, s, a);
+    bool any = false;
+    for (int i = 0; i < b.n; ++i) any |= b.item[i].chunks > 0;
+    if (!any) return KVC_OK;
+    hipLaunchKernelGGL((hist_kernel<BITS, G, DT, IS_V>), dim3(16 * UnitGeom<BITS, G, DT, IS_V>::kUnits, (unsigned)b.n), dim3(64), 0, s, b);
     return launched();
 }
 
-template <int BITS, int DT, bool ISV> static int hist_g(int group, const CoderArgs &a, hipStream_t s)
+template <int BITS, int DT, bool ISV> static int hist_g(int group, const CoderBatch &a, hipStream_t s)
 {
     switch (group) {
     case 32: return hist_launch<BITS, 32, DT, ISV>(a, s);
@@ -274,12 +280,12 @@ template <int BITS, int DT, bool ISV> static int hist_g(int group, const CoderAr
     return KVC_ERR_UNSUPPORTED;
 }
 
-template <int BITS, bool ISV> static int hist_d(int group, int dtype, const CoderArgs &a, hipStream_t s)
+template <int BITS, bool ISV> static int hist_d(int group, int dtype, const CoderBatch &a, hipStream_t s)
 {
     return dtype == DT_F16 ? hist_g<BITS, DT_F16, ISV>(group, a, s) : hist_g<BITS, DT_BF16, ISV>(group, a, s);
 }
 
-template <bool ISV> static int hist_b(int bits, int group, int dtype, const CoderArgs &a, hipStream_t s)
+template <bool ISV> static int hist_b(int bits, int group, int dtype, const CoderBatch &a, hipStream_t s)
 {
     switch (bits) {
     case 2: return hist_d<2, ISV>(group, dtype, a, s);
@@ -290,24 +296,24 @@ template <bool ISV> static int hist_b(int bits, int group, int dtype, const Code
     return KVC_ERR_UNSUPPORTED;
 }
 
-int launch_table_sample(int bits, int group, int dtype, const CoderArgs &a, hipStream_t s)
+int launch_table_sample(int bits, int group, int dtype, const CoderBatch &b, hipStream_t s)
 {
-    return a.is_v ? hist_b<true>(bits, group, dtype, a, s) : hist_b<false>(bits, group, dtype, a, s);
+    return b.item[0].is_v ? hist_b<true>(bits, group, dtype, b, s) : hist_b<false>(bits, group, dtype, b, s);
 }
 
-int launch_build_tables(const CoderArgs &any, hipStream_t s)
+int launch_build_tables(const CoderBatch &b, hipStream_t s)
 {
-    hipLaunchKernelGGL(build_tables_kernel, dim3(any.slots * kCandidates), dim3(256), 0, s, any);
+    hipLaunchKernelGGL(build_tables_kernel, dim3(b.item[0].slots * kCandidates, (unsigned)b.n), dim3(256), 0, s, b);
     return launched();
 }
 
-int launch_decode_prepare(const CoderArgs &k, hipStream_t s)
+int launch_decode_prepare(const CoderBatch &b, hipStream_t s)
 {
-    hipLaunchKernelGGL(decode_prepare_kernel, dim3(k.slots), dim3(kTableWaves * 64), 0, s, k);
+    hipLaunchKernelGGL(decode_prepare_kernel, dim3(b.item[0].slots, (unsigned)b.n), dim3(kTableWaves * 64), 0, s, b);
     return launched();
 }
 
-int launch_encode_section(int bits, int group, int dtype, const CoderArgs &a, hipStream_t s)
+int launch_encode_section(int bits, int group, int dtype, const CoderBatch &a, hipStream_t s)
 {
     switch (bits) {
     case 2: return launch_encode_bits2(group, dtype, a, s);
@@ -318,7 +324,7 @@ int launch_encode_section(int bits, int group, int dtype, const CoderArgs &a, hi
     return KVC_ERR_UNSUPPORTED;
 }
 
-int launch_decode_section(int bits, int group, int dtype, const CoderArgs &a, hipStream_t s)
+int launch_decode_section(int bits, int group, int dtype, const CoderBatch &a, hipStream_t s)
 {
     (void)group;
     switch (bits) {

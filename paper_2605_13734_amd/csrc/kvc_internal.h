@@ -34,13 +34,24 @@ struct QuantArgs {
     int *status;                // device status word of the request
 };
 
-// The same tensor (K or V) of several requests of a call in one launch: blockIdx.y picks the request.
+// The same tensor (K or V) of several requests of a call in one launch, their workgroups one request
+// after the other.
 // All items take the same kernel (same plan; same layout class, see QuantArgs::dense).
 constexpr int kQuantBatch = 12;     // (the argument block stays below 4 KB)
 struct QuantBatch {
     QuantArgs item[kQuantBatch];
+    unsigned start[kQuantBatch + 1];    // first workgroup of every item in the launch (set by the launcher)
     int n;
 };
+
+// The item a workgroup belongs to, and its number among the item's workgroups (the same in all lanes).
+template <class Batch> __device__ __forceinline__ int batch_item(const Batch &b, unsigned &wg)
+{
+    int i = 0;
+    while (i + 1 < b.n && blockIdx.x >= b.start[i + 1]) ++i;
+    wg = blockIdx.x - b.start[i];
+    return i;
+}
 
 // Geometry of one payload (all byte counts), shared by host code of compress / decompress.
 struct Geometry {
@@ -151,15 +162,27 @@ struct CoderArgs {
     unsigned long long *out_bytes;   // device: true payload size (written by the last workgroup)
 };
 
-int launch_table_sample(int bits, int group, int dtype, const CoderArgs &a, hipStream_t s);
-int launch_build_tables(const CoderArgs &any, hipStream_t s);
-int launch_encode_section(int bits, int group, int dtype, const CoderArgs &a, hipStream_t s);
-int launch_decode_prepare(const CoderArgs &k, hipStream_t s);
-int launch_decode_section(int bits, int group, int dtype, const CoderArgs &a, hipStream_t s);
+// One launch of the coder for several requests of a call (the table kernels: blockIdx.y picks the
+// request; encoder and decoder: the requests' workgroups one after the other).  All items are
+// the same launch of their request (same tensor, width and kernel variant; see request_window).
+constexpr int kCoderBatch = 8;      // (the argument block stays below 4 KB)
+struct CoderBatch {
+    CoderArgs item[kCoderBatch];
+    unsigned start[kCoderBatch + 1];    // encoder and decoder: first workgroup of every item (set by the launcher)
+    int n;
+};
+static_assert(sizeof(CoderBatch) <= 4000, "kernel arguments are limited to 4 KB");
+static_assert(sizeof(QuantBatch) <= 4000, "kernel arguments are limited to 4 KB");
+
+int launch_table_sample(int bits, int group, int dtype, const CoderBatch &b, hipStream_t s);
+int launch_build_tables(const CoderBatch &b, hipStream_t s);
+int launch_encode_section(int bits, int group, int dtype, const CoderBatch &b, hipStream_t s);
+int launch_decode_prepare(const CoderBatch &b, hipStream_t s);
+int launch_decode_section(int bits, int group, int dtype, const CoderBatch &b, hipStream_t s);
 // one translation unit per code width (kvc_huff_enc.hip / kvc_huff_dec.hip compiled with -DKVC_BITS=...)
 #define KVC_DECLARE_CODER(B)                                                                  \
-    int launch_encode_bits##B(int group, int dtype, const CoderArgs &a, hipStream_t s);       \
-    int launch_decode_bits##B(int dtype, const CoderArgs &a, hipStream_t s);
+    int launch_encode_bits##B(int group, int dtype, const CoderBatch &b, hipStream_t s);      \
+    int launch_decode_bits##B(int dtype, const CoderBatch &b, hipStream_t s);
 KVC_DECLARE_CODER(2) KVC_DECLARE_CODER(3) KVC_DECLARE_CODER(4) KVC_DECLARE_CODER(8)
 #undef KVC_DECLARE_CODER
 

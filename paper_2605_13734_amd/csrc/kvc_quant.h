@@ -14,9 +14,9 @@ struct UnitPos {
     long long head_off;  // element offset of x[l][h][0][0]
 };
 
-__device__ __forceinline__ bool unit_pos(const QuantArgs &a, UnitPos &u)
+__device__ __forceinline__ bool unit_pos(const QuantArgs &a, unsigned wg, UnitPos &u)
 {
-    long long unit = (long long)blockIdx.x * 4 + wave_id();
+    long long unit = (long long)wg * 4 + wave_id();
     if (unit >= a.total_units) return false;
     if (a.head_minor) {
         // unit = (layer * units_per_head + block) * heads + head: the four waves of a workgroup read or
@@ -47,19 +47,23 @@ __device__ __forceinline__ void report(int *status, bool bad)
     if (bad) atomicOr(status, KVC_DEV_BAD_BLOCK);
 }
 
-// grid: x = workgroups of four units for the largest item, y = items
-static inline dim3 grid_for(const QuantBatch &b)
+// workgroups of four units, item after item
+static inline unsigned place_items(QuantBatch &b)
 {
-    long long most = 0;
-    for (int i = 0; i < b.n; ++i) most = b.item[i].total_units > most ? b.item[i].total_units : most;
-    return dim3((unsigned)((most + 3) / 4), (unsigned)b.n);
+    unsigned at = 0;
+    for (int i = 0; i < b.n; ++i) {
+        b.start[i] = at;
+        at += (unsigned)((b.item[i].total_units + 3) / 4);
+    }
+    b.start[b.n] = at;
+    return at;
 }
 
-#define KVC_LAUNCH(kernel, b, s)                                                        \
+#define KVC_LAUNCH(kernel, batch, s)                                                    \
     do {                                                                                \
-        const dim3 grid_ = grid_for(b);                                                 \
-        if (grid_.x > 0 && grid_.y > 0)                                                 \
-            hipLaunchKernelGGL(kernel, grid_, dim3(256), 0, s, b);                      \
+        QuantBatch placed_ = batch;                                                     \
+        const unsigned wgs_ = place_items(placed_);                                     \
+        if (wgs_ > 0) hipLaunchKernelGGL(kernel, dim3(wgs_), dim3(256), 0, s, placed_); \
         return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_DEVICE;               \
     } while (0)
 

@@ -21,10 +21,11 @@ namespace kvc {
 template <int BITS, int G, int DT, bool DENSE, bool XF>
 __global__ __launch_bounds__(256) void compress_k_kernel(QuantBatch b)
 {
-    const QuantArgs &a = b.item[blockIdx.y];
+    unsigned wg;
+    const QuantArgs &a = b.item[batch_item(b, wg)];
     __shared__ __attribute__((aligned(16))) float xch_all[4 * kXchFloats];
     UnitPos u;
-    if (!unit_pos(a, u)) return;
+    if (!unit_pos(a, wg, u)) return;
     constexpr int P = G / kPassRows;
     const long long row0 = u.blk * G;
     bool bad = false;
@@ -48,9 +49,10 @@ __global__ __launch_bounds__(256) void compress_k_kernel(QuantBatch b)
 template <int BITS, int DT, bool DENSE>
 __global__ __launch_bounds__(256) void decompress_k_kernel(QuantBatch b)
 {
-    const QuantArgs &a = b.item[blockIdx.y];
+    unsigned wg;
+    const QuantArgs &a = b.item[batch_item(b, wg)];
     UnitPos u;
-    if (!unit_pos(a, u)) return;
+    if (!unit_pos(a, wg, u)) return;
     if (*a.status & KVC_DEV_BAD_HEADER) return;
     const int col = lane_id() & 15;
     const long long row0 = u.blk * kPassRows;
@@ -76,9 +78,10 @@ __global__ __launch_bounds__(256) void decompress_k_kernel(QuantBatch b)
 template <int BITS, int GV, int DT, bool DENSE>
 __global__ __launch_bounds__(256) void compress_v_kernel(QuantBatch b)
 {
-    const QuantArgs &a = b.item[blockIdx.y];
+    unsigned wg;
+    const QuantArgs &a = b.item[batch_item(b, wg)];
     UnitPos u;
-    if (!unit_pos(a, u)) return;
+    if (!unit_pos(a, wg, u)) return;
     constexpr int NG = kDim / GV;
     const long long row0 = u.blk * kPassRows;
     bool bad = false;
@@ -101,9 +104,10 @@ __global__ __launch_bounds__(256) void compress_v_kernel(QuantBatch b)
 template <int BITS, int DT, bool DENSE>
 __global__ __launch_bounds__(256) void decompress_v_kernel(QuantBatch b)
 {
-    const QuantArgs &a = b.item[blockIdx.y];
+    unsigned wg;
+    const QuantArgs &a = b.item[batch_item(b, wg)];
     UnitPos u;
-    if (!unit_pos(a, u)) return;
+    if (!unit_pos(a, wg, u)) return;
     if (*a.status & KVC_DEV_BAD_HEADER) return;
     const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
     const long long row0 = u.blk * kPassRows;

@@ -10,9 +10,10 @@ namespace kvc {
 template <bool TO_PAYLOAD>
 __global__ __launch_bounds__(256) void copy_rows_kernel(QuantBatch batch)
 {
-    const QuantArgs &a = batch.item[blockIdx.y];
+    unsigned wg;
+    const QuantArgs &a = batch.item[batch_item(batch, wg)];
     UnitPos u;
-    if (!unit_pos(a, u)) return;
+    if (!unit_pos(a, wg, u)) return;
     if (!TO_PAYLOAD && (*a.status & KVC_DEV_BAD_HEADER)) return;
     const int lane = lane_id(), col = lane & 15, rsub = lane >> 4;
     const long long row0 = u.blk * kPassRows;

@@ -350,6 +350,56 @@ def test_codec_paged_and_batch(ref):
         assert ulp_distance_16(kvgen.as_u16(kvgen.from_paged(outs[i].cpu(), tabs[i], T)), ru).max() == 0
 
 
+@pytest.mark.parametrize("codec,transform", [(0, 0), (1, 0), (1, 2), (0, 1)])
+def test_many_requests_share_launches(ref, codec, transform):
+    """Short requests of a call share their launches (up to 12 without the coder, 8 with it, one layout
+    class per launch).  Fourteen requests -- the first one empty, lengths from 1 to several chunks, a
+    run of paged ones in the middle -- each give the payload the oracle makes for that request alone,
+    and come back bit for bit."""
+    L, H, bt, P = 2, 3, 16, 48
+    lens = [0, 300, 1, 129, 517, 64, 0, 700, 33, 256, 130, 5, 411, 128]
+    paged = [False] * 4 + [True] * 5 + [False] * 5
+    period = 32 if transform == 2 else 0
+    cfg = ref.config(dtype=1, layers=L, heads=H, bits_k=4, bits_v=3, group_k=32, group_v=64, codec=codec,
+                     transform=transform, anchor_period=period)
+    plan = kvc.Plan(1, L, H, 128, 4, 3, 32, 64, codec, max_tokens=max(lens), max_batch=len(lens), transform=transform,
+                    anchor_period=period)
+    xs = [kvgen.make_kv(300 + i, L, H, 128, max(T, 1), torch.float16) for i, T in enumerate(lens)]
+    tabs = [kvgen.block_table(9 + i, -(-max(T, 1) // bt), P) for i, T in enumerate(lens)]
+    src, dst, outs = [], [], []
+    keep = []
+    for i, T in enumerate(lens):
+        if paged[i]:
+            pool, tab = kvgen.to_paged(xs[i], tabs[i], bt, P).cuda(), tabs[i].cuda()
+            out = torch.zeros_like(pool)
+            src.append(kvc.paged_request(pool, tab, T))
+            dst.append(kvc.paged_request(out, tab, T))
+            keep += [pool, tab]
+        else:
+            xd = xs[i].cuda()
+            out = torch.zeros_like(xd)
+            src.append(kvc.contiguous_request(xd, T))
+            dst.append(kvc.contiguous_request(out, T))
+            keep.append(xd)
+        outs.append(out)
+    buf = gpu_compress(plan, src, lens)
+    buf.decompress(dst, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    for i, T in enumerate(lens):
+        xu = kvgen.as_u16(xs[i])
+        lay = ref.contiguous_layout(H, max(T, 1), 128)
+        want = ref.compress(cfg, xu[0, 0], xu[0, 1], lay, T)
+        assert int(buf.status[i]) == 0, i
+        got = buf.payload_of(i)
+        assert np.array_equal(got, want), (i, first_diff(got, want))
+        if T == 0:
+            continue
+        ru = np.zeros_like(xu)
+        assert ref.decompress(want, ru[0, 0], ru[0, 1], lay, cfg) == 0
+        y = kvgen.from_paged(outs[i].cpu(), tabs[i], T) if paged[i] else outs[i].cpu()[:, :, :, :T]
+        assert np.array_equal(kvgen.as_u16(y.contiguous()), ru[:, :, :, :T]), i
+
+
 def test_codec_corrupt_payload_is_reported(ref):
     """A damaged directory or table sets a status bit; nothing faults and nothing hangs."""
     T = 512
