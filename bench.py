@@ -480,7 +480,7 @@ def main():
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get(args.workload, {}).get(dom)
 
-    # the practical ceiling: the same bytes in the same access shape with no arithmetic (both directions)
+    # the reference rate: the same bytes in the same access shape with no arithmetic (both directions)
     rows = L * H * T
     per_row = -(-(alg["k"] - 2 * n_half) // rows)                   # payload-side bytes per token row
     row_bytes = max(16, min(256, (per_row + 15) // 16 * 16))

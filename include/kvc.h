@@ -258,7 +258,7 @@ int kvc_trace(kvc_plan_t *plan, void **hip_events, int32_t capacity);
 
 /*
  * Measurement aid, for benchmarks only: moves bytes in the access shape of a tensor pass with no
- * arithmetic, so that a benchmark can put the memory system's practical ceiling for this pattern
+ * arithmetic, so that a benchmark can put what the memory system gives to this pattern
  * beside the published HBM peak (the path is bound by HBM bandwidth: every element is read once
  * and written once in the other form, sections 3.1 and 5.1 give the two directions).
  *   mode 0  the compress direction: one wave per 128 token rows reads 128 x 256 bytes from `src`
