@@ -50,12 +50,17 @@ __global__ __launch_bounds__(64) void hist_kernel(CoderBatch batch)
 // weight order) the other; the heads of the two queues are the two candidates.  The joining
 // itself is sequential (lane 0).  Weights stay far below 2^32 (a table sample is at most 16
 // chunks of 16 KB).
+constexpr int kQueue = 260;
+
 struct BuildLds {
     uint32_t w[256];               // leaf weights by symbol
-    uint32_t sw[258];              // leaf weights in queue order, then two sentinels
-    uint32_t wi[256];              // weights of the joined nodes, in order of creation
-    uint16_t parent_leaf[256];     // by queue position: index of the joined node above the leaf
-    uint16_t parent_int[256];      // by joined node: index of the joined node above it
+    // The two queues of the join and, at one and the same distance behind each (kQueue words), the
+    // parents of their entries: the join walks both queues with one byte offset each and reaches
+    // weight and parent through constant displacements.
+    uint32_t sw[kQueue];           // leaf weights in queue order, then two sentinels
+    uint32_t parent_leaf[kQueue];  // by queue position: index of the joined node above the leaf
+    uint32_t wi[kQueue];           // weights of the joined nodes, in order of creation
+    uint32_t parent_int[kQueue];   // by joined node: index of the joined node above it
     uint8_t len[256];
     uint32_t count[16], first[16], start[16];
     uint16_t by_len[256];          // symbols by (length, symbol)
@@ -85,27 +90,30 @@ __device__ __forceinline__ void build_once(BuildLds &s)
     if (tid == 0) {
         // Every join reads the two front entries of both queues in one go (one LDS round trip) and
         // decides in registers; the entries it writes are read by later joins only.
-        int lq = 0, jq = 0;
-        for (int made = 0; made < 255; ++made) {
-            const uint32_t a0 = s.sw[lq], a1 = s.sw[lq + 1], b0 = s.wi[jq], b1 = s.wi[jq + 1];
+        uint8_t *base = (uint8_t *)&s;
+        uint32_t lo = (uint32_t)__builtin_offsetof(BuildLds, sw), jo = (uint32_t)__builtin_offsetof(BuildLds, wi);
+        constexpr uint32_t kParent = kQueue * 4;       // from a queue entry to its parent word
+        for (uint32_t made = 0; made < 255; ++made) {
+            const uint32_t a0 = *(const uint32_t *)(base + lo), a1 = *(const uint32_t *)(base + lo + 4);
+            const uint32_t b0 = *(const uint32_t *)(base + jo), b1 = *(const uint32_t *)(base + jo + 4);
             const bool first_leaf = a0 <= b0;      // a leaf wins a tie: its id is lower
             const uint32_t la = first_leaf ? a1 : a0, jb = first_leaf ? b0 : b1;     // the fronts after the first pick
             const bool second_leaf = la <= jb;
             const uint32_t sum = (first_leaf ? a0 : b0) + (second_leaf ? la : jb);
-            uint16_t *p0 = first_leaf ? &s.parent_leaf[lq] : &s.parent_int[jq];
-            lq += first_leaf ? 1 : 0;
-            jq += first_leaf ? 0 : 1;
-            uint16_t *p1 = second_leaf ? &s.parent_leaf[lq] : &s.parent_int[jq];
-            lq += second_leaf ? 1 : 0;
-            jq += second_leaf ? 0 : 1;
-            *p0 = (uint16_t)made;
-            *p1 = (uint16_t)made;
+            const uint32_t p0 = first_leaf ? lo : jo;
+            lo += first_leaf ? 4 : 0;
+            jo += first_leaf ? 0 : 4;
+            const uint32_t p1 = second_leaf ? lo : jo;
+            lo += second_leaf ? 4 : 0;
+            jo += second_leaf ? 0 : 4;
+            *(uint32_t *)(base + p0 + kParent) = made;
+            *(uint32_t *)(base + p1 + kParent) = made;
             s.wi[made] = sum;
         }
     }
     __syncthreads();
     int d = 1;
-    for (int i = s.parent_leaf[pos]; i != 254 && d < 256; i = s.parent_int[i]) ++d;
+    for (uint32_t i = s.parent_leaf[pos]; i != 254 && d < 256; i = s.parent_int[i]) ++d;
     s.len[tid] = (uint8_t)d;
     atomicMax(&s.longest, d);
     __syncthreads();
